@@ -1,0 +1,201 @@
+/*
+ * libttkv -- tiered decode attention for gfx950 (MI355X), C ABI.
+ *
+ * The data-parallel hot path of TTKV ("Temporal-Tiered KV Cache"): block-wise
+ * streaming decode attention over a KV cache split into temporal tiers.  Tier 0
+ * holds the most recent tokens in fp16/bf16 in HBM (Sec. 4.1, fast tier); older
+ * tiers hold low-bit codes with per-group fp16 scale/zero (Sec. 4.2,
+ * differential quantization) in HBM or in pinned host DRAM, organised in blocks
+ * of B_blk tokens (Sec. 4.1, block-wise organisation) that are fetched,
+ * decompressed in registers and attended block by block while later blocks are
+ * still in flight (Sec. 4.3, Alg. 1).
+ *
+ * Conventions
+ *   - Every pointer is tagged [host], [pinned] (page-locked host) or [device].
+ *   - All memory is allocated and owned by the caller.  The library never
+ *     allocates or frees device memory and never synchronises the device,
+ *     except where a call says it blocks.
+ *   - Streams are passed as void* holding a hipStream_t (NULL = default stream).
+ *   - Every call validates its arguments on the host and returns a status
+ *     before enqueuing anything; on error nothing was enqueued and no tier
+ *     state changed.  There are no exceptions and no aborts.
+ *   - head_dim is fixed to 128.  batch <= TTKV_MAX_BATCH.
+ *
+ * Block record (the unit of storage, eviction and DMA; Sec. 4.1 "blocks B_j")
+ *   A tier's `data` is a pool of `pool_blocks` records of ttkv_record_bytes()
+ *   bytes.  One record holds block_tokens tokens of every KV head:
+ *     record = [n_kv_heads] x head part
+ *     head part = K codes [block_tokens][kc] | K meta [block_tokens][km]
+ *               | V codes [block_tokens][vc] | V meta [block_tokens][vm]
+ *   per token-head:  F16/BF16: codes = 128 x 2 B, no meta
+ *                    I8_SYM_G32: codes = 128 x int8, meta = 4 x fp16 scale
+ *                    I4_ASYM_G64: codes = 64 B (element 2i low nibble, 2i+1 high
+ *                                 nibble of byte i), meta = fp16 {s0, z0, s1, z1}
+ *   Sequence b's token with lifetime ordinal o (o = start[b] + i for its i-th
+ *   live token) sits in ring block r = (o / block_tokens) % ring_blocks at row
+ *   o % block_tokens of record  block_table ? block_table[b*ring_blocks + r]
+ *                                           : b*ring_blocks + r.
+ *   o / block_tokens is the block id of Eq. (1).
+ */
+#ifndef TTKV_H
+#define TTKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TTKV_MAX_TIERS 4
+#define TTKV_MAX_BATCH 64
+#define TTKV_HEAD_DIM 128
+#define TTKV_MAX_SLOTS 8
+
+typedef enum {
+  TTKV_OK = 0,
+  TTKV_ERR_INVALID_ARG = 1, /* NULL / out-of-range / inconsistent argument */
+  TTKV_ERR_CAPACITY = 2,    /* a tier ring would overflow, or too few tokens to evict */
+  TTKV_ERR_UNSUPPORTED = 3, /* head_dim != 128, format combination without a kernel */
+  TTKV_ERR_WORKSPACE = 4,   /* workspace smaller than ttkv_workspace_bytes() */
+  TTKV_ERR_HIP = 5          /* a HIP launch / copy / event call failed; code in ttkv_stats */
+} ttkv_status;
+
+typedef enum {
+  TTKV_F16 = 0,
+  TTKV_BF16 = 1,
+  TTKV_I8_SYM_G32 = 2,  /* Q_8bit: symmetric int8, group 32 along head_dim, fp16 scale */
+  TTKV_I4_ASYM_G64 = 3, /* Q_4bit: asymmetric int4, group 64, fp16 scale + zero */
+  TTKV_F32 = 4          /* source format of ttkv_quantize_append only */
+} ttkv_fmt;
+
+typedef enum { TTKV_MEM_DEVICE = 0, TTKV_MEM_HOST_PINNED = 1 } ttkv_mem;
+
+/* One temporal tier.  Tier 0 is the newest (the paper's fast tier). */
+typedef struct ttkv_tier {
+  int32_t k_fmt, v_fmt;      /* ttkv_fmt of keys / values (set separately: K 8-bit + V 4-bit is Sec. 4.2's choice) */
+  int32_t mem;               /* ttkv_mem: where `data` lives */
+  int32_t block_tokens;      /* B_blk: tokens per record; multiple of 64 */
+  int64_t capacity_tokens;   /* eviction threshold per sequence (L_fast for tier 0): a tier is due when len >= capacity */
+  int64_t ring_blocks;       /* records per sequence ring; ring_blocks*block_tokens >= the largest len ever held */
+  int64_t pool_blocks;       /* records in `data` */
+  void *data;                /* [device] or [pinned] per `mem`: pool_blocks records */
+  const int32_t *block_table;     /* [host] [batch][ring_blocks] record index per ring block, or NULL = b*ring_blocks + r */
+  const int32_t *block_table_dev; /* [device] copy of block_table; required iff block_table != NULL and mem == DEVICE */
+  float *k_sum;              /* [device] fp32 [pool_blocks][n_kv_heads][128] running key sums, or NULL (no summaries) */
+  void *k_summary;           /* [device] fp16 [pool_blocks][n_kv_heads][128] mean keys; required iff k_sum != NULL */
+  int64_t *start;            /* [host] [batch] lifetime ordinal of the oldest live token (library updates) */
+  int64_t *len;              /* [host] [batch] live tokens (library updates) */
+} ttkv_tier;
+
+typedef struct ttkv_cache {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, n_tiers;
+  float softmax_scale; /* multiplies q.k; 1/sqrt(head_dim) in the usual case */
+  ttkv_tier tier[TTKV_MAX_TIERS];
+} ttkv_cache;
+
+typedef struct ttkv_stats {
+  uint64_t h2d_bytes;       /* host-tier record bytes fetched (Sec. 5.1 item 5: host-to-GPU KV traffic) */
+  uint64_t d2h_bytes;       /* bytes written to host tiers by eviction */
+  uint64_t blocks_fetched;  /* host-tier records fetched */
+  uint64_t kernels;         /* kernels launched */
+  uint64_t demotions;       /* blocks evicted, all tiers and sequences */
+  int32_t last_hip_error;   /* hipError_t of the last failed HIP call, 0 if none */
+} ttkv_stats;
+
+typedef struct ttkv_handle_s *ttkv_handle; /* events for the copy/compute chain + stats; one per calling thread */
+
+/* Create / destroy a handle on the current device.  Creates HIP events only. */
+ttkv_status ttkv_create(ttkv_handle *out);
+ttkv_status ttkv_destroy(ttkv_handle h);
+void ttkv_get_stats(ttkv_handle h, ttkv_stats *out);
+void ttkv_reset_stats(ttkv_handle h);
+const char *ttkv_status_string(ttkv_status s);
+
+/* Bytes of one block record of `tier` (all KV heads). 0 on invalid formats. */
+size_t ttkv_record_bytes(const ttkv_cache *c, int32_t tier);
+
+/* Position -> block index, Eq. (1).  pos counts the sequence's tokens from the
+ * oldest live one (0) to the newest (sum of len - 1) at the time of the call.
+ * Outputs: tier, block id (lifetime ordinal / block_tokens), row in the block,
+ * record index in the tier's pool.  INVALID_ARG if pos is not live. */
+ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *tier, int64_t *block_id,
+                        int32_t *row, int64_t *record);
+
+/* [device] workspace ttkv_decode_attn needs for this cache: split partials for
+ * up to max_parts parts per (sequence, query head) plus n_slots staging records
+ * of the largest host tier.  ttkv_tier_demote needs batch records of its
+ * destination tier when that is a host tier (always covered when n_slots >= batch,
+ * else use ttkv_demote_workspace_bytes). */
+size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots);
+size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
+/* Parts per (sequence, query head) ttkv_decode_attn would use right now. */
+int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride);
+
+/* Append n_tokens per sequence at the tail of `tier` (Sec. 4.1 "newly generated
+ * tokens are appended to the fast tier"; also the bulk loader of any tier).
+ * k_src, v_src: [device] [batch][n_kv_heads][n_tokens][128] in src_fmt (F16, BF16
+ * or F32).  Tier format == src format: plain copy; a quantized tier format: Q of
+ * Sec. 4.2 (device tiers only).  Updates len[].  CAPACITY if any ring would
+ * overflow.  Enqueues on `stream`; src must stay valid until it has run. */
+ttkv_status ttkv_quantize_append(ttkv_handle h, ttkv_cache *c, int32_t tier, const void *k_src, const void *v_src,
+                                 int32_t src_fmt, int64_t n_tokens, void *stream);
+
+/* Like ttkv_quantize_append for a host tier: quantizes into `workspace`
+ * ([device], batch * ceil(n_tokens/block_tokens + 1) records) and copies the
+ * touched records to the pinned pool on `stream`.  Bulk loader of host tiers. */
+ttkv_status ttkv_quantize_append_host(ttkv_handle h, ttkv_cache *c, int32_t tier, const void *k_src,
+                                      const void *v_src, int32_t src_fmt, int64_t n_tokens, void *workspace,
+                                      size_t ws_bytes, void *stream);
+
+/* FIFO tier management (Sec. 4.1; Alg. 1 "evict & compress"): for every
+ * sequence whose src_tier holds >= capacity_tokens, move its oldest block
+ * (src block_tokens tokens; values as stored or decompressed) to the tail of
+ * tier src_tier+1 in that tier's formats, repeating while still due, at most
+ * max_blocks times per sequence (<= 0: no limit).  Host destination: quantized
+ * into `workspace` [device] on `compute`, then copied device->pinned on `copy`
+ * after an event.  Updates start[], len[] of both tiers and the destination's
+ * key summaries.  CAPACITY if a destination ring would overflow. */
+ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int32_t max_blocks, void *workspace,
+                             size_t ws_bytes, void *compute, void *copy);
+
+/* One decode step of streaming attention (Alg. 1 lines 1-10, Sec. 4.3) for every
+ * sequence: partial (max, sum-exp, weighted V) over each part of every device
+ * tier and over each fetched host-tier block, merged by log-sum-exp.
+ *   q    [device] [batch][n_q_heads][128], q_fmt F16 or BF16
+ *   out  [device] [batch][n_q_heads][128] fp32;  lse [device] [batch][n_q_heads] fp32 or NULL
+ *   sel_blocks [host] [batch][sel_stride] block ids (Eq. 1) of the LAST tier to
+ *        attend, ascending, sel_count [host] [batch] how many; both NULL = every
+ *        live block (dense).
+ * Host-tier records are copied to staging slots in `workspace` on `copy`
+ * (n_slots-deep, event-chained) while `compute` attends earlier parts.
+ * Both streams may be the same (then nothing overlaps).  Returns after
+ * enqueuing; `out` is complete when `compute` has drained. */
+ttkv_status ttkv_decode_attn(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
+                             float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
+                             void *workspace, size_t ws_bytes, int32_t n_slots, void *compute, void *copy);
+
+/* Log-sum-exp merge of n_parts partials per row (the "+" of Alg. 1 line 10):
+ *   m, l [device] [rows][part_stride] fp32;  acc [device] [rows][part_stride][128] fp32;
+ *   n_parts_row [device] [rows] int32 parts to merge per row, or NULL = n_parts for all.
+ *   out [device] [rows][128] fp32 = sum_p acc_p e^(m_p-m*) / sum_p l_p e^(m_p-m*);
+ *   lse [device] [rows] = m* + ln(sum) or NULL.  Parts with m = -inf count as empty;
+ *   a row with no non-empty part gives out = 0, lse = -inf. */
+ttkv_status ttkv_merge_partials(ttkv_handle h, const float *m, const float *l, const float *acc, int32_t n_parts,
+                                int32_t part_stride, const int32_t *n_parts_row, int32_t rows, float *out,
+                                float *lse, void *stream);
+
+/* Block identification (Alg. 1 lines 2-6): phi(q, B_j) = sum over query heads of
+ * q_h . mean-key_j for every live block of the LAST tier (needs k_summary), then
+ * the k best per sequence, ties to the lower block id.  sel_blocks [pinned]
+ * [batch][sel_stride] block ids ascending, sel_count [pinned] [batch];
+ * scratch [device] >= batch*(max live blocks)*8 + batch*(sel_stride+1)*4 bytes.
+ * BLOCKS until the ids are on the host. */
+ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k,
+                               int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
+                               size_t scratch_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TTKV_H */
