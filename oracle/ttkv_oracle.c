@@ -138,6 +138,7 @@ void o_quant_i4_asym_g64(const float *x, int64_t rows, int32_t d, uint8_t *packe
         if (xg[i] < lo) lo = xg[i];
         if (xg[i] > hi) hi = xg[i];
       }
+      if (lo == 0.0f) lo = 0.0f; /* a zero minimum is stored as +0 whatever its sign */
       float s32 = (hi - lo) / 15.0f;
       uint16_t sh = o_f32_to_f16(s32);
       uint16_t zh = o_f32_to_f16(lo);

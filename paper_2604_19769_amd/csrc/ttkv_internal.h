@@ -1,0 +1,163 @@
+// Internal declarations shared by the translation units of libttkv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ttkv.h"
+
+namespace ttkv {
+
+// ---------------------------------------------------------------- layout
+// Per token-head byte counts of one format (K or V alone).
+struct FmtBytes {
+  int code, meta;
+};
+inline FmtBytes fmt_bytes(int fmt) {
+  switch (fmt) {
+    case TTKV_F16:
+    case TTKV_BF16: return {256, 0};
+    case TTKV_I8_SYM_G32: return {128, 8};
+    case TTKV_I4_ASYM_G64: return {64, 8};
+    default: return {0, 0};
+  }
+}
+
+// Byte geometry of one block record of a tier (see the header's "Block record").
+struct Layout {
+  int32_t bt;          // tokens per record
+  int32_t kc, km, vc, vm;
+  int32_t k_meta_off;  // offsets inside one head part
+  int32_t v_off, v_meta_off;
+  int32_t head_bytes;
+  int64_t rec_bytes;
+};
+inline Layout make_layout(const ttkv_tier &t, int n_kv_heads) {
+  Layout L{};
+  FmtBytes k = fmt_bytes(t.k_fmt), v = fmt_bytes(t.v_fmt);
+  L.bt = t.block_tokens;
+  L.kc = k.code; L.km = k.meta; L.vc = v.code; L.vm = v.meta;
+  L.k_meta_off = L.bt * L.kc;
+  L.v_off = L.k_meta_off + L.bt * L.km;
+  L.v_meta_off = L.v_off + L.bt * L.vc;
+  L.head_bytes = L.v_meta_off + L.bt * L.vm;
+  L.rec_bytes = (int64_t)L.head_bytes * n_kv_heads;
+  return L;
+}
+
+// What a kernel needs to find a token of a tier (or of a staging slot that holds
+// a few consecutive records of it).
+struct TierView {
+  uint8_t *base;          // record pool (device) or staging slot
+  const int32_t *table;   // device block table or nullptr
+  int64_t rec_bytes;
+  int32_t head_bytes, k_meta_off, v_off, v_meta_off;
+  int32_t bt, ring_blocks;
+  int32_t k_fmt, v_fmt;
+};
+
+// Per-launch sequence table, passed by value in the kernel arguments so that no
+// host->device copy is needed per step.
+struct SeqTable {
+  int32_t n_seq;
+  int32_t seq_id[TTKV_MAX_BATCH];       // sequence (batch index) of entry j
+  int32_t rec_base[TTKV_MAX_BATCH];     // record index of ring block 0 when there is no block table
+  int32_t first_tok[TTKV_MAX_BATCH];    // ring token index of the entry's first token (multiple of 64)
+  int32_t len[TTKV_MAX_BATCH];          // tokens
+  int32_t item_start[TTKV_MAX_BATCH + 1];  // prefix sum of work items (chunks) per entry
+  int32_t part_base[TTKV_MAX_BATCH];    // first partial index this launch writes for the entry
+};
+
+// ---------------------------------------------------------------- handle
+struct Handle {
+  int device;
+  hipEvent_t ready[TTKV_MAX_SLOTS];
+  hipEvent_t freed[TTKV_MAX_SLOTS];
+  hipEvent_t fence;     // orders the copy stream behind earlier compute work
+  hipEvent_t fence2;    // orders device->host eviction copies behind the quantize kernel
+  ttkv_stats stats;
+};
+
+#define TTKV_HIP(h, expr)                                   \
+  do {                                                      \
+    hipError_t e_ = (expr);                                 \
+    if (e_ != hipSuccess) {                                 \
+      if (h) (h)->stats.last_hip_error = (int32_t)e_;       \
+      return TTKV_ERR_HIP;                                  \
+    }                                                       \
+  } while (0)
+
+inline bool is_fp(int f) { return f == TTKV_F16 || f == TTKV_BF16; }
+inline bool is_tier_fmt(int f) { return f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64; }
+
+ttkv_status validate_cache(const ttkv_cache *c);
+
+// ---------------------------------------------------------------- launchers (defined in the .hip files)
+struct ConvSource {
+  // flat source [n_seq_total][Hkv][n][128] (tier == 0) or a tier view
+  const void *k_flat, *v_flat;
+  int32_t flat_fmt;
+  int32_t from_tier;    // 0: flat source, 1: read rows of `src`
+  TierView src;
+  int32_t src_first_tok[TTKV_MAX_BATCH];  // ring token index of the first row to read, per entry
+  int32_t src_rec_base[TTKV_MAX_BATCH];
+};
+struct ConvArgs {
+  ConvSource s;
+  TierView dst;
+  int32_t n_seq, Hkv, n_tokens;            // rows per entry and head
+  int32_t seq_id[TTKV_MAX_BATCH];
+  int32_t dst_first_tok[TTKV_MAX_BATCH];   // ring token index where the first row lands
+  int32_t dst_rec_base[TTKV_MAX_BATCH];
+  int32_t n_via;                           // intermediate formats a value passes through first
+  int32_t via_k[TTKV_MAX_TIERS], via_v[TTKV_MAX_TIERS];
+  // summaries of the destination tier (nullable)
+  float *k_sum;
+  uint16_t *k_summary;
+  const int32_t *sum_table;                // device block table of the destination pool for the summaries
+  int32_t sum_rec_base[TTKV_MAX_BATCH];
+  int32_t sum_ring_blocks;
+  float inv_bt;
+};
+hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels);
+
+struct AttnArgs {
+  TierView tv;
+  SeqTable st;
+  const void *q;
+  int32_t q_fmt;
+  float *pm, *pl, *pacc;
+  int32_t part_stride;
+  int32_t Hq, Hkv;
+  float scale;
+  int32_t chunk_tokens;
+};
+hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s, int *n_kernels);
+bool attn_supported(int k_fmt, int v_fmt, int G);
+
+struct MergeArgs {
+  const float *m, *l, *acc;
+  int32_t n_parts, part_stride, rows;
+  const int32_t *n_parts_row;   // device, nullable
+  int32_t rows_per_seq;         // > 0: use cnt[row / rows_per_seq]
+  int32_t cnt[TTKV_MAX_BATCH];
+  float *out, *lse;
+};
+hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
+
+struct SelectArgs {
+  const void *q;
+  int32_t q_fmt;
+  const uint16_t *k_summary;
+  const int32_t *table;          // device block table of the last tier or nullptr
+  int32_t ring_blocks, Hq, Hkv, k, sel_stride, n_seq;
+  int32_t rec_base[TTKV_MAX_BATCH];
+  int32_t first_block[TTKV_MAX_BATCH];   // ring index of the oldest live block
+  int64_t first_block_id[TTKV_MAX_BATCH];  // its block id (Eq. 1)
+  int32_t n_blocks[TTKV_MAX_BATCH];
+  int32_t max_blocks;
+  float *scores;                 // [n_seq][max_blocks]
+  int32_t *sel_out;              // [n_seq][sel_stride + 1]: count then ids relative to first_block_id
+};
+hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+
+}  // namespace ttkv

@@ -1,0 +1,295 @@
+// Row conversion kernels: append (Sec. 4.1), Q_8bit / Q_4bit (Sec. 4.2) and the
+// eviction path's decompress -> re-quantize.  Compiled with -ffp-contract=off:
+// every fp32 step below is one IEEE operation (divide and fp16 conversion
+// round to nearest even), so codes, scales and zeros are reproducible bit for bit.
+#include "ttkv_internal.h"
+
+#include <hip/hip_fp16.h>
+
+namespace ttkv {
+
+namespace {
+
+__device__ __forceinline__ float h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+__device__ __forceinline__ uint16_t f2h(float f) { return __half_as_ushort(__float2half_rn(f)); }
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Record index and row of ring token `tok` of sequence `seq`.
+__device__ __forceinline__ uint8_t *head_ptr(const TierView &v, int seq, int rec_base, int tok, int h, int *row) {
+  int r = tok / v.bt;
+  *row = tok - r * v.bt;
+  int64_t rec = v.table ? (int64_t)v.table[(int64_t)seq * v.ring_blocks + r] : (int64_t)rec_base + r;
+  return v.base + rec * v.rec_bytes + (int64_t)h * v.head_bytes;
+}
+
+__device__ __forceinline__ int wrap(int tok, const TierView &v) {
+  int ring = v.ring_blocks * v.bt;
+  return tok >= ring ? tok - ring : tok;
+}
+
+// ---- in-register quantize / decompress over a group spread across `LANES`
+// consecutive lanes holding N values each.
+
+// Q1 on a 32-element group: returns the fp16 scale bits, codes as ints.
+template <int N, int LANES>
+__device__ __forceinline__ uint16_t q1_group(const float (&x)[N], int (&c)[N]) {
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < N; ++i) amax = fmaxf(amax, fabsf(x[i]));
+#pragma unroll
+  for (int m = 1; m < LANES; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m));
+  float s32 = amax / 127.0f;
+  uint16_t sh = f2h(s32);
+  float s = h2f(sh);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    float q = 0.0f;
+    if (s != 0.0f) q = fminf(fmaxf(rintf(x[i] / s), -127.0f), 127.0f);
+    c[i] = (int)q;
+  }
+  return sh;
+}
+
+// Q2 on a 64-element group: fp16 scale and zero bits, codes 0..15.
+template <int N, int LANES>
+__device__ __forceinline__ void q2_group(const float (&x)[N], int (&c)[N], uint16_t *sh_out, uint16_t *zh_out) {
+  float lo = x[0], hi = x[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i) {
+    lo = fminf(lo, x[i]);
+    hi = fmaxf(hi, x[i]);
+  }
+#pragma unroll
+  for (int m = 1; m < LANES; m <<= 1) {
+    lo = fminf(lo, __shfl_xor(lo, m));
+    hi = fmaxf(hi, __shfl_xor(hi, m));
+  }
+  if (lo == 0.0f) lo = 0.0f;  // a zero minimum is stored as +0 whatever its sign
+  float s32 = (hi - lo) / 15.0f;
+  uint16_t sh = f2h(s32), zh = f2h(lo);
+  float s = h2f(sh), z = h2f(zh);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    float q = 0.0f;
+    if (s != 0.0f) q = fminf(fmaxf(rintf((x[i] - z) / s), 0.0f), 15.0f);
+    c[i] = (int)q;
+  }
+  *sh_out = sh;
+  *zh_out = zh;
+}
+
+// The values a format decompresses to (a token that passed through a tier).
+template <int N, int L8, int L4>
+__device__ __forceinline__ void roundtrip(int fmt, float (&x)[N]) {
+  int c[N];
+  if (fmt == TTKV_I8_SYM_G32) {
+    uint16_t sh = q1_group<N, L8>(x, c);
+    float s = h2f(sh);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = (float)c[i] * s;
+  } else if (fmt == TTKV_I4_ASYM_G64) {
+    uint16_t sh, zh;
+    q2_group<N, L4>(x, c, &sh, &zh);
+    float s = h2f(sh), z = h2f(zh);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      float p = (float)c[i] * s;
+      x[i] = p + z;
+    }
+  }
+}
+
+// ---- loading 8 consecutive elements [8*l16, 8*l16+8) of one row as fp32.
+__device__ __forceinline__ void load8_flat(const void *flat, int fmt, int64_t row, int l16, float (&x)[8]) {
+  if (fmt == TTKV_F32) {
+    const float4 *p = (const float4 *)((const float *)flat + row * 128 + l16 * 8);
+    float4 a = p[0], b = p[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  } else {
+    uint4 w = *(const uint4 *)((const uint16_t *)flat + row * 128 + l16 * 8);
+    uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint16_t a = (uint16_t)(u[i] & 0xffff), b = (uint16_t)(u[i] >> 16);
+      x[2 * i] = fmt == TTKV_F16 ? h2f(a) : bf2f(a);
+      x[2 * i + 1] = fmt == TTKV_F16 ? h2f(b) : bf2f(b);
+    }
+  }
+}
+
+__device__ __forceinline__ void load8_tier(const uint8_t *head, int fmt, int code_off, int meta_off, int row, int l16,
+                                           float (&x)[8]) {
+  if (fmt == TTKV_F16 || fmt == TTKV_BF16) {
+    uint4 w = *(const uint4 *)(head + code_off + row * 256 + l16 * 16);
+    uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint16_t a = (uint16_t)(u[i] & 0xffff), b = (uint16_t)(u[i] >> 16);
+      x[2 * i] = fmt == TTKV_F16 ? h2f(a) : bf2f(a);
+      x[2 * i + 1] = fmt == TTKV_F16 ? h2f(b) : bf2f(b);
+    }
+  } else if (fmt == TTKV_I8_SYM_G32) {
+    uint2 w = *(const uint2 *)(head + code_off + row * 128 + l16 * 8);
+    float s = h2f(*(const uint16_t *)(head + meta_off + row * 8 + (l16 >> 2) * 2));
+    uint32_t u[2] = {w.x, w.y};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (float)(int)(int8_t)((u[i >> 2] >> (8 * (i & 3))) & 0xff) * s;
+  } else {
+    uint32_t w = *(const uint32_t *)(head + code_off + row * 64 + l16 * 4);
+    uint32_t sz = *(const uint32_t *)(head + meta_off + row * 8 + (l16 >> 3) * 4);
+    float s = h2f((uint16_t)(sz & 0xffff)), z = h2f((uint16_t)(sz >> 16));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float p = (float)(int)((w >> (4 * i)) & 0xf) * s;
+      x[i] = p + z;
+    }
+  }
+}
+
+__device__ __forceinline__ void store8_tier(uint8_t *head, int fmt, int code_off, int meta_off, int row, int l16,
+                                            float (&x)[8], bool live) {
+  if (fmt == TTKV_F16 || fmt == TTKV_BF16) {
+    uint32_t u[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t a, b;
+      if (fmt == TTKV_F16) {
+        a = f2h(x[2 * i]);
+        b = f2h(x[2 * i + 1]);
+      } else {  // source values are bf16 already: the upper half is exact
+        a = __float_as_uint(x[2 * i]) >> 16;
+        b = __float_as_uint(x[2 * i + 1]) >> 16;
+      }
+      u[i] = a | (b << 16);
+    }
+    if (live) *(uint4 *)(head + code_off + row * 256 + l16 * 16) = make_uint4(u[0], u[1], u[2], u[3]);
+  } else if (fmt == TTKV_I8_SYM_G32) {
+    int c[8];
+    uint16_t sh = q1_group<8, 4>(x, c);
+    uint32_t u[2] = {0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u[i >> 2] |= ((uint32_t)c[i] & 0xffu) << (8 * (i & 3));
+    if (live) {
+      *(uint2 *)(head + code_off + row * 128 + l16 * 8) = make_uint2(u[0], u[1]);
+      if ((l16 & 3) == 0) *(uint16_t *)(head + meta_off + row * 8 + (l16 >> 2) * 2) = sh;
+    }
+  } else {
+    int c[8];
+    uint16_t sh, zh;
+    q2_group<8, 8>(x, c, &sh, &zh);
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w |= ((uint32_t)c[i] & 0xfu) << (4 * i);
+    if (live) {
+      *(uint32_t *)(head + code_off + row * 64 + l16 * 4) = w;
+      if ((l16 & 7) == 0) *(uint32_t *)(head + meta_off + row * 8 + (l16 >> 3) * 4) = (uint32_t)sh | ((uint32_t)zh << 16);
+    }
+  }
+}
+
+// One 16-lane group converts one row (one token of one KV head); blockIdx.y
+// picks K (0) or V (1).
+__global__ __launch_bounds__(256) void convert_rows_kernel(const ConvArgs a) {
+  const int which = blockIdx.y;
+  const int l16 = threadIdx.x & 15;
+  const int64_t total = (int64_t)a.n_seq * a.Hkv * a.n_tokens;
+  int64_t row_id = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const bool live = row_id < total;
+  if (!live) row_id = total - 1;
+  const int t = (int)(row_id % a.n_tokens);
+  const int h = (int)((row_id / a.n_tokens) % a.Hkv);
+  const int j = (int)(row_id / ((int64_t)a.n_tokens * a.Hkv));
+  const int seq = a.seq_id[j];
+
+  float x[8];
+  if (!a.s.from_tier) {
+    load8_flat(which ? a.s.v_flat : a.s.k_flat, a.s.flat_fmt, ((int64_t)seq * a.Hkv + h) * a.n_tokens + t, l16, x);
+  } else {
+    int row;
+    const uint8_t *head = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
+    if (which)
+      load8_tier(head, a.s.src.v_fmt, a.s.src.v_off, a.s.src.v_meta_off, row, l16, x);
+    else
+      load8_tier(head, a.s.src.k_fmt, 0, a.s.src.k_meta_off, row, l16, x);
+  }
+  for (int u = 0; u < a.n_via; ++u) roundtrip<8, 4, 8>(which ? a.via_v[u] : a.via_k[u], x);
+
+  int row;
+  uint8_t *head = head_ptr(a.dst, seq, a.dst_rec_base[j], wrap(a.dst_first_tok[j] + t, a.dst), h, &row);
+  if (which)
+    store8_tier(head, a.dst.v_fmt, a.dst.v_off, a.dst.v_meta_off, row, l16, x, live);
+  else
+    store8_tier(head, a.dst.k_fmt, 0, a.dst.k_meta_off, row, l16, x, live);
+}
+
+// Running key sums per destination block, token order (one thread per channel,
+// one workgroup per sequence entry and KV head), and the fp16 mean key.
+__global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
+  const int j = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+  const int seq = a.seq_id[j];
+  float sum = 0.0f;
+  for (int t = 0; t < a.n_tokens; ++t) {
+    float x[1];
+    if (!a.s.from_tier) {
+      int64_t row = ((int64_t)seq * a.Hkv + h) * a.n_tokens + t;
+      if (a.s.flat_fmt == TTKV_F32)
+        x[0] = ((const float *)a.s.k_flat)[row * 128 + i];
+      else {
+        uint16_t w = ((const uint16_t *)a.s.k_flat)[row * 128 + i];
+        x[0] = a.s.flat_fmt == TTKV_F16 ? h2f(w) : bf2f(w);
+      }
+    } else {
+      int row;
+      const uint8_t *head = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
+      const int f = a.s.src.k_fmt;
+      if (f == TTKV_F16 || f == TTKV_BF16) {
+        uint16_t w = *(const uint16_t *)(head + row * 256 + i * 2);
+        x[0] = f == TTKV_F16 ? h2f(w) : bf2f(w);
+      } else if (f == TTKV_I8_SYM_G32) {
+        float s = h2f(*(const uint16_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 5) * 2));
+        x[0] = (float)(int)(int8_t)head[row * 128 + i] * s;
+      } else {
+        uint32_t sz = *(const uint32_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 6) * 4);
+        uint8_t byte = head[row * 64 + (i >> 1)];
+        float p = (float)(int)((i & 1) ? (byte >> 4) : (byte & 0xf)) * h2f((uint16_t)(sz & 0xffff));
+        x[0] = p + h2f((uint16_t)(sz >> 16));
+      }
+    }
+    for (int u = 0; u < a.n_via; ++u) roundtrip<1, 32, 64>(a.via_k[u], x);
+
+    const int tok = wrap(a.dst_first_tok[j] + t, a.dst);
+    const int r = tok / a.dst.bt, row = tok - r * a.dst.bt;
+    const int64_t rec = a.sum_table ? (int64_t)a.sum_table[(int64_t)seq * a.sum_ring_blocks + r] : (int64_t)a.sum_rec_base[j] + r;
+    const int64_t o = (rec * a.Hkv + h) * 128 + i;
+    if (row == 0)
+      sum = 0.0f;
+    else if (t == 0)
+      sum = a.k_sum[o];
+    sum = sum + x[0];
+    if (row == a.dst.bt - 1 || t == a.n_tokens - 1) {
+      a.k_sum[o] = sum;
+      a.k_summary[o] = f2h(sum * a.inv_bt);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
+  const int64_t total = (int64_t)a.n_seq * a.Hkv * a.n_tokens;
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 15) / 16), 2);
+  hipLaunchKernelGGL(convert_rows_kernel, grid, dim3(256), 0, s, a);
+  ++*n_kernels;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.k_sum) {
+    hipLaunchKernelGGL(summary_kernel, dim3(a.n_seq, a.Hkv), dim3(128), 0, s, a);
+    ++*n_kernels;
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace ttkv

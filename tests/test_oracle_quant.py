@@ -142,6 +142,9 @@ def test_q2_ties_and_degenerate():
     packed, scale, zero = O.quant_i4(x)
     c = np.stack([packed & 0xF, packed >> 4], -1).reshape(1, 64)
     assert list(c[0, :8]) == [0, 15, 0, 2, 2, 14, 14, 8]
+    x = np.abs(np.random.default_rng(0).standard_normal((2, 64))).astype(np.float32)
+    x[0, 5], x[1, 5], x[1, 9] = -0.0, 0.0, -0.0   # a zero minimum: the zero point is +0 whichever zero comes first
+    assert np.all(O.quant_i4(x)[2] == 0)
     x = np.full((1, 64), 2.5, np.float32)      # constant group: scale 0, codes 0, decodes to the zero point
     packed, scale, zero = O.quant_i4(x)
     assert np.all(packed == 0) and scale[0, 0] == 0 and zero.view(np.float16)[0, 0] == np.float16(2.5)
