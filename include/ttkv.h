@@ -105,7 +105,8 @@ typedef struct ttkv_stats {
 
 typedef struct ttkv_handle_s *ttkv_handle; /* events for the copy/compute chain + stats; one per calling thread */
 
-/* Create / destroy a handle on the current device.  Creates HIP events only. */
+/* Create / destroy a handle (host memory only; the HIP events of the copy/compute
+ * chain are created on the device current at the first call that needs them). */
 ttkv_status ttkv_create(ttkv_handle *out);
 ttkv_status ttkv_destroy(ttkv_handle h);
 void ttkv_get_stats(ttkv_handle h, ttkv_stats *out);
@@ -132,21 +133,28 @@ size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
 /* Parts per (sequence, query head) ttkv_decode_attn would use right now. */
 int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride);
 
-/* Append n_tokens per sequence at the tail of `tier` (Sec. 4.1 "newly generated
- * tokens are appended to the fast tier"; also the bulk loader of any tier).
- * k_src, v_src: [device] [batch][n_kv_heads][n_tokens][128] in src_fmt (F16, BF16
- * or F32).  Tier format == src format: plain copy; a quantized tier format: Q of
- * Sec. 4.2 (device tiers only).  Updates len[].  CAPACITY if any ring would
- * overflow.  Enqueues on `stream`; src must stay valid until it has run. */
-ttkv_status ttkv_quantize_append(ttkv_handle h, ttkv_cache *c, int32_t tier, const void *k_src, const void *v_src,
-                                 int32_t src_fmt, int64_t n_tokens, void *stream);
+/* Append n_tokens at the tail of `tier` (Sec. 4.1 "newly generated tokens are
+ * appended to the fast tier"; also the bulk loader of any device tier).
+ *   seq  -1: every sequence, k_src/v_src [device] [batch][n_kv_heads][n_tokens][128];
+ *        >= 0: that sequence only, k_src/v_src [device] [n_kv_heads][n_tokens][128].
+ *   src_fmt F16, BF16 or F32.  An fp tier takes only its own format (plain
+ *   copy); a quantized tier applies Q of Sec. 4.2.
+ *   through_tiers != 0: the values first pass through the formats of tiers
+ *   1..tier-1 (quantize + decompress each), i.e. arrive as eviction would have
+ *   delivered them; 0: quantized directly.
+ * Updates len[].  CAPACITY if a ring would overflow.  Enqueues on `stream`;
+ * the sources must stay valid until it has run. */
+ttkv_status ttkv_quantize_append(ttkv_handle h, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src,
+                                 const void *v_src, int32_t src_fmt, int64_t n_tokens, int32_t through_tiers,
+                                 void *stream);
 
-/* Like ttkv_quantize_append for a host tier: quantizes into `workspace`
- * ([device], batch * ceil(n_tokens/block_tokens + 1) records) and copies the
- * touched records to the pinned pool on `stream`.  Bulk loader of host tiers. */
-ttkv_status ttkv_quantize_append_host(ttkv_handle h, ttkv_cache *c, int32_t tier, const void *k_src,
-                                      const void *v_src, int32_t src_fmt, int64_t n_tokens, void *workspace,
-                                      size_t ws_bytes, void *stream);
+/* The same for a host tier: quantizes into `workspace` [device]
+ * (ttkv_append_host_workspace_bytes) and copies the touched rows of the touched
+ * records to the pinned pool on `stream`. */
+ttkv_status ttkv_quantize_append_host(ttkv_handle h, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src,
+                                      const void *v_src, int32_t src_fmt, int64_t n_tokens, int32_t through_tiers,
+                                      void *workspace, size_t ws_bytes, void *stream);
+size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32_t seq, int64_t n_tokens);
 
 /* FIFO tier management (Sec. 4.1; Alg. 1 "evict & compress"): for every
  * sequence whose src_tier holds >= capacity_tokens, move its oldest block

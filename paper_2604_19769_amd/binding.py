@@ -1,0 +1,199 @@
+"""ctypes binding of libttkv.so: the same names as include/ttkv.h, argument
+marshalling only.  The library must have been built (python -m
+paper_2604_19769_amd.build, or __graft_entry__.build()); there is no fallback
+path of any kind: a missing library is an error."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libttkv.so")
+
+TTKV_MAX_TIERS = 4
+TTKV_MAX_BATCH = 64
+TTKV_MAX_SLOTS = 8
+
+OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
+F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32 = range(5)
+MEM_DEVICE, MEM_HOST_PINNED = 0, 1
+FMT_NAMES = {"f16": F16, "bf16": BF16, "i8": I8_SYM_G32, "i4": I4_ASYM_G64, "f32": F32}
+
+
+class ttkv_tier(C.Structure):
+    _fields_ = [
+        ("k_fmt", C.c_int32), ("v_fmt", C.c_int32), ("mem", C.c_int32), ("block_tokens", C.c_int32),
+        ("capacity_tokens", C.c_int64), ("ring_blocks", C.c_int64), ("pool_blocks", C.c_int64),
+        ("data", C.c_void_p), ("block_table", C.c_void_p), ("block_table_dev", C.c_void_p),
+        ("k_sum", C.c_void_p), ("k_summary", C.c_void_p), ("start", C.c_void_p), ("len", C.c_void_p),
+    ]
+
+
+class ttkv_cache(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("n_tiers", C.c_int32), ("softmax_scale", C.c_float), ("tier", ttkv_tier * TTKV_MAX_TIERS),
+    ]
+
+
+class ttkv_stats(C.Structure):
+    _fields_ = [
+        ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64), ("blocks_fetched", C.c_uint64),
+        ("kernels", C.c_uint64), ("demotions", C.c_uint64), ("last_hip_error", C.c_int32),
+    ]
+
+
+EXPORTS = [
+    "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
+    "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
+    "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
+    "ttkv_merge_partials", "ttkv_select_blocks",
+]
+
+_lib = None
+
+
+class TTKVError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def lib():
+    """Load libttkv.so.  Raises if it has not been built: nothing replaces it."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_19769_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        p, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        cp = C.POINTER(ttkv_cache)
+        L.ttkv_create.argtypes = [C.POINTER(p)]
+        L.ttkv_destroy.argtypes = [p]
+        L.ttkv_get_stats.argtypes = [p, C.POINTER(ttkv_stats)]
+        L.ttkv_get_stats.restype = None
+        L.ttkv_reset_stats.argtypes = [p]
+        L.ttkv_reset_stats.restype = None
+        L.ttkv_status_string.argtypes = [i32]
+        L.ttkv_status_string.restype = C.c_char_p
+        L.ttkv_record_bytes.argtypes = [cp, i32]
+        L.ttkv_record_bytes.restype = sz
+        L.ttkv_locate.argtypes = [cp, i32, i64, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32), C.POINTER(i64)]
+        L.ttkv_workspace_bytes.argtypes = [cp, i32, i32]
+        L.ttkv_workspace_bytes.restype = sz
+        L.ttkv_demote_workspace_bytes.argtypes = [cp, i32]
+        L.ttkv_demote_workspace_bytes.restype = sz
+        L.ttkv_append_host_workspace_bytes.argtypes = [cp, i32, i32, i64]
+        L.ttkv_append_host_workspace_bytes.restype = sz
+        L.ttkv_count_parts.argtypes = [cp, p, p, i32]
+        L.ttkv_count_parts.restype = i32
+        L.ttkv_quantize_append.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p]
+        L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
+        L.ttkv_tier_demote.argtypes = [p, cp, i32, i32, p, sz, p, p]
+        L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
+        L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
+        L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
+        for name in EXPORTS:
+            f = getattr(L, name)
+            if name not in ("ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
+                            "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes",
+                            "ttkv_append_host_workspace_bytes", "ttkv_count_parts"):
+                f.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().ttkv_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != OK:
+        raise TTKVError(status, what)
+
+
+def _p(x):
+    """Pointer of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return C.c_void_p(x)
+    return C.c_void_p(x.data_ptr())
+
+
+def ttkv_create():
+    h = C.c_void_p()
+    _check(lib().ttkv_create(C.byref(h)), "ttkv_create")
+    return h
+
+
+def ttkv_destroy(h):
+    _check(lib().ttkv_destroy(h), "ttkv_destroy")
+
+
+def ttkv_get_stats(h):
+    s = ttkv_stats()
+    lib().ttkv_get_stats(h, C.byref(s))
+    return {k: getattr(s, k) for k, _ in ttkv_stats._fields_}
+
+
+def ttkv_reset_stats(h):
+    lib().ttkv_reset_stats(h)
+
+
+def ttkv_record_bytes(cache, tier):
+    return lib().ttkv_record_bytes(C.byref(cache), tier)
+
+
+def ttkv_locate(cache, b, pos):
+    t, blk, row, rec = C.c_int32(), C.c_int64(), C.c_int32(), C.c_int64()
+    _check(lib().ttkv_locate(C.byref(cache), b, pos, C.byref(t), C.byref(blk), C.byref(row), C.byref(rec)), "ttkv_locate")
+    return t.value, blk.value, row.value, rec.value
+
+
+def ttkv_workspace_bytes(cache, max_parts, n_slots):
+    return lib().ttkv_workspace_bytes(C.byref(cache), max_parts, n_slots)
+
+
+def ttkv_demote_workspace_bytes(cache, src_tier):
+    return lib().ttkv_demote_workspace_bytes(C.byref(cache), src_tier)
+
+
+def ttkv_append_host_workspace_bytes(cache, tier, seq, n_tokens):
+    return lib().ttkv_append_host_workspace_bytes(C.byref(cache), tier, seq, n_tokens)
+
+
+def ttkv_count_parts(cache, sel_blocks=None, sel_count=None, sel_stride=0):
+    return lib().ttkv_count_parts(C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride)
+
+
+def ttkv_quantize_append(h, cache, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, stream):
+    _check(lib().ttkv_quantize_append(h, C.byref(cache), tier, seq, _p(k_src), _p(v_src), src_fmt, n_tokens,
+                                      through_tiers, _p(stream)), "ttkv_quantize_append")
+
+
+def ttkv_quantize_append_host(h, cache, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, workspace,
+                              ws_bytes, stream):
+    _check(lib().ttkv_quantize_append_host(h, C.byref(cache), tier, seq, _p(k_src), _p(v_src), src_fmt, n_tokens,
+                                           through_tiers, _p(workspace), ws_bytes, _p(stream)),
+           "ttkv_quantize_append_host")
+
+
+def ttkv_tier_demote(h, cache, src_tier, max_blocks, workspace, ws_bytes, compute, copy):
+    _check(lib().ttkv_tier_demote(h, C.byref(cache), src_tier, max_blocks, _p(workspace), ws_bytes, _p(compute),
+                                  _p(copy)), "ttkv_tier_demote")
+
+
+def ttkv_decode_attn(h, cache, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots,
+                     compute, copy):
+    _check(lib().ttkv_decode_attn(h, C.byref(cache), _p(q), q_fmt, _p(out), _p(lse), _p(sel_blocks), _p(sel_count),
+                                  sel_stride, _p(workspace), ws_bytes, n_slots, _p(compute), _p(copy)),
+           "ttkv_decode_attn")
+
+
+def ttkv_merge_partials(h, m, l, acc, n_parts, part_stride, n_parts_row, rows, out, lse, stream):
+    _check(lib().ttkv_merge_partials(h, _p(m), _p(l), _p(acc), n_parts, part_stride, _p(n_parts_row), rows, _p(out),
+                                     _p(lse), _p(stream)), "ttkv_merge_partials")
+
+
+def ttkv_select_blocks(h, cache, q, q_fmt, k, sel_blocks, sel_count, sel_stride, scratch, scratch_bytes, stream):
+    _check(lib().ttkv_select_blocks(h, C.byref(cache), _p(q), q_fmt, k, _p(sel_blocks), _p(sel_count), sel_stride,
+                                    _p(scratch), scratch_bytes, _p(stream)), "ttkv_select_blocks")

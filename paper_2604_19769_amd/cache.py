@@ -1,0 +1,201 @@
+"""Caller-side plumbing around libttkv: allocates the tiers' record pools
+(torch tensors: HBM or pinned host memory), fills the ttkv_cache descriptor and
+forwards to the C ABI.  No arithmetic of the method lives here; every step of
+the hot path runs in the library's kernels."""
+import ctypes as C
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class TierConfig:
+    k_fmt: str                 # 'f16' | 'bf16' | 'i8' | 'i4'
+    v_fmt: str
+    capacity: int              # eviction threshold in tokens (L_fast for tier 0)
+    block_tokens: int          # B_blk
+    ring_blocks: int           # records per sequence ring
+    mem: str = "device"        # 'device' | 'host'
+    paged_seed: int = None     # not None: shuffled block table over a shared pool (paged KV)
+    summary: bool = False      # keep mean-key summaries (block identification)
+
+
+_SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 8)}
+
+
+class TieredCache:
+    def __init__(self, batch, n_q_heads, n_kv_heads, tiers, device="cuda:0", softmax_scale=None, n_slots=2):
+        self.B, self.Hq, self.Hkv = batch, n_q_heads, n_kv_heads
+        self.cfg = list(tiers)
+        self.device = torch.device(device)
+        self.n_slots = n_slots
+        self.h = B.ttkv_create()
+        self.c = B.ttkv_cache()
+        c = self.c
+        c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_tiers = batch, n_q_heads, n_kv_heads, 128, len(self.cfg)
+        c.softmax_scale = float(softmax_scale) if softmax_scale is not None else 1.0 / float(np.sqrt(128.0))
+        self._keep = []          # tensors / arrays the descriptor points into
+        self.start, self.len, self.pool, self.table = [], [], [], []
+        for t, cfg in enumerate(self.cfg):
+            T = c.tier[t]
+            T.k_fmt, T.v_fmt = B.FMT_NAMES[cfg.k_fmt], B.FMT_NAMES[cfg.v_fmt]
+            T.mem = B.MEM_HOST_PINNED if cfg.mem == "host" else B.MEM_DEVICE
+            T.block_tokens, T.capacity_tokens, T.ring_blocks = cfg.block_tokens, cfg.capacity, cfg.ring_blocks
+            T.pool_blocks = batch * cfg.ring_blocks
+            rec = B.ttkv_record_bytes(c, t)
+            assert rec > 0
+            nbytes = T.pool_blocks * rec
+            if cfg.mem == "host":
+                pool = torch.zeros(nbytes, dtype=torch.uint8, pin_memory=True)
+            else:
+                pool = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+            T.data = pool.data_ptr()
+            start = np.zeros(batch, np.int64)
+            ln = np.zeros(batch, np.int64)
+            T.start, T.len = start.ctypes.data, ln.ctypes.data
+            table = None
+            if cfg.paged_seed is not None:
+                table = np.random.Generator(np.random.Philox(cfg.paged_seed)).permutation(T.pool_blocks).astype(np.int32)
+                table = np.ascontiguousarray(table.reshape(batch, cfg.ring_blocks))
+                tdev = torch.from_numpy(table).to(self.device)
+                T.block_table, T.block_table_dev = table.ctypes.data, tdev.data_ptr()
+                self._keep.append(tdev)
+            if cfg.summary:
+                ksum = torch.zeros(T.pool_blocks * n_kv_heads * 128, dtype=torch.float32, device=self.device)
+                kmu = torch.zeros(T.pool_blocks * n_kv_heads * 128, dtype=torch.float16, device=self.device)
+                T.k_sum, T.k_summary = ksum.data_ptr(), kmu.data_ptr()
+                self._keep += [ksum, kmu]
+                self.ksum, self.kmu = ksum, kmu
+            self.start.append(start)
+            self.len.append(ln)
+            self.pool.append(pool)
+            self.table.append(table)
+        self.copy_stream = torch.cuda.Stream(device=self.device)
+        self.ws = None
+        self.ws_parts = 0
+        self.demote_ws = None
+        self.sel_blocks = self.sel_count = self.sel_scratch = None
+        self.out = torch.empty(batch, n_q_heads, 128, dtype=torch.float32, device=self.device)
+        self.lse = torch.empty(batch, n_q_heads, dtype=torch.float32, device=self.device)
+
+    def close(self):
+        if self.h is not None:
+            torch.cuda.synchronize(self.device)
+            B.ttkv_destroy(self.h)
+            self.h = None
+
+    # ------------------------------------------------------------------ streams
+    def _compute(self):
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def _copy(self, overlap=True):
+        return self.copy_stream.cuda_stream if overlap else self._compute()
+
+    # ------------------------------------------------------------------ calls
+    def record_bytes(self, t):
+        return B.ttkv_record_bytes(self.c, t)
+
+    def locate(self, b, pos):
+        return B.ttkv_locate(self.c, b, pos)
+
+    def stats(self):
+        return B.ttkv_get_stats(self.h)
+
+    def append(self, tier, k, v, seq=-1, through_tiers=False):
+        """k, v: device tensors [B][Hkv][n][128] (seq=-1) or [Hkv][n][128], f16 / bf16 / f32."""
+        fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16, torch.float32: B.F32}[k.dtype]
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape and k.dtype == v.dtype
+        n = k.shape[-2]
+        if self.cfg[tier].mem == "host":
+            need = B.ttkv_append_host_workspace_bytes(self.c, tier, seq, n)
+            ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+            B.ttkv_quantize_append_host(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), ws, need, self._compute())
+            torch.cuda.current_stream(self.device).synchronize()   # ws goes out of scope
+        else:
+            B.ttkv_quantize_append(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), self._compute())
+
+    def demote(self, overlap=True):
+        """Cascade eviction through all tiers (Alg. 1, last lines)."""
+        for t in range(len(self.cfg) - 1):
+            need = B.ttkv_demote_workspace_bytes(self.c, t)
+            if need and (self.demote_ws is None or self.demote_ws.numel() < need):
+                self.demote_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+            B.ttkv_tier_demote(self.h, self.c, t, 0, self.demote_ws if need else None, need, self._compute(),
+                               self._copy(overlap))
+
+    def _workspace(self, parts):
+        if self.ws is None or parts > self.ws_parts:
+            parts = max(parts + 16, int(parts * 1.25))
+            need = B.ttkv_workspace_bytes(self.c, parts, self.n_slots)
+            assert need > 0
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self.ws_parts = parts
+        return self.ws
+
+    def decode(self, q, selected=None, overlap=True):
+        """q [B][Hq][128] f16/bf16 on the device.  selected: None or (sel_blocks, sel_count) pinned int32 tensors."""
+        q_fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[q.dtype]
+        assert q.is_contiguous() and tuple(q.shape) == (self.B, self.Hq, 128)
+        sb = sc = None
+        stride = 0
+        if selected is not None:
+            sb, sc = selected
+            stride = sb.shape[1]
+        parts = B.ttkv_count_parts(self.c, sb, sc, stride)
+        if parts < 0:
+            raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
+        ws = self._workspace(max(parts, 1))
+        B.ttkv_decode_attn(self.h, self.c, q, q_fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(), self.n_slots,
+                           self._compute(), self._copy(overlap))
+        return self.out, self.lse
+
+    def select(self, q, k):
+        q_fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[q.dtype]
+        stride = max(1, k)
+        if self.sel_blocks is None or self.sel_blocks.shape[1] != stride:
+            self.sel_blocks = torch.zeros(self.B, stride, dtype=torch.int32, pin_memory=True)
+            self.sel_count = torch.zeros(self.B, dtype=torch.int32, pin_memory=True)
+            self.sel_scratch = torch.empty(self.B * (1024 * 4 + (stride + 1) * 4) + 512, dtype=torch.uint8, device=self.device)
+        B.ttkv_select_blocks(self.h, self.c, q, q_fmt, k, self.sel_blocks, self.sel_count, stride, self.sel_scratch,
+                             self.sel_scratch.numel(), self._compute())
+        return self.sel_blocks, self.sel_count
+
+    def step(self, q, k_new, v_new, select_k=None, overlap=True):
+        """One decode step (Alg. 1): append -> [identify blocks] -> attend -> evict."""
+        self.append(0, k_new, v_new)
+        sel = self.select(q, select_k) if select_k is not None else None
+        out, lse = self.decode(q, sel, overlap)
+        self.demote(overlap)
+        return out, lse
+
+    # ------------------------------------------------------------------ inspection (layout decoding only)
+    def dump_tier(self, t, b):
+        """Live rows of tier t, sequence b, oldest first, as raw bytes:
+        {'k': uint8 [Hkv][n][kc], 'k_meta': uint8 [Hkv][n][km], 'v': ..., 'v_meta': ...}."""
+        torch.cuda.synchronize(self.device)
+        cfg = self.cfg[t]
+        bt, ring = cfg.block_tokens, cfg.ring_blocks
+        kc, km = _SECTION_BYTES[cfg.k_fmt]
+        vc, vm = _SECTION_BYTES[cfg.v_fmt]
+        head_bytes = bt * (kc + km + vc + vm)
+        pool = self.pool[t].cpu().numpy().reshape(-1, self.Hkv, head_bytes)
+        o = int(self.start[t][b]) + np.arange(int(self.len[t][b]), dtype=np.int64)
+        r = (o // bt) % ring
+        rec = self.table[t][b][r] if self.table[t] is not None else b * ring + r
+        row = o % bt
+        out, off = {}, 0
+        for name, w in (("k", kc), ("k_meta", km), ("v", vc), ("v_meta", vm)):
+            sec = pool[:, :, off:off + bt * w].reshape(pool.shape[0], self.Hkv, bt, w)
+            out[name] = np.ascontiguousarray(sec[rec, :, row].transpose(1, 0, 2)) if w else None
+            off += bt * w
+        return out
+
+    def dump_summary(self, t, b, block_id):
+        torch.cuda.synchronize(self.device)
+        ring = self.cfg[t].ring_blocks
+        r = block_id % ring
+        rec = int(self.table[t][b][r]) if self.table[t] is not None else b * ring + r
+        return self.kmu.view(-1, self.Hkv, 128)[rec].cpu().numpy().view(np.uint16)

@@ -1,0 +1,751 @@
+// Host side of libttkv: argument validation, tier bookkeeping (Sec. 4.1), the
+// split-K plan, and the copy/compute event chain of streaming attention
+// (Sec. 4.3, Alg. 1).  No device memory is allocated here.
+#include "ttkv_internal.h"
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+using namespace ttkv;
+
+namespace ttkv {
+
+ttkv_status validate_cache(const ttkv_cache *c) {
+  if (!c) return TTKV_ERR_INVALID_ARG;
+  if (c->head_dim != TTKV_HEAD_DIM) return TTKV_ERR_UNSUPPORTED;
+  if (c->batch < 1 || c->batch > TTKV_MAX_BATCH) return TTKV_ERR_INVALID_ARG;
+  if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return TTKV_ERR_INVALID_ARG;
+  if (c->n_tiers < 1 || c->n_tiers > TTKV_MAX_TIERS) return TTKV_ERR_INVALID_ARG;
+  if (!(c->softmax_scale > 0.0f)) return TTKV_ERR_INVALID_ARG;
+  for (int t = 0; t < c->n_tiers; ++t) {
+    const ttkv_tier &T = c->tier[t];
+    if (!is_tier_fmt(T.k_fmt) || !is_tier_fmt(T.v_fmt)) return TTKV_ERR_INVALID_ARG;
+    if (!attn_supported(T.k_fmt, T.v_fmt, c->n_q_heads / c->n_kv_heads)) return TTKV_ERR_UNSUPPORTED;
+    if (T.mem != TTKV_MEM_DEVICE && T.mem != TTKV_MEM_HOST_PINNED) return TTKV_ERR_INVALID_ARG;
+    if (T.block_tokens < 64 || T.block_tokens % 64) return TTKV_ERR_INVALID_ARG;
+    if (T.ring_blocks < 1 || T.pool_blocks < 1 || !T.data || !T.start || !T.len) return TTKV_ERR_INVALID_ARG;
+    if (T.ring_blocks * (int64_t)T.block_tokens >= (int64_t)1 << 30) return TTKV_ERR_INVALID_ARG;
+    if (T.pool_blocks >= (int64_t)1 << 31) return TTKV_ERR_INVALID_ARG;
+    if (T.capacity_tokens < T.block_tokens) return TTKV_ERR_INVALID_ARG;
+    if (!T.block_table && T.pool_blocks < (int64_t)c->batch * T.ring_blocks) return TTKV_ERR_INVALID_ARG;
+    if (T.block_table && (T.mem == TTKV_MEM_DEVICE || T.k_sum) && !T.block_table_dev) return TTKV_ERR_INVALID_ARG;
+    if (T.k_sum && !T.k_summary) return TTKV_ERR_INVALID_ARG;
+    if (T.block_table)
+      for (int64_t i = 0; i < (int64_t)c->batch * T.ring_blocks; ++i)
+        if (T.block_table[i] < 0 || T.block_table[i] >= T.pool_blocks) return TTKV_ERR_INVALID_ARG;
+    for (int b = 0; b < c->batch; ++b) {
+      if (T.len[b] < 0 || T.len[b] > T.ring_blocks * T.block_tokens) return TTKV_ERR_INVALID_ARG;
+      if (T.start[b] < 0 || T.start[b] % T.block_tokens) return TTKV_ERR_INVALID_ARG;
+    }
+  }
+  return TTKV_OK;
+}
+
+}  // namespace ttkv
+
+namespace {
+
+TierView make_view(const ttkv_tier &T, const Layout &L) {
+  TierView v{};
+  v.base = (uint8_t *)T.data;
+  v.table = T.block_table_dev;
+  v.rec_bytes = L.rec_bytes;
+  v.head_bytes = L.head_bytes;
+  v.k_meta_off = L.k_meta_off;
+  v.v_off = L.v_off;
+  v.v_meta_off = L.v_meta_off;
+  v.bt = L.bt;
+  v.ring_blocks = (int32_t)T.ring_blocks;
+  v.k_fmt = T.k_fmt;
+  v.v_fmt = T.v_fmt;
+  return v;
+}
+
+// A staging area holding `nrec` consecutive records in the tier's layout.
+TierView make_slot_view(const ttkv_tier &T, const Layout &L, void *slot, int nrec) {
+  TierView v = make_view(T, L);
+  v.base = (uint8_t *)slot;
+  v.table = nullptr;
+  v.ring_blocks = nrec;
+  return v;
+}
+
+inline int64_t ring_tokens(const ttkv_tier &T) { return T.ring_blocks * (int64_t)T.block_tokens; }
+inline int64_t record_of(const ttkv_tier &T, int b, int64_t ring_block) {
+  return T.block_table ? (int64_t)T.block_table[(int64_t)b * T.ring_blocks + ring_block] : (int64_t)b * T.ring_blocks + ring_block;
+}
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Consecutive pool records merged into one copy when adjacent (dense, unpaged tiers).
+int copy_granule(int64_t rec_bytes) {
+  int64_t g = ((int64_t)1 << 20) / rec_bytes;
+  return (int)std::max<int64_t>(1, std::min<int64_t>(8, g));
+}
+
+struct DevLaunch {
+  int tier;
+  int chunk;
+  SeqTable st;
+};
+struct Fetch {
+  int tier, b;
+  int64_t rec;     // first pool record
+  int nrec;        // consecutive records in this copy
+  int ntok;        // live tokens covered
+  int part_base;
+  int chunk;
+};
+struct Plan {
+  std::vector<DevLaunch> dev;
+  std::vector<Fetch> fetch;
+  int parts[TTKV_MAX_BATCH];
+  int max_parts;
+  size_t slot_bytes;
+  ttkv_status status;
+};
+
+int pick_chunk(const ttkv_cache *c, int t) {
+  const ttkv_tier &T = c->tier[t];
+  int64_t total = 0;
+  for (int b = 0; b < c->batch; ++b) total += T.len[b];
+  const int G = c->n_q_heads / c->n_kv_heads;
+  const int n_hg = G % 4 == 0 ? G / 4 : (G % 2 == 0 ? G / 2 : G);
+  // aim at ~4096 workgroups (16 per CU) with chunks of 256..2048 tokens
+  int64_t want = total * c->n_kv_heads * n_hg / 4096;
+  int64_t lo = is_fp(T.k_fmt) ? 128 : 256;
+  want = std::max<int64_t>(lo, std::min<int64_t>(2048, want));
+  return (int)((want + 63) / 64 * 64);
+}
+
+void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, Plan *P) {
+  P->status = TTKV_OK;
+  P->slot_bytes = 0;
+  for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
+  const int last = c->n_tiers - 1;
+  for (int t = 0; t < c->n_tiers; ++t) {
+    const ttkv_tier &T = c->tier[t];
+    const Layout L = make_layout(T, c->n_kv_heads);
+    const bool sparse = sel_blocks && t == last;
+    if (T.mem == TTKV_MEM_DEVICE && !sparse) {
+      DevLaunch d{};
+      d.tier = t;
+      d.chunk = pick_chunk(c, t);
+      int items = 0;
+      for (int b = 0; b < c->batch; ++b) {
+        if (T.len[b] == 0) continue;
+        const int j = d.st.n_seq++;
+        d.st.seq_id[j] = b;
+        d.st.rec_base[j] = (int32_t)((int64_t)b * T.ring_blocks);
+        d.st.first_tok[j] = (int32_t)(T.start[b] % ring_tokens(T));
+        d.st.len[j] = (int32_t)T.len[b];
+        d.st.item_start[j] = items;
+        d.st.part_base[j] = P->parts[b];
+        const int n = (int)((T.len[b] + d.chunk - 1) / d.chunk);
+        items += n;
+        P->parts[b] += n;
+      }
+      d.st.item_start[d.st.n_seq] = items;
+      if (d.st.n_seq) P->dev.push_back(d);
+      continue;
+    }
+    // host tier, or a sparse (selected-blocks) pass over the last tier: one part
+    // group per fetched / selected block
+    const int gran = T.mem == TTKV_MEM_HOST_PINNED ? copy_granule(L.rec_bytes) : 1;
+    if (T.mem == TTKV_MEM_HOST_PINNED) P->slot_bytes = std::max(P->slot_bytes, align256((size_t)gran * L.rec_bytes));
+    const int chunk = std::min(L.bt, 256);
+    for (int b = 0; b < c->batch; ++b) {
+      if (T.len[b] == 0 && !sparse) continue;
+      const int64_t first_id = T.start[b] / L.bt;
+      const int64_t end_id = (T.start[b] + T.len[b] + L.bt - 1) / L.bt;  // exclusive
+      const int64_t n_ids = sparse ? sel_count[b] : end_id - first_id;
+      int64_t prev_id = -1;
+      for (int64_t i = 0; i < n_ids; ++i) {
+        const int64_t id = sparse ? (int64_t)sel_blocks[(int64_t)b * sel_stride + i] : first_id + i;
+        if (id < first_id || id >= end_id || id <= prev_id) {
+          P->status = TTKV_ERR_INVALID_ARG;
+          return;
+        }
+        prev_id = id;
+        const int64_t rec = record_of(T, b, id % T.ring_blocks);
+        const int ntok = (int)std::min<int64_t>(L.bt, T.start[b] + T.len[b] - id * L.bt);
+        if (!P->fetch.empty()) {
+          Fetch &f = P->fetch.back();
+          if (f.tier == t && f.b == b && f.nrec < gran && f.rec + f.nrec == rec && f.ntok == f.nrec * L.bt) {
+            f.nrec += 1;
+            f.ntok += ntok;
+            P->parts[b] += (ntok + chunk - 1) / chunk;
+            continue;
+          }
+        }
+        Fetch f{};
+        f.tier = t; f.b = b; f.rec = rec; f.nrec = 1; f.ntok = ntok; f.chunk = chunk;
+        f.part_base = P->parts[b];
+        P->parts[b] += (ntok + chunk - 1) / chunk;
+        P->fetch.push_back(f);
+      }
+    }
+  }
+  P->max_parts = 0;
+  for (int b = 0; b < c->batch; ++b) P->max_parts = std::max(P->max_parts, P->parts[b]);
+}
+
+ttkv_status check_sel(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride) {
+  if ((sel_blocks == nullptr) != (sel_count == nullptr)) return TTKV_ERR_INVALID_ARG;
+  if (sel_blocks) {
+    if (sel_stride < 0) return TTKV_ERR_INVALID_ARG;
+    for (int b = 0; b < c->batch; ++b)
+      if (sel_count[b] < 0 || sel_count[b] > sel_stride) return TTKV_ERR_INVALID_ARG;
+  }
+  return TTKV_OK;
+}
+
+// Rows were described by `a` (their destination may be a staging view); update the
+// running key sums / mean keys of tier t, whose ring position is taken from its
+// start/len before they are advanced.
+hipError_t run_summary(const ConvArgs &a, const ttkv_cache *c, int t, hipStream_t s, int *nk) {
+  const ttkv_tier &T = c->tier[t];
+  if (!T.k_sum) return hipSuccess;
+  ConvArgs u = a;
+  u.dst = make_view(T, make_layout(T, c->n_kv_heads));
+  u.k_sum = T.k_sum;
+  u.k_summary = (uint16_t *)T.k_summary;
+  u.sum_table = T.block_table_dev;
+  u.sum_ring_blocks = (int32_t)T.ring_blocks;
+  u.inv_bt = 1.0f / (float)T.block_tokens;
+  for (int j = 0; j < a.n_seq; ++j) {
+    const int b = a.seq_id[j];
+    u.dst_first_tok[j] = (int32_t)((T.start[b] + T.len[b]) % ring_tokens(T));
+    u.sum_rec_base[j] = (int32_t)((int64_t)b * T.ring_blocks);
+  }
+  return launch_summary(u, s, nk);
+}
+
+void fill_via(ConvArgs &a, const ttkv_cache *c, int tier, bool through) {
+  a.n_via = 0;
+  if (!through) return;
+  for (int u = 1; u < tier; ++u) {
+    a.via_k[a.n_via] = c->tier[u].k_fmt;
+    a.via_v[a.n_via] = c->tier[u].v_fmt;
+    ++a.n_via;
+  }
+}
+
+// Device->pinned copies of rows [row_lo, row_hi) of one record (all heads, all sections).
+ttkv_status copy_rows_to_host(Handle *h, const Layout &L, int Hkv, uint8_t *host_rec, const uint8_t *dev_rec, int row_lo,
+                              int row_hi, hipStream_t s) {
+  if (row_lo == 0 && row_hi == L.bt) {
+    TTKV_HIP(h, hipMemcpyAsync(host_rec, dev_rec, (size_t)L.rec_bytes, hipMemcpyDeviceToHost, s));
+    h->stats.d2h_bytes += (uint64_t)L.rec_bytes;
+    return TTKV_OK;
+  }
+  const int off[4] = {0, L.k_meta_off, L.v_off, L.v_meta_off};
+  const int rowb[4] = {L.kc, L.km, L.vc, L.vm};
+  for (int sct = 0; sct < 4; ++sct) {
+    if (!rowb[sct]) continue;
+    const size_t o = (size_t)off[sct] + (size_t)row_lo * rowb[sct];
+    const size_t width = (size_t)(row_hi - row_lo) * rowb[sct];
+    TTKV_HIP(h, hipMemcpy2DAsync(host_rec + o, (size_t)L.head_bytes, dev_rec + o, (size_t)L.head_bytes, width, (size_t)Hkv,
+                                 hipMemcpyDeviceToHost, s));
+    h->stats.d2h_bytes += (uint64_t)width * Hkv;
+  }
+  return TTKV_OK;
+}
+
+ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src, const void *v_src,
+                        int32_t src_fmt, int64_t n_tokens, int32_t through, void *workspace, size_t ws_bytes,
+                        hipStream_t stream, bool host_variant) {
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (tier < 0 || tier >= c->n_tiers || seq < -1 || seq >= c->batch || !k_src || !v_src || n_tokens < 0)
+    return TTKV_ERR_INVALID_ARG;
+  if (src_fmt != TTKV_F16 && src_fmt != TTKV_BF16 && src_fmt != TTKV_F32) return TTKV_ERR_INVALID_ARG;
+  ttkv_tier &T = c->tier[tier];
+  if ((T.mem == TTKV_MEM_HOST_PINNED) != host_variant) return TTKV_ERR_INVALID_ARG;
+  if ((is_fp(T.k_fmt) && T.k_fmt != src_fmt) || (is_fp(T.v_fmt) && T.v_fmt != src_fmt)) return TTKV_ERR_UNSUPPORTED;
+  if (n_tokens == 0) return TTKV_OK;
+  const int b0 = seq < 0 ? 0 : seq, b1 = seq < 0 ? c->batch : seq + 1;
+  for (int b = b0; b < b1; ++b)
+    if (T.len[b] + n_tokens > ring_tokens(T)) return TTKV_ERR_CAPACITY;
+  const Layout L = make_layout(T, c->n_kv_heads);
+
+  ConvArgs a{};
+  a.s.k_flat = k_src;
+  a.s.v_flat = v_src;
+  a.s.flat_fmt = src_fmt;
+  a.s.from_tier = 0;
+  a.n_seq = b1 - b0;
+  a.Hkv = c->n_kv_heads;
+  a.n_tokens = (int32_t)n_tokens;
+  fill_via(a, c, tier, through != 0);
+
+  int max_touched = 0;
+  if (!host_variant) {
+    a.dst = make_view(T, L);
+    for (int b = b0; b < b1; ++b) {
+      const int j = b - b0;
+      a.seq_id[j] = b;
+      a.dst_rec_base[j] = (int32_t)((int64_t)b * T.ring_blocks);
+      a.dst_first_tok[j] = (int32_t)((T.start[b] + T.len[b]) % ring_tokens(T));
+    }
+  } else {
+    // quantize into workspace records laid out [entry][touched block], then copy rows out
+    for (int b = b0; b < b1; ++b) {
+      const int64_t o0 = T.start[b] + T.len[b];
+      max_touched = std::max<int>(max_touched, (int)((o0 + n_tokens - 1) / L.bt - o0 / L.bt + 1));
+    }
+    if (!workspace || ws_bytes < (size_t)a.n_seq * max_touched * L.rec_bytes) return TTKV_ERR_WORKSPACE;
+    if (T.ring_blocks < max_touched) return TTKV_ERR_CAPACITY;
+    a.dst = make_slot_view(T, L, workspace, max_touched);
+    for (int b = b0; b < b1; ++b) {
+      const int j = b - b0;
+      a.seq_id[j] = b;
+      a.dst_rec_base[j] = j * max_touched;
+      a.dst_first_tok[j] = (int32_t)((T.start[b] + T.len[b]) % L.bt);
+    }
+  }
+  int nk = 0;
+  TTKV_HIP(h, launch_convert(a, stream, &nk));
+  TTKV_HIP(h, run_summary(a, c, tier, stream, &nk));
+  h->stats.kernels += nk;
+  if (host_variant) {
+    for (int b = b0; b < b1; ++b) {
+      const int j = b - b0;
+      const int64_t o0 = T.start[b] + T.len[b];
+      for (int64_t id = o0 / L.bt; id <= (o0 + n_tokens - 1) / L.bt; ++id) {
+        const int lo = (int)std::max<int64_t>(o0 - id * L.bt, 0);
+        const int hi = (int)std::min<int64_t>(o0 + n_tokens - id * L.bt, L.bt);
+        uint8_t *host_rec = (uint8_t *)T.data + record_of(T, b, id % T.ring_blocks) * L.rec_bytes;
+        const uint8_t *dev_rec = (const uint8_t *)workspace + ((int64_t)j * max_touched + (id - o0 / L.bt)) * L.rec_bytes;
+        st = copy_rows_to_host(h, L, c->n_kv_heads, host_rec, dev_rec, lo, hi, stream);
+        if (st != TTKV_OK) return st;
+      }
+    }
+  }
+  for (int b = b0; b < b1; ++b) T.len[b] += n_tokens;
+  return TTKV_OK;
+}
+
+// Events are created on the first call that chains streams (on the device
+// current at that time), so that a handle can exist without a device.
+ttkv_status ensure_events(Handle *h) {
+  if (h->have_events) return TTKV_OK;
+  TTKV_HIP(h, hipGetDevice(&h->device));
+  for (int i = 0; i < TTKV_MAX_SLOTS; ++i) {
+    TTKV_HIP(h, hipEventCreateWithFlags(&h->ready[i], hipEventDisableTiming));
+    TTKV_HIP(h, hipEventCreateWithFlags(&h->freed[i], hipEventDisableTiming));
+  }
+  TTKV_HIP(h, hipEventCreateWithFlags(&h->fence, hipEventDisableTiming));
+  TTKV_HIP(h, hipEventCreateWithFlags(&h->fence2, hipEventDisableTiming));
+  h->have_events = true;
+  return TTKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ttkv_status ttkv_create(ttkv_handle *out) {
+  if (!out) return TTKV_ERR_INVALID_ARG;
+  Handle *h = new (std::nothrow) Handle();
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  h->have_events = false;
+  *out = reinterpret_cast<ttkv_handle>(h);
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_destroy(ttkv_handle hh) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  if (h->have_events) {
+    for (int i = 0; i < TTKV_MAX_SLOTS; ++i) {
+      (void)hipEventDestroy(h->ready[i]);
+      (void)hipEventDestroy(h->freed[i]);
+    }
+    (void)hipEventDestroy(h->fence);
+    (void)hipEventDestroy(h->fence2);
+  }
+  delete h;
+  return TTKV_OK;
+}
+
+void ttkv_get_stats(ttkv_handle hh, ttkv_stats *out) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (h && out) *out = h->stats;
+}
+void ttkv_reset_stats(ttkv_handle hh) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (h) h->stats = ttkv_stats{};
+}
+
+const char *ttkv_status_string(ttkv_status s) {
+  switch (s) {
+    case TTKV_OK: return "ok";
+    case TTKV_ERR_INVALID_ARG: return "invalid argument";
+    case TTKV_ERR_CAPACITY: return "tier capacity";
+    case TTKV_ERR_UNSUPPORTED: return "unsupported";
+    case TTKV_ERR_WORKSPACE: return "workspace too small";
+    case TTKV_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+size_t ttkv_record_bytes(const ttkv_cache *c, int32_t tier) {
+  if (!c || tier < 0 || tier >= c->n_tiers || tier >= TTKV_MAX_TIERS) return 0;
+  const ttkv_tier &T = c->tier[tier];
+  if (!is_tier_fmt(T.k_fmt) || !is_tier_fmt(T.v_fmt) || T.block_tokens <= 0 || c->n_kv_heads <= 0) return 0;
+  return (size_t)make_layout(T, c->n_kv_heads).rec_bytes;
+}
+
+ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *tier, int64_t *block_id, int32_t *row,
+                        int64_t *record) {
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (b < 0 || b >= c->batch || pos < 0) return TTKV_ERR_INVALID_ARG;
+  // tiers hold adjacent ranges, oldest tokens in the last tier
+  int64_t base = 0;
+  for (int t = c->n_tiers - 1; t >= 0; --t) {
+    const ttkv_tier &T = c->tier[t];
+    if (pos < base + T.len[b]) {
+      const int64_t o = T.start[b] + (pos - base);
+      if (tier) *tier = t;
+      if (block_id) *block_id = o / T.block_tokens;
+      if (row) *row = (int32_t)(o % T.block_tokens);
+      if (record) *record = record_of(T, b, (o / T.block_tokens) % T.ring_blocks);
+      return TTKV_OK;
+    }
+    base += T.len[b];
+  }
+  return TTKV_ERR_INVALID_ARG;
+}
+
+size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots) {
+  if (validate_cache(c) != TTKV_OK || max_parts < 1 || n_slots < 0 || n_slots > TTKV_MAX_SLOTS) return 0;
+  size_t slot = 0;
+  for (int t = 0; t < c->n_tiers; ++t)
+    if (c->tier[t].mem == TTKV_MEM_HOST_PINNED) {
+      const Layout L = make_layout(c->tier[t], c->n_kv_heads);
+      slot = std::max(slot, align256((size_t)copy_granule(L.rec_bytes) * L.rec_bytes));
+    }
+  const size_t rows = (size_t)c->batch * c->n_q_heads;
+  return (size_t)n_slots * slot + align256(rows * max_parts * 130 * sizeof(float)) + 256;
+}
+
+size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier) {
+  if (validate_cache(c) != TTKV_OK || src_tier < 0 || src_tier + 1 >= c->n_tiers) return 0;
+  const ttkv_tier &D = c->tier[src_tier + 1];
+  if (D.mem != TTKV_MEM_HOST_PINNED) return 0;
+  const Layout L = make_layout(D, c->n_kv_heads);
+  const int touched = c->tier[src_tier].block_tokens / D.block_tokens + 2;
+  return (size_t)c->batch * touched * L.rec_bytes;
+}
+
+size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32_t seq, int64_t n_tokens) {
+  if (validate_cache(c) != TTKV_OK || tier < 0 || tier >= c->n_tiers || n_tokens < 0) return 0;
+  const Layout L = make_layout(c->tier[tier], c->n_kv_heads);
+  const int64_t touched = n_tokens / L.bt + 2;
+  return (size_t)(seq < 0 ? c->batch : 1) * touched * L.rec_bytes;
+}
+
+int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride) {
+  if (validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
+  Plan P;
+  build_plan(c, sel_blocks, sel_count, sel_stride, &P);
+  return P.status == TTKV_OK ? P.max_parts : -1;
+}
+
+ttkv_status ttkv_quantize_append(ttkv_handle hh, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src,
+                                 const void *v_src, int32_t src_fmt, int64_t n_tokens, int32_t through_tiers,
+                                 void *stream) {
+  return append_impl(reinterpret_cast<Handle *>(hh), c, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, nullptr,
+                     0, (hipStream_t)stream, false);
+}
+
+ttkv_status ttkv_quantize_append_host(ttkv_handle hh, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src,
+                                      const void *v_src, int32_t src_fmt, int64_t n_tokens, int32_t through_tiers,
+                                      void *workspace, size_t ws_bytes, void *stream) {
+  return append_impl(reinterpret_cast<Handle *>(hh), c, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers,
+                     workspace, ws_bytes, (hipStream_t)stream, true);
+}
+
+ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, int32_t max_blocks, void *workspace,
+                             size_t ws_bytes, void *compute_, void *copy_) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (src_tier < 0 || src_tier + 1 >= c->n_tiers) return TTKV_ERR_INVALID_ARG;
+  ttkv_tier &S = c->tier[src_tier];
+  ttkv_tier &D = c->tier[src_tier + 1];
+  if (S.mem != TTKV_MEM_DEVICE) return TTKV_ERR_UNSUPPORTED;
+  if (is_fp(D.k_fmt) && D.k_fmt != S.k_fmt) return TTKV_ERR_UNSUPPORTED;
+  if (is_fp(D.v_fmt) && D.v_fmt != S.v_fmt) return TTKV_ERR_UNSUPPORTED;
+  hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
+  const Layout LS = make_layout(S, c->n_kv_heads), LD = make_layout(D, c->n_kv_heads);
+  const bool to_host = D.mem == TTKV_MEM_HOST_PINNED;
+
+  // how many blocks each sequence moves; check every ring before touching anything
+  int nmove[TTKV_MAX_BATCH], rounds = 0;
+  for (int b = 0; b < c->batch; ++b) {
+    int64_t len = S.len[b];
+    int n = 0;
+    while (len >= S.capacity_tokens && (max_blocks <= 0 || n < max_blocks)) {
+      if (len < LS.bt) return TTKV_ERR_CAPACITY;
+      len -= LS.bt;
+      ++n;
+    }
+    nmove[b] = n;
+    rounds = std::max(rounds, n);
+    if (D.len[b] + (int64_t)n * LS.bt > ring_tokens(D)) return TTKV_ERR_CAPACITY;
+  }
+  if (rounds == 0) return TTKV_OK;
+  const int touched = LS.bt / LD.bt + 2;
+  if (to_host && (!workspace || ws_bytes < (size_t)c->batch * touched * LD.rec_bytes)) return TTKV_ERR_WORKSPACE;
+  if (to_host && (st = ensure_events(h)) != TTKV_OK) return st;
+
+  for (int round = 0; round < rounds; ++round) {
+    ConvArgs a{};
+    a.s.from_tier = 1;
+    a.s.src = make_view(S, LS);
+    a.Hkv = c->n_kv_heads;
+    a.n_tokens = LS.bt;
+    a.n_via = 0;
+    a.dst = to_host ? make_slot_view(D, LD, workspace, touched) : make_view(D, LD);
+    for (int b = 0; b < c->batch; ++b) {
+      if (round >= nmove[b]) continue;
+      const int j = a.n_seq++;
+      a.seq_id[j] = b;
+      a.s.src_first_tok[j] = (int32_t)(S.start[b] % ring_tokens(S));
+      a.s.src_rec_base[j] = (int32_t)((int64_t)b * S.ring_blocks);
+      const int64_t o = D.start[b] + D.len[b];  // ordinal of the first row written
+      if (to_host) {
+        a.dst_rec_base[j] = j * touched;
+        a.dst_first_tok[j] = (int32_t)(o % LD.bt);
+      } else {
+        a.dst_rec_base[j] = (int32_t)((int64_t)b * D.ring_blocks);
+        a.dst_first_tok[j] = (int32_t)(o % ring_tokens(D));
+      }
+    }
+    int nk = 0;
+    TTKV_HIP(h, launch_convert(a, compute, &nk));
+    TTKV_HIP(h, run_summary(a, c, src_tier + 1, compute, &nk));
+    h->stats.kernels += nk;
+
+    if (to_host) {
+      TTKV_HIP(h, hipEventRecord(h->fence2, compute));
+      TTKV_HIP(h, hipStreamWaitEvent(copy, h->fence2, 0));
+    }
+    for (int j = 0; j < a.n_seq; ++j) {
+      const int b = a.seq_id[j];
+      if (to_host) {
+        const int64_t o0 = D.start[b] + D.len[b];
+        for (int64_t id = o0 / LD.bt; id <= (o0 + LS.bt - 1) / LD.bt; ++id) {
+          const int lo = (int)std::max<int64_t>(o0 - id * LD.bt, 0);
+          const int hi = (int)std::min<int64_t>(o0 + LS.bt - id * LD.bt, LD.bt);
+          uint8_t *host_rec = (uint8_t *)D.data + record_of(D, b, id % D.ring_blocks) * LD.rec_bytes;
+          const uint8_t *dev_rec = (const uint8_t *)workspace + ((int64_t)j * touched + (id - o0 / LD.bt)) * LD.rec_bytes;
+          st = copy_rows_to_host(h, LD, c->n_kv_heads, host_rec, dev_rec, lo, hi, copy);
+          if (st != TTKV_OK) return st;
+        }
+      }
+      S.start[b] += LS.bt;
+      S.len[b] -= LS.bt;
+      D.len[b] += LS.bt;
+      h->stats.demotions += 1;
+    }
+    if (to_host && round + 1 < rounds) {
+      // the staging records are reused by the next round: wait for the copies
+      TTKV_HIP(h, hipEventRecord(h->fence2, copy));
+      TTKV_HIP(h, hipStreamWaitEvent(compute, h->fence2, 0));
+    }
+  }
+  if (to_host) {
+    // later compute work (and the next step's fetches on `copy`) must see the host records complete;
+    // `copy` is ordered by itself, `compute` is released by this event
+    TTKV_HIP(h, hipEventRecord(h->fence2, copy));
+    TTKV_HIP(h, hipStreamWaitEvent(compute, h->fence2, 0));
+  }
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
+                             const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
+                             size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (!q || !out || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
+  st = check_sel(c, sel_blocks, sel_count, sel_stride);
+  if (st != TTKV_OK) return st;
+  if (n_slots < 0 || n_slots > TTKV_MAX_SLOTS) return TTKV_ERR_INVALID_ARG;
+  hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
+
+  Plan P;
+  build_plan(c, sel_blocks, sel_count, sel_stride, &P);
+  if (P.status != TTKV_OK) return P.status;
+  const bool any_host_fetch = std::any_of(P.fetch.begin(), P.fetch.end(), [&](const Fetch &f) { return c->tier[f.tier].mem == TTKV_MEM_HOST_PINNED; });
+  if (any_host_fetch && n_slots < 1) return TTKV_ERR_WORKSPACE;
+  if (!workspace) return TTKV_ERR_WORKSPACE;
+  // workspace = [n_slots staging slots][m][l][acc]
+  const size_t slots_bytes = (size_t)n_slots * P.slot_bytes;
+  const size_t rows = (size_t)c->batch * c->n_q_heads;
+  const size_t mis = (256 - ((uintptr_t)workspace & 255)) & 255;
+  if (ws_bytes < mis + slots_bytes) return TTKV_ERR_WORKSPACE;
+  const int64_t stride = (int64_t)((ws_bytes - mis - slots_bytes) / (rows * 130 * sizeof(float)));
+  if (stride < std::max(1, P.max_parts)) return TTKV_ERR_WORKSPACE;
+  const int32_t part_stride = (int32_t)std::min<int64_t>(stride, 1 << 20);
+  if (any_host_fetch && (st = ensure_events(h)) != TTKV_OK) return st;
+  uint8_t *ws = (uint8_t *)workspace + mis;
+  float *pm = (float *)(ws + slots_bytes);
+  float *pl = pm + rows * part_stride;
+  float *pacc = pl + rows * part_stride;
+
+  int nk = 0;
+  AttnArgs a{};
+  a.q = q;
+  a.q_fmt = q_fmt;
+  a.pm = pm; a.pl = pl; a.pacc = pacc;
+  a.part_stride = part_stride;
+  a.Hq = c->n_q_heads;
+  a.Hkv = c->n_kv_heads;
+  a.scale = c->softmax_scale;
+
+  if (any_host_fetch && copy != compute) {
+    // staging slots may still be read by earlier work on `compute`
+    TTKV_HIP(h, hipEventRecord(h->fence, compute));
+    TTKV_HIP(h, hipStreamWaitEvent(copy, h->fence, 0));
+  }
+  // device-resident tiers first: they run while the first host blocks are in flight
+  for (const DevLaunch &d : P.dev) {
+    const ttkv_tier &T = c->tier[d.tier];
+    a.tv = make_view(T, make_layout(T, c->n_kv_heads));
+    a.st = d.st;
+    a.chunk_tokens = d.chunk;
+    TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
+  }
+  // host-tier blocks (and selected blocks): copy i+1 overlaps compute on i
+  int issued = 0;
+  for (const Fetch &f : P.fetch) {
+    const ttkv_tier &T = c->tier[f.tier];
+    const Layout L = make_layout(T, c->n_kv_heads);
+    a.st = SeqTable{};
+    a.st.n_seq = 1;
+    a.st.seq_id[0] = f.b;
+    a.st.len[0] = f.ntok;
+    a.st.item_start[0] = 0;
+    a.st.item_start[1] = (f.ntok + f.chunk - 1) / f.chunk;
+    a.st.part_base[0] = f.part_base;
+    a.chunk_tokens = f.chunk;
+    if (T.mem == TTKV_MEM_HOST_PINNED) {
+      const int slot = issued % n_slots;
+      uint8_t *dst = ws + (size_t)slot * P.slot_bytes;
+      if (issued >= n_slots && copy != compute) TTKV_HIP(h, hipStreamWaitEvent(copy, h->freed[slot], 0));
+      const size_t bytes = (size_t)f.nrec * L.rec_bytes;
+      TTKV_HIP(h, hipMemcpyAsync(dst, (const uint8_t *)T.data + f.rec * L.rec_bytes, bytes, hipMemcpyHostToDevice, copy));
+      if (copy != compute) {
+        TTKV_HIP(h, hipEventRecord(h->ready[slot], copy));
+        TTKV_HIP(h, hipStreamWaitEvent(compute, h->ready[slot], 0));
+      }
+      a.tv = make_slot_view(T, L, dst, f.nrec);
+      a.st.rec_base[0] = 0;
+      a.st.first_tok[0] = 0;
+      TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
+      if (copy != compute) TTKV_HIP(h, hipEventRecord(h->freed[slot], compute));
+      h->stats.h2d_bytes += bytes;
+      h->stats.blocks_fetched += f.nrec;
+      ++issued;
+    } else {
+      // selected block of a device-resident last tier: attend it in place
+      a.tv = make_view(T, L);
+      a.tv.table = nullptr;
+      a.tv.ring_blocks = 1;
+      a.st.rec_base[0] = (int32_t)f.rec;
+      a.st.first_tok[0] = 0;
+      TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
+    }
+  }
+  MergeArgs m{};
+  m.m = pm; m.l = pl; m.acc = pacc;
+  m.n_parts = P.max_parts;
+  m.part_stride = part_stride;
+  m.rows = (int32_t)rows;
+  m.n_parts_row = nullptr;
+  m.rows_per_seq = c->n_q_heads;
+  for (int b = 0; b < c->batch; ++b) m.cnt[b] = P.parts[b];
+  m.out = out;
+  m.lse = lse;
+  TTKV_HIP(h, launch_merge(m, compute));
+  h->stats.kernels += nk + 1;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_merge_partials(ttkv_handle hh, const float *m, const float *l, const float *acc, int32_t n_parts,
+                                int32_t part_stride, const int32_t *n_parts_row, int32_t rows, float *out, float *lse,
+                                void *stream) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !m || !l || !acc || !out || n_parts < 0 || part_stride < n_parts || rows < 0) return TTKV_ERR_INVALID_ARG;
+  MergeArgs a{};
+  a.m = m; a.l = l; a.acc = acc;
+  a.n_parts = n_parts;
+  a.part_stride = part_stride;
+  a.rows = rows;
+  a.n_parts_row = n_parts_row;
+  a.rows_per_seq = 0;
+  a.out = out;
+  a.lse = lse;
+  TTKV_HIP(h, launch_merge(a, (hipStream_t)stream));
+  h->stats.kernels += rows > 0;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k,
+                               int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
+                               size_t scratch_bytes, void *stream_) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (!q || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16) || k < 0 || !sel_blocks || !sel_count || sel_stride < 1)
+    return TTKV_ERR_INVALID_ARG;
+  const ttkv_tier &T = c->tier[c->n_tiers - 1];
+  if (!T.k_summary) return TTKV_ERR_UNSUPPORTED;
+  hipStream_t stream = (hipStream_t)stream_;
+  SelectArgs a{};
+  a.q = q;
+  a.q_fmt = q_fmt;
+  a.k_summary = (const uint16_t *)T.k_summary;
+  a.table = T.block_table_dev;
+  a.ring_blocks = (int32_t)T.ring_blocks;
+  a.Hq = c->n_q_heads;
+  a.Hkv = c->n_kv_heads;
+  a.k = std::min(k, sel_stride);
+  a.sel_stride = sel_stride;
+  a.n_seq = c->batch;
+  a.max_blocks = 1;
+  for (int b = 0; b < c->batch; ++b) {
+    const int64_t first_id = T.start[b] / T.block_tokens;
+    const int64_t end_id = (T.start[b] + T.len[b] + T.block_tokens - 1) / T.block_tokens;
+    a.rec_base[b] = (int32_t)((int64_t)b * T.ring_blocks);
+    a.first_block[b] = (int32_t)(first_id % T.ring_blocks);
+    a.first_block_id[b] = first_id;
+    a.n_blocks[b] = (int32_t)(end_id - first_id);
+    a.max_blocks = std::max(a.max_blocks, a.n_blocks[b]);
+  }
+  if (a.max_blocks > 1024) return TTKV_ERR_UNSUPPORTED;
+  const size_t need = align256((size_t)c->batch * a.max_blocks * sizeof(float)) + (size_t)c->batch * (sel_stride + 1) * sizeof(int32_t);
+  if (!scratch || scratch_bytes < need) return TTKV_ERR_WORKSPACE;
+  a.scores = (float *)scratch;
+  a.sel_out = (int32_t *)((uint8_t *)scratch + align256((size_t)c->batch * a.max_blocks * sizeof(float)));
+  TTKV_HIP(h, launch_select(a, stream));
+  h->stats.kernels += 2;
+  // sel_out = [batch counts][batch][sel_stride ids]
+  TTKV_HIP(h, hipMemcpyAsync(sel_count, a.sel_out, (size_t)c->batch * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  TTKV_HIP(h, hipMemcpyAsync(sel_blocks, a.sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
+                             hipMemcpyDeviceToHost, stream));
+  TTKV_HIP(h, hipStreamSynchronize(stream));
+  return TTKV_OK;
+}
+
+}  // extern "C"

@@ -70,6 +70,7 @@ struct SeqTable {
 // ---------------------------------------------------------------- handle
 struct Handle {
   int device;
+  bool have_events;
   hipEvent_t ready[TTKV_MAX_SLOTS];
   hipEvent_t freed[TTKV_MAX_SLOTS];
   hipEvent_t fence;     // orders the copy stream behind earlier compute work
@@ -93,7 +94,7 @@ ttkv_status validate_cache(const ttkv_cache *c);
 
 // ---------------------------------------------------------------- launchers (defined in the .hip files)
 struct ConvSource {
-  // flat source [n_seq_total][Hkv][n][128] (tier == 0) or a tier view
+  // flat source [n_seq][Hkv][n][128] indexed by launch entry, or a tier view
   const void *k_flat, *v_flat;
   int32_t flat_fmt;
   int32_t from_tier;    // 0: flat source, 1: read rows of `src`
@@ -119,6 +120,7 @@ struct ConvArgs {
   float inv_bt;
 };
 hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels);
+hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels);
 
 struct AttnArgs {
   TierView tv;

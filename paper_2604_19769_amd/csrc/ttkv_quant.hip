@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const ConvArgs a) {
 
   float x[8];
   if (!a.s.from_tier) {
-    load8_flat(which ? a.s.v_flat : a.s.k_flat, a.s.flat_fmt, ((int64_t)seq * a.Hkv + h) * a.n_tokens + t, l16, x);
+    load8_flat(which ? a.s.v_flat : a.s.k_flat, a.s.flat_fmt, ((int64_t)j * a.Hkv + h) * a.n_tokens + t, l16, x);
   } else {
     int row;
     const uint8_t *head = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
   for (int t = 0; t < a.n_tokens; ++t) {
     float x[1];
     if (!a.s.from_tier) {
-      int64_t row = ((int64_t)seq * a.Hkv + h) * a.n_tokens + t;
+      int64_t row = ((int64_t)j * a.Hkv + h) * a.n_tokens + t;
       if (a.s.flat_fmt == TTKV_F32)
         x[0] = ((const float *)a.s.k_flat)[row * 128 + i];
       else {
@@ -282,14 +282,16 @@ hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
   dim3 grid((unsigned)((total + 15) / 16), 2);
   hipLaunchKernelGGL(convert_rows_kernel, grid, dim3(256), 0, s, a);
   ++*n_kernels;
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (a.k_sum) {
-    hipLaunchKernelGGL(summary_kernel, dim3(a.n_seq, a.Hkv), dim3(128), 0, s, a);
-    ++*n_kernels;
-    e = hipGetLastError();
-  }
-  return e;
+  return hipGetLastError();
+}
+
+// `a.dst` gives the destination ring geometry only (block_tokens, ring_blocks);
+// the kernel writes k_sum / k_summary, never dst.
+hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels) {
+  if (a.n_seq <= 0 || a.n_tokens <= 0 || !a.k_sum) return hipSuccess;
+  hipLaunchKernelGGL(summary_kernel, dim3(a.n_seq, a.Hkv), dim3(128), 0, s, a);
+  ++*n_kernels;
+  return hipGetLastError();
 }
 
 }  // namespace ttkv

@@ -1,0 +1,133 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function the
+header declares, sizes records as the format table says, and turns bad arguments
+into status codes before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_19769_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ttkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ttkv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    L = B.lib()
+    names = header_functions()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def host_cache(batch=2, Hq=8, Hkv=2, fmts=(("f16", "f16"), ("i8", "i8"), ("i4", "i4")), bt=(128, 128, 1024)):
+    """A descriptor whose pointers are host memory: good enough for everything that must fail before a launch."""
+    c = B.ttkv_cache()
+    c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_tiers = batch, Hq, Hkv, 128, len(fmts)
+    c.softmax_scale = 0.088
+    keep = []
+    for t, ((kf, vf), b) in enumerate(zip(fmts, bt)):
+        T = c.tier[t]
+        T.k_fmt, T.v_fmt, T.mem, T.block_tokens = B.FMT_NAMES[kf], B.FMT_NAMES[vf], B.MEM_DEVICE, b
+        T.capacity_tokens, T.ring_blocks, T.pool_blocks = 4 * b, 8, 8 * batch
+        buf = np.zeros(16, np.uint8)
+        s, l = np.zeros(batch, np.int64), np.zeros(batch, np.int64)
+        T.data, T.start, T.len = buf.ctypes.data, s.ctypes.data, l.ctypes.data
+        keep += [buf, s, l]
+    c._keep = keep
+    return c
+
+
+def test_record_bytes_follow_the_format_table():
+    c = host_cache(Hkv=8)
+    assert B.ttkv_record_bytes(c, 0) == 128 * 8 * 512          # fp16 K+V: 512 B per token-head
+    assert B.ttkv_record_bytes(c, 1) == 128 * 8 * 272          # int8 g32: 2 x (128 + 4 x 2)
+    assert B.ttkv_record_bytes(c, 2) == 1024 * 8 * 144 == 1179648   # int4 g64: 2 x (64 + 2 x 4)
+    c.tier[1].v_fmt = B.I4_ASYM_G64                              # K 8-bit / V 4-bit
+    assert B.ttkv_record_bytes(c, 1) == 128 * 8 * 208
+    assert B.ttkv_record_bytes(c, 3) == 0 and B.ttkv_record_bytes(c, -1) == 0
+
+
+def test_invalid_arguments_are_status_codes():
+    h = B.ttkv_create()
+    L = B.lib()
+    c = host_cache()
+    null = C.c_void_p()
+    dummy = C.c_void_p(c._keep[0].ctypes.data)
+    # NULL handle / NULL pointers
+    assert L.ttkv_decode_attn(None, C.byref(c), dummy, B.F16, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_attn(h, C.byref(c), None, B.F16, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_attn(h, C.byref(c), dummy, B.I8_SYM_G32, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_INVALID_ARG
+    # workspace too small for even one part
+    assert L.ttkv_decode_attn(h, C.byref(c), dummy, B.F16, dummy, None, None, None, 0, dummy, 64, 2, None, None) == B.ERR_WORKSPACE
+    # head_dim
+    c.head_dim = 64
+    assert L.ttkv_decode_attn(h, C.byref(c), dummy, B.F16, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_UNSUPPORTED
+    c.head_dim = 128
+    # unsupported format pair (V wider than K)
+    c.tier[1].k_fmt, c.tier[1].v_fmt = B.I4_ASYM_G64, B.I8_SYM_G32
+    assert L.ttkv_count_parts(C.byref(c), None, None, 0) == -1
+    assert L.ttkv_quantize_append(h, C.byref(c), 1, -1, dummy, dummy, B.F16, 4, 0, None) == B.ERR_UNSUPPORTED
+    c.tier[1].k_fmt = c.tier[1].v_fmt = B.I8_SYM_G32
+    # block_tokens not a multiple of 64, batch out of range, GQA ratio
+    c.tier[0].block_tokens = 100
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
+    c.tier[0].block_tokens = 128
+    c.batch = 65
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
+    c.batch = 2
+    c.n_q_heads = 7
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
+    c.n_q_heads = 8
+    # fp tier only takes its own format; ring overflow; bad tier / seq
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.BF16, 1, 0, None) == B.ERR_UNSUPPORTED
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 8 * 128 + 1, 0, None) == B.ERR_CAPACITY
+    assert L.ttkv_quantize_append(h, C.byref(c), 3, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, 2, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 0, 0, None) == B.OK     # nothing to do
+    # nothing is due: demote is a no-op; src tier out of range
+    assert L.ttkv_tier_demote(h, C.byref(c), 0, 0, None, 0, None, None) == B.OK
+    assert L.ttkv_tier_demote(h, C.byref(c), 2, 0, None, 0, None, None) == B.ERR_INVALID_ARG
+    # destination ring overflow is found before anything is enqueued
+    c._keep[2][:] = 4 * 128            # tier 0 len = capacity -> due
+    c._keep[5][:] = 8 * 128            # tier 1 ring full
+    assert L.ttkv_tier_demote(h, C.byref(c), 0, 0, None, 0, None, None) == B.ERR_CAPACITY
+    assert list(c._keep[2]) == [512, 512] and list(c._keep[5]) == [1024, 1024]    # no state change
+    # selection lists
+    c._keep[2][:] = 0
+    c._keep[5][:] = 0
+    cnt = np.array([3, 0], np.int32)
+    ids = np.zeros((2, 2), np.int32)
+    assert L.ttkv_count_parts(C.byref(c), ids.ctypes.data, cnt.ctypes.data, 2) == -1   # count > stride
+    assert L.ttkv_count_parts(C.byref(c), ids.ctypes.data, None, 2) == -1
+    # locate on an empty cache, merge argument checks
+    t = C.c_int32()
+    assert L.ttkv_locate(C.byref(c), 0, 0, C.byref(t), None, None, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_merge_partials(h, dummy, dummy, dummy, 4, 2, None, 1, dummy, None, None) == B.ERR_INVALID_ARG
+    assert B.status_string(B.ERR_CAPACITY) == "tier capacity"
+    B.ttkv_destroy(h)
+
+
+def test_locate_and_part_count_are_host_arithmetic():
+    c = host_cache(batch=1)
+    # tier 2 holds the oldest 2048 tokens (start ordinal 1024), tier 1 the next 300, tier 0 the newest 70
+    c._keep[7][0], c._keep[8][0] = 1024, 2048
+    c._keep[4][0], c._keep[5][0] = 256, 300
+    c._keep[1][0], c._keep[2][0] = 0, 70
+    assert B.ttkv_locate(c, 0, 0) == (2, 1, 0, 1)
+    assert B.ttkv_locate(c, 0, 2047) == (2, 2, 1023, 2)
+    assert B.ttkv_locate(c, 0, 2048) == (1, 2, 0, 2)
+    assert B.ttkv_locate(c, 0, 2048 + 299) == (1, 4, 43, 4)
+    assert B.ttkv_locate(c, 0, 2048 + 300 + 69) == (0, 0, 69, 0)
+    with pytest.raises(B.TTKVError):
+        B.ttkv_locate(c, 0, 2048 + 300 + 70)
+    assert B.ttkv_count_parts(c) >= 3
+    assert B.ttkv_workspace_bytes(c, 8, 2) >= 1 * 8 * 8 * 130 * 4

@@ -1,0 +1,224 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, same seeded
+inputs.  Codes / scales / zeros / fp bits / tier and block indices bit-exact;
+attention outputs within 2e-3 + 1e-2*|ref| (fp32 accumulation on the device,
+fp64 in the oracle)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2604_19769_amd import binding as B
+from paper_2604_19769_amd import synth
+from ttkv_testlib import Pair, assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def tiers3(dtype, fmts=(("i8", "i8"), ("i4", "i4")), caps=(256, 512), bts=(64, 128, 256), rings=(6, 8, 16), host=True,
+           summary=False, paged=False):
+    return [
+        dict(k_fmt=dtype, v_fmt=dtype, capacity=caps[0], block_tokens=bts[0], ring_blocks=rings[0]),
+        dict(k_fmt=fmts[0][0], v_fmt=fmts[0][1], capacity=caps[1], block_tokens=bts[1], ring_blocks=rings[1],
+             paged_seed=11 if paged else None),
+        dict(k_fmt=fmts[1][0], v_fmt=fmts[1][1], capacity=10**9, block_tokens=bts[2], ring_blocks=rings[2],
+             mem="host" if host else "device", summary=summary, paged_seed=12 if paged else None),
+    ]
+
+
+def edge_rows(dtype):
+    """Hand-made rows that exercise ties, clamping, degenerate and denormal-scale groups."""
+    rows = np.zeros((8, 128), np.float32)
+    rows[0, :] = 0.0                                            # all zero
+    rows[1, :] = 2.5                                            # constant
+    rows[2, ::32] = 127.0
+    rows[2, 1:9] = [0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 125.5]   # exact ties at scale 1
+    rows[3, :] = 0.01
+    rows[3, 7] = -50.0                                          # single outlier
+    rows[4, :64] = 3e-4
+    rows[4, 8] = 1e-4                                           # fp16-subnormal scale
+    rows[4, 64:] = 1e-9                                         # underflows to scale 0
+    rows[5, 0::2] = 15.0
+    rows[5, 3] = 7.5
+    rows[5, 5] = 0.5                                            # int4 ties: (x - 0) / 1
+    rows[6, :] = np.abs(synth.normal(synth.rng(5), 128, "f16"))
+    rows[6, 5] = -0.0                                           # zero minimum with a sign
+    rows[7, :] = np.arange(128) - 64.0
+    return synth.round_to(rows, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("fmt", [("i8", "i8"), ("i4", "i4"), ("i8", "i4")])
+def test_quantize_append_bit_exact(dtype, fmt):
+    """ttkv_quantize_append into a quantized tier: codes, scales and zeros equal the oracle's Q."""
+    n = 200                                       # spans 3 blocks of 64 + a ragged tail
+    tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=64, block_tokens=64, ring_blocks=2),
+             dict(k_fmt=fmt[0], v_fmt=fmt[1], capacity=10**9, block_tokens=64, ring_blocks=5)]
+    p = Pair(2, 4, 2, tiers, dtype)
+    try:
+        g = synth.rng(synth.SEED_BASE + 100)
+        k = synth.normal(g, (2, 2, n, 128), dtype) * synth.round_to(np.exp2(g.integers(-6, 6, (2, 2, n, 1))).astype(np.float32), dtype)
+        v = synth.normal(g, (2, 2, n, 128), dtype)
+        k = synth.round_to(k, dtype)
+        k[0, 0, :8] = edge_rows(dtype)
+        v[1, 1, 100:108] = edge_rows(dtype)
+        p.gpu.append(1, dev(k, dtype), dev(v, dtype))
+        for b in range(2):
+            p.ora.append(1, b, k[b], v[b], 0)
+        p.assert_state_equal()
+        # appending again continues at the tail (row 200 of the ring), one sequence only
+        k2, v2 = synth.normal(g, (2, 37, 128), dtype), synth.normal(g, (2, 37, 128), dtype)
+        p.gpu.append(1, dev(k2, dtype), dev(v2, dtype), seq=1)
+        p.ora.append(1, 1, k2, v2, n)
+        p.assert_state_equal()
+    finally:
+        p.close()
+
+
+def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None,
+               lens=None, peaked=False):
+    p = Pair(B_, Hq, Hkv, tiers, dtype)
+    worst = 0.0
+    try:
+        g = synth.rng(seed)
+        for b in range(B_):
+            n = N if lens is None else lens[b]
+            k, v = synth.kv(seed * 31 + b, Hkv, n, dtype)
+            if peaked:                                      # a few keys aligned with q -> O(1) outputs
+                k[:, ::97] *= 4.0
+                k = synth.round_to(k, dtype)
+            p.load(b, k, v)
+        p.assert_state_equal()
+        for s in range(steps):
+            q = synth.normal(g, (B_, Hq, 128), dtype)
+            kn, vn = synth.normal(g, (B_, Hkv, 128), dtype), synth.normal(g, (B_, Hkv, 128), dtype)
+            r = p.step(q, kn, vn, select_k, overlap)
+            worst = max(worst, assert_close(r[0], r[2], f"out step {s}"))
+            assert_close(r[1], r[3], f"lse step {s}")
+            if select_k is not None:
+                for b in range(B_):
+                    assert np.array_equal(r[4][b], r[5][b]), (s, b, r[4][b], r[5][b])
+            if check_state_every and (s + 1) % check_state_every == 0:
+                p.assert_state_equal()
+        p.assert_state_equal()
+        for b in range(B_):
+            total = sum(int(p.gpu.len[t][b]) for t in range(len(tiers)))
+            p.assert_locate_equal(b, np.unique(np.concatenate([[0, total - 1], synth.rng(seed + b).integers(0, total, 64)])))
+        st = p.gpu.stats()
+        assert st["h2d_bytes"] == p.ora.h2d_bytes and st["blocks_fetched"] == p.ora.blocks_fetched
+        assert st["demotions"] == sum(sum(d) for d in p.ora.demotions)
+    finally:
+        p.close()
+    return worst
+
+
+def test_config1_tiny_fp16_plus_int8():
+    """batch 1, 8 q / 2 kv heads, 4096 tokens: last 512 fp16, older 3584 int8 g32, all in HBM, one step."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=512, block_tokens=128, ring_blocks=5),
+             dict(k_fmt="i8", v_fmt="i8", capacity=10**9, block_tokens=128, ring_blocks=30)]
+    run_config(1, 8, 2, tiers, "f16", 4095, 1, synth.SEED_BASE + 1)
+
+
+@pytest.mark.parametrize("fmt", [("f16", "f16"), ("i8", "i4"), ("i4", "i4")])
+def test_config1_shape_other_slow_formats(fmt):
+    """Same shape with the slow tier all-fp16 (exact attention), K 8-bit / V 4-bit (the paper's choice), int4."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=512, block_tokens=128, ring_blocks=5),
+             dict(k_fmt=fmt[0], v_fmt=fmt[1], capacity=10**9, block_tokens=128, ring_blocks=30)]
+    run_config(1, 8, 2, tiers, "f16", 4095, 2, synth.SEED_BASE + 2, peaked=True)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (8, 1), (12, 4)])
+def test_gqa_ratios_and_ragged_lengths(Hq, Hkv):
+    """Group sizes 1, 2, 8 (two passes of 4), 3; lengths that are not multiples of a tile or a block."""
+    run_config(3, Hq, Hkv, tiers3("bf16", host=False), "bf16", None, 3, synth.SEED_BASE + 3 + Hq, lens=[1, 777, 2500])
+
+
+def test_three_tiers_with_host_streaming_and_eviction_cascade():
+    """fp16 -> int8 (HBM) -> int4 (pinned host, streamed block by block): 150 steps cross several
+    evictions of both device tiers; state compared along the way."""
+    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150, synth.SEED_BASE + 4, check_state_every=50)
+
+
+def test_host_tier_no_overlap_gives_the_same_result():
+    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 3, synth.SEED_BASE + 4, overlap=False)
+
+
+def test_paged_tiers_with_ragged_batch():
+    """Shuffled block tables (paged KV) on the int8 and host tiers, ragged contexts."""
+    run_config(4, 8, 2, tiers3("f16", paged=True, rings=(6, 8, 12)), "f16", None, 70, synth.SEED_BASE + 5,
+               lens=[300, 1500, 2900, 2047], check_state_every=35)
+
+
+def test_sparse_block_selection():
+    """Block identification: mean-key summaries, phi, top-k; only selected host blocks are fetched."""
+    tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
+    run_config(2, 8, 2, tiers, "bf16", 3500, 40, synth.SEED_BASE + 6, select_k=6, check_state_every=20)
+
+
+def test_summaries_match_the_oracle_bit_for_bit():
+    tiers = tiers3("f16", summary=True, bts=(64, 128, 256), rings=(6, 8, 16))
+    p = Pair(1, 8, 2, tiers, "f16")
+    try:
+        k, v = synth.kv(synth.SEED_BASE + 7, 2, 2500, "f16")
+        p.load(0, k, v)
+        g = synth.rng(7)
+        for s in range(130):
+            p.step(synth.normal(g, (1, 8, 128), "f16"), synth.normal(g, (1, 2, 128), "f16"), synth.normal(g, (1, 2, 128), "f16"))
+        want = p.ora.summaries(0)
+        assert len(want) >= 7
+        for blk, mu in want.items():
+            assert np.array_equal(p.gpu.dump_summary(2, 0, blk), mu), blk
+    finally:
+        p.close()
+
+
+def test_merge_partials_standalone():
+    """ttkv_merge_partials against the oracle's merge: random partials, empty parts, ragged part counts."""
+    g = synth.rng(synth.SEED_BASE + 8)
+    rows, P, stride = 37, 19, 24
+    m = (g.standard_normal((rows, stride)) * 5).astype(np.float32)
+    l = (g.random((rows, stride)) * 50 + 0.1).astype(np.float32)
+    acc = (g.standard_normal((rows, stride, 128)) * 30).astype(np.float32)
+    m[3, 4] = -np.inf
+    l[3, 4] = 0
+    acc[3, 4] = 0
+    m[5, :] = -np.inf
+    l[5, :] = 0
+    acc[5] = 0
+    cnt = g.integers(1, P + 1, rows).astype(np.int32)
+    cnt[7] = 0
+    h = B.ttkv_create()
+    try:
+        for counts in (None, cnt):
+            out = torch.empty(rows, 128, dtype=torch.float32, device="cuda:0")
+            lse = torch.empty(rows, dtype=torch.float32, device="cuda:0")
+            B.ttkv_merge_partials(h, torch.from_numpy(m).cuda(), torch.from_numpy(l).cuda(), torch.from_numpy(acc).cuda(), P, stride,
+                                  None if counts is None else torch.from_numpy(counts).cuda(), rows, out, lse, None)
+            torch.cuda.synchronize()
+            for r in range(rows):
+                n = P if counts is None else int(counts[r])
+                acc_p = O.empty_partial(1, 128)
+                for i in range(n):
+                    O.merge_into(acc_p, (m[r, i:i + 1].astype(np.float64), l[r, i:i + 1].astype(np.float64),
+                                         acc[r, i:i + 1].astype(np.float64)))
+                ro, rl = O.finalize(acc_p)
+                got = out[r].cpu().numpy()
+                assert np.max(np.abs(got - ro[0])) <= 1e-5 * (1 + np.max(np.abs(ro[0]))), r
+                gl = float(lse[r])
+                assert (gl == rl[0]) if not np.isfinite(rl[0]) else abs(gl - rl[0]) < 1e-5 * (1 + abs(rl[0])), r
+    finally:
+        B.ttkv_destroy(h)
+
+
+def test_capacity_error_leaves_state_untouched():
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=64, block_tokens=64, ring_blocks=1)]
+    p = Pair(1, 2, 2, tiers, "f16")
+    try:
+        k = dev(np.zeros((1, 2, 64, 128), np.float32), "f16")
+        p.gpu.append(0, k, k)
+        with pytest.raises(B.TTKVError) as e:
+            p.gpu.append(0, k[:, :, :1].contiguous(), k[:, :, :1].contiguous())
+        assert e.value.status == B.ERR_CAPACITY and int(p.gpu.len[0][0]) == 64
+    finally:
+        p.close()

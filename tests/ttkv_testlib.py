@@ -1,0 +1,101 @@
+"""Shared helpers of the GPU parity tests: build the device cache and the oracle
+cache from one description, feed both the same seeded inputs, compare."""
+import numpy as np
+import torch
+
+import oracle as O
+from oracle import OracleCache, TierSpec
+from paper_2604_19769_amd import synth
+from paper_2604_19769_amd.cache import TierConfig, TieredCache
+
+TORCH_DT = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+# |gpu - oracle| <= ABS_TOL + REL_TOL * |oracle|, element-wise, on fp32-accumulated outputs
+ABS_TOL, REL_TOL = 2e-3, 1e-2
+
+
+def dev(x, dtype, device="cuda:0"):
+    """float32 numpy values (representable in dtype) -> device tensor of dtype."""
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(device).to(TORCH_DT[dtype]).contiguous()
+
+
+class Pair:
+    """tiers: list of dicts(k_fmt, v_fmt, capacity, block_tokens, ring_blocks, mem, paged_seed, summary)."""
+
+    def __init__(self, B, Hq, Hkv, tiers, dtype, oracle_max_tokens=None, n_slots=2):
+        self.B, self.Hq, self.Hkv, self.dtype = B, Hq, Hkv, dtype
+        self.tiers = tiers
+        self.gpu = TieredCache(B, Hq, Hkv, [TierConfig(t["k_fmt"], t["v_fmt"], t["capacity"], t["block_tokens"],
+                                                        t["ring_blocks"], t.get("mem", "device"), t.get("paged_seed"),
+                                                        t.get("summary", False)) for t in tiers], n_slots=n_slots)
+        if oracle_max_tokens is None:
+            oracle_max_tokens = [t["ring_blocks"] * t["block_tokens"] * 4 for t in tiers]
+        self.ora = OracleCache(B, Hq, Hkv, 128,
+                               [TierSpec(t["k_fmt"], t["v_fmt"], t["capacity"], t["block_tokens"], t.get("mem", "device"),
+                                         t.get("summary", False)) for t in tiers], oracle_max_tokens)
+
+    def close(self):
+        self.gpu.close()
+
+    # -------------------------------------------------------------- feeding
+    def load(self, b, k, v):
+        """Bulk initial state of sequence b from k, v [Hkv][N][128] (float32, representable in dtype)."""
+        spans = self.ora.load(b, k, v)
+        for t in reversed(range(len(self.tiers))):
+            lo, hi = spans[t]
+            if hi > lo:
+                self.gpu.append(t, dev(k[:, lo:hi], self.dtype), dev(v[:, lo:hi], self.dtype), seq=b, through_tiers=True)
+        return spans
+
+    def step(self, q, k_new, v_new, select_k=None, overlap=True):
+        """q [B][Hq][128], k_new/v_new [B][Hkv][128] float32.  Returns (gpu_out, gpu_lse, ora_out, ora_lse[, sel])."""
+        res = self.ora.step(q, k_new, v_new, select_k)
+        out, lse = self.gpu.step(dev(q, self.dtype), dev(k_new[:, :, None, :], self.dtype), dev(v_new[:, :, None, :], self.dtype),
+                                 select_k, overlap)
+        torch.cuda.synchronize()
+        r = (out.cpu().numpy().copy(), lse.cpu().numpy().copy(), res[0], res[1])
+        if select_k is not None:
+            sb, sc = self.gpu.sel_blocks.numpy(), self.gpu.sel_count.numpy()
+            r = r + ([sb[b, :sc[b]].copy() for b in range(self.B)], res[2])
+        return r
+
+    # -------------------------------------------------------------- comparing
+    def assert_state_equal(self):
+        """Codes, scales, zeros, fp bits and tier/block indices: bit-exact."""
+        for t, spec in enumerate(self.tiers):
+            for b in range(self.B):
+                s = self.ora.seq[t][b]
+                assert int(self.gpu.len[t][b]) == s.count, (t, b, int(self.gpu.len[t][b]), s.count)
+                assert int(self.gpu.start[t][b]) == s.first, (t, b)
+                if s.count == 0:
+                    continue
+                d = self.gpu.dump_tier(t, b)
+                sl = slice(s.first, s.first + s.count)
+                for name, fmt, hat, q in (("k", spec["k_fmt"], s.khat, s.kq), ("v", spec["v_fmt"], s.vhat, s.vq)):
+                    if fmt in ("f16", "bf16"):
+                        want = synth.to_bits(hat[:, sl], fmt)
+                        assert np.array_equal(d[name].view(np.uint16), want), (t, b, name, "fp bits")
+                    elif fmt == "i8":
+                        assert np.array_equal(d[name], q["codes"][:, sl].view(np.uint8)), (t, b, name, "codes")
+                        assert np.array_equal(d[name + "_meta"].view(np.uint16), q["scale"][:, sl]), (t, b, name, "scale")
+                    else:
+                        assert np.array_equal(d[name], q["codes"][:, sl]), (t, b, name, "codes")
+                        meta = d[name + "_meta"].view(np.uint16)
+                        assert np.array_equal(meta[:, :, 0::2], q["scale"][:, sl]), (t, b, name, "scale")
+                        assert np.array_equal(meta[:, :, 1::2], q["zero"][:, sl]), (t, b, name, "zero")
+
+    def assert_locate_equal(self, b, positions):
+        for pos in positions:
+            t, blk, row, _ = self.gpu.locate(b, int(pos))
+            assert (t, blk, row) == tuple(int(x) for x in self.ora.locate(b, int(pos))), pos
+
+
+def assert_close(gpu, ora, what=""):
+    gpu = np.asarray(gpu, np.float64)
+    ora = np.asarray(ora, np.float64)
+    fin = np.isfinite(ora)
+    assert np.array_equal(np.isfinite(gpu), fin), what
+    err = np.abs(gpu[fin] - ora[fin])
+    lim = ABS_TOL + REL_TOL * np.abs(ora[fin])
+    assert np.all(err <= lim), f"{what}: max err {err.max():.3e} (max |ref| {np.abs(ora[fin]).max():.3e}, worst ratio {(err / lim).max():.3f})"
+    return float(err.max())
