@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiered decode-attention hot path on one MI355X.
+
+A step = append the new token's K/V -> streaming decode attention over every
+tier (split-K partials + log-sum-exp merge) -> evict when the fast tier is full
+(Alg. 1 of the TTKV paper).  Inputs are seeded synthetic tensors resident in HBM
+(and, for the offload workload, in pinned host memory, which is where the
+method keeps its slow tier) before the timed region starts.
+
+Main workload `mha32k`: batch 4, 32 heads (MHA), head_dim 128, 32K context,
+recent 2K fp16 + 30K int4 (group 64, scale+zero), all in HBM -- the HBM-bound
+configuration.  Extra object `offload_128k`: batch 1, 32 q / 8 kv heads, 128K
+context, 4K bf16 + 28K int8 in HBM + 96K int4 in pinned host DRAM streamed in
+1024-token blocks -- the PCIe-bound configuration (microseconds per token).
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+PCIE_PEAK_GBS = 64.0        # PCIe Gen5 x16 per direction, nominal
+SEED = 1976900
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k"])
+    ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--offload-steps", type=int, default=20)
+    return ap.parse_args()
+
+
+def device_normal(gen, shape, dtype):
+    import torch
+    return torch.randn(shape, generator=gen, device=gen.device, dtype=torch.float32).to(dtype)
+
+
+def sync_time():
+    import torch
+    torch.cuda.synchronize()
+    return time.perf_counter()
+
+
+def timed_steps(cache, q, kn, vn, first, count, overlap=True, keep=None):
+    """Run steps [first, first+count) and return seconds, bracketed by full synchronisation."""
+    t0 = sync_time()
+    for s in range(first, first + count):
+        out, lse = cache.step(q[s], kn[s], vn[s], overlap=overlap)
+        if keep is not None:
+            keep.append(out.clone())
+    return sync_time() - t0
+
+
+# ------------------------------------------------------------------ workload: MHA 32K, int4 in HBM
+
+def build_mha32k(steps_total):
+    import numpy as np
+    import torch
+    from paper_2604_19769_amd import synth
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    B, H, N, R, bt = 4, 32, 32768, 2048, 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 2)
+    tiers = [TierConfig("f16", "f16", R, bt, R // bt + 1),
+             TierConfig("i4", "i4", 10**9, bt, (N - R) // bt + 2 + steps_total // bt + 1)]
+    cache = TieredCache(B, H, H, tiers)
+    K = torch.randn((B, H, N - 1, 128), generator=gen, device=dev, dtype=torch.float32)
+    V = torch.randn((B, H, N - 1, 128), generator=gen, device=dev, dtype=torch.float32)
+    outl = synth.outlier_channels(synth.rng(SEED + 2), H, 128, 0.02)      # 82 (head, channel) pairs, x8 on K
+    for h, ch in outl:
+        K[:, h, :, ch] *= 8.0
+    K, V = K.to(torch.float16), V.to(torch.float16)
+    n_old = N - R                                                       # 30720 tokens -> int4 tier
+    cache.append(1, K[:, :, :n_old].contiguous(), V[:, :, :n_old].contiguous(), through_tiers=True)
+    cache.append(0, K[:, :, n_old:].contiguous(), V[:, :, n_old:].contiguous())
+    q = device_normal(gen, (steps_total, B, H, 128), torch.float16)
+    kn = device_normal(gen, (steps_total, B, H, 1, 128), torch.float16)
+    vn = device_normal(gen, (steps_total, B, H, 1, 128), torch.float16)
+    for h, ch in outl:
+        kn[:, :, h, :, ch] *= 8.0
+    torch.cuda.synchronize()
+    return cache, (K, V), (q, kn, vn), dict(B=B, Hq=H, Hkv=H, N=N, R=R, bt=bt)
+
+
+def algorithmic_bytes(cache):
+    """Stored bytes the step must read: codes + scales + zeros + fp K/V of every live token."""
+    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72}
+    total, by_tier = 0, []
+    for t, cfg in enumerate(cache.cfg):
+        n = int(cache.len[t].sum()) * cache.Hkv * (per[cfg.k_fmt] + per[cfg.v_fmt])
+        by_tier.append(n)
+        total += n
+    return total, by_tier
+
+
+def cpu_baseline_mha32k(kv, steps, shape, gpu_outs):
+    """The oracle as it stands, timed on this machine's host cores on the same workload (whole batch, 2 steps)."""
+    import numpy as np
+    import oracle as O
+    from oracle import OracleCache, TierSpec
+    K, V = kv
+    q, kn, vn = steps
+    B, H, N, R, bt = shape["B"], shape["Hq"], shape["N"], shape["R"], shape["bt"]
+    cores = len(os.sched_getaffinity(0))
+    ora = OracleCache(B, H, H, 128, [TierSpec("f16", "f16", R, bt), TierSpec("i4", "i4", 10**9, bt)], [R + bt, N + bt])
+    for b in range(B):
+        ora.load(b, K[b].float().cpu().numpy(), V[b].float().cpu().numpy())
+    n_steps, secs, bytes_, err = 2, 0.0, 0, 0.0
+    for s in range(n_steps):
+        qs = q[s].float().cpu().numpy()
+        ks, vs = kn[s, :, :, 0].float().cpu().numpy(), vn[s, :, :, 0].float().cpu().numpy()
+        # same accounting as the GPU line: stored bytes of every token the step attends (incl. the new one)
+        bytes_ += sum((ora.seq[0][b].count + 1) * H * 512 + ora.seq[1][b].count * H * 144 for b in range(B))
+        t0 = time.perf_counter()
+        out, _ = ora.step(qs, ks, vs)
+        secs += time.perf_counter() - t0
+        g = gpu_outs[s].cpu().numpy()
+        err = max(err, float(np.max(np.abs(g - out) / (2e-3 + 1e-2 * np.abs(out)))))
+    return {"value": round(bytes_ / secs / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"whole workload (batch {B}, {H} heads, {N} tokens), {n_steps} decode steps incl. append+evict",
+            "ms_per_step": round(secs / n_steps * 1e3, 1), "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
+
+
+# ------------------------------------------------------------------ workload: 128K offload
+
+def build_offload128k(steps_total):
+    import torch
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    B, Hq, Hkv, N = 1, 32, 8, 131072
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 3)
+    tiers = [TierConfig("bf16", "bf16", 4096, 128, 33),
+             TierConfig("i8", "i8", 28672, 128, 28672 // 128 + 2),
+             TierConfig("i4", "i4", 10**9, 1024, 98304 // 1024 + 2, mem="host")]
+    cache = TieredCache(B, Hq, Hkv, tiers)
+    K = device_normal(gen, (B, Hkv, N - 1, 128), torch.bfloat16)
+    V = device_normal(gen, (B, Hkv, N - 1, 128), torch.bfloat16)
+    a, b = 98304, 98304 + 28672
+    cache.append(2, K[:, :, :a].contiguous(), V[:, :, :a].contiguous(), through_tiers=True)
+    cache.append(1, K[:, :, a:b].contiguous(), V[:, :, a:b].contiguous(), through_tiers=True)
+    cache.append(0, K[:, :, b:].contiguous(), V[:, :, b:].contiguous())
+    q = device_normal(gen, (steps_total, B, Hq, 128), torch.bfloat16)
+    kn = device_normal(gen, (steps_total, B, Hkv, 1, 128), torch.bfloat16)
+    vn = device_normal(gen, (steps_total, B, Hkv, 1, 128), torch.bfloat16)
+    torch.cuda.synchronize()
+    return cache, (K, V), (q, kn, vn), dict(B=B, Hq=Hq, Hkv=Hkv, N=N)
+
+
+def measure_h2d_peak():
+    """Pinned host -> device copy rate of one 1 GiB hipMemcpyAsync (what the link delivers at best)."""
+    import torch
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    dst.copy_(src, non_blocking=True)
+    t0 = sync_time()
+    for _ in range(3):
+        dst.copy_(src, non_blocking=True)
+    dt = (sync_time() - t0) / 3
+    return n / dt / 1e9
+
+
+def copy_only_seconds(cache, reps):
+    """The step's host-tier copies alone (same sizes, same pinned pool, one stream)."""
+    import torch
+    rec = cache.record_bytes(2)
+    nblk = int((cache.len[2][0] + 1023) // 1024)
+    slots = [torch.empty(rec, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    pool = cache.pool[2]
+    t0 = sync_time()
+    for _ in range(reps):
+        for i in range(nblk):
+            slots[i % 2].copy_(pool[i * rec:(i + 1) * rec], non_blocking=True)
+    return (sync_time() - t0) / reps
+
+
+def run_offload128k(steps, warmup):
+    cache, _, (q, kn, vn), shape = build_offload128k(2 * (steps + warmup) + 4)
+    try:
+        timed_steps(cache, q, kn, vn, 0, warmup)
+        total, by_tier = algorithmic_bytes(cache)
+        cache_stats0 = cache.stats()
+        t_overlap = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        st = cache.stats()
+        h2d_per_step = (st["h2d_bytes"] - cache_stats0["h2d_bytes"]) / steps
+        t_serial = timed_steps(cache, q, kn, vn, warmup + steps, steps, overlap=False) / steps
+        t_copy = copy_only_seconds(cache, 5)
+        t_compute = max(t_serial - t_copy, 1e-9)
+        overlap = (t_copy + t_compute - t_overlap) / min(t_copy, t_compute)
+        peak = measure_h2d_peak()
+        return {
+            "workload": "batch 1, 32 q / 8 kv heads, 131072 tokens: 4K bf16 + 28K int8 in HBM, 96K int4 in pinned host "
+                        "DRAM streamed in 1024-token blocks",
+            "us_per_token": round(t_overlap * 1e6, 1),
+            "us_per_token_no_overlap": round(t_serial * 1e6, 1),
+            "host_tier_bytes_per_step": int(h2d_per_step),
+            "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
+            "pcie_h2d_GBs": round(h2d_per_step / t_overlap / 1e9, 2),
+            "pcie_frac_of_nominal_64": round(h2d_per_step / t_overlap / 1e9 / PCIE_PEAK_GBS, 4),
+            "pcie_measured_peak_GBs": round(peak, 2),
+            "pcie_frac_of_measured_peak": round(h2d_per_step / t_overlap / 1e9 / peak, 4),
+            "copy_only_us": round(t_copy * 1e6, 1),
+            "overlap_fraction": round(overlap, 4),
+            "effective_kv_GBs": round(total / t_overlap / 1e9, 2),
+        }
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ main
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_19769_amd import binding as B
+    B.lib()      # fails loudly if the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    W, K = args.warmup, args.steps
+
+    if args.workload == "offload128k":
+        r = run_offload128k(K, W)
+        line = {"metric": "decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K", "value": r["effective_kv_GBs"],
+                "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(r["us_per_token"] / 1e3, 4),
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16/int8/int4 -> f32",
+                "data": "synthetic", "config": {"workload": "offload128k: " + r["workload"]}, "offload_128k": r,
+                "roofline": {"bound": "pcie", "achieved": r["pcie_h2d_GBs"], "peak": PCIE_PEAK_GBS, "unit": "GB/s",
+                             "frac": r["pcie_frac_of_nominal_64"], "traffic": None}}
+        print(json.dumps(line))
+        return
+
+    cache, kv, steps_in, shape = build_mha32k(W + K)
+    q, kn, vn = steps_in
+    keep = []
+    B.ttkv_time_tier(cache.h, 1, W + K)
+    timed_steps(cache, q, kn, vn, 0, W, keep=keep)
+    B.ttkv_read_tier_timing(cache.h)                       # drop warm-up samples
+    total_bytes, by_tier = algorithmic_bytes(cache)        # state at the start of the timed region
+    secs = timed_steps(cache, q, kn, vn, W, K)
+    kernel_ms = B.ttkv_read_tier_timing(cache.h)
+    total_bytes_end, by_tier_end = algorithmic_bytes(cache)
+    step_bytes = (total_bytes + total_bytes_end) / 2 + shape["B"] * shape["Hkv"] * 512   # + the appended token
+    ms = secs / K * 1e3
+    value = step_bytes / (secs / K) / 1e9
+    kms = sum(kernel_ms) / len(kernel_ms)
+    k_bytes = (by_tier[1] + by_tier_end[1]) / 2
+    roofline = {"bound": "hbm", "kernel": "attn_partial_kernel<int4,int4,G=1> over the int4 tier",
+                "achieved": round(k_bytes / (kms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(k_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel_us": round(kms * 1e3, 2), "bytes_per_launch": int(k_bytes), "launches_timed": len(kernel_ms)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline_mha32k(kv, steps_in, shape, keep[:2])
+    cache.close()
+    del cache, kv
+    torch.cuda.empty_cache()
+    off = None
+    if not args.no_offload:
+        off = run_offload128k(args.offload_steps, 3)
+    line = {
+        "metric": "decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16/int4 -> f32", "data": "synthetic",
+        "config": {"workload": "mha32k: batch 4, 32 heads MHA, head_dim 128, 32768 tokens, recent 2048 fp16 + 30720 int4 "
+                               "(group 64, asymmetric) in HBM, append + attend + evict per step",
+                   "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -203,6 +203,16 @@ ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q
                                int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
                                size_t scratch_bytes, void *stream);
 
+/* Measurement aid (roofline of one kernel, Sec. 5.1 item 4 "latency is measured on
+ * the GPU with events"): from now on every ttkv_decode_attn records a HIP event
+ * pair around the partial kernel of device tier `tier` on its compute stream, for
+ * at most max_samples calls (<= 4096).  tier < 0 switches it off.  Creates HIP
+ * events only.  ttkv_read_tier_timing BLOCKS until the recorded kernels have
+ * finished, writes their durations in milliseconds (oldest first, at most
+ * `capacity`), returns the count in *n_out and clears the samples. */
+ttkv_status ttkv_time_tier(ttkv_handle h, int32_t tier, int32_t max_samples);
+ttkv_status ttkv_read_tier_timing(ttkv_handle h, float *ms, int32_t capacity, int32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

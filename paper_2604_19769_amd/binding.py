@@ -45,7 +45,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
-    "ttkv_merge_partials", "ttkv_select_blocks",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_tier", "ttkv_read_tier_timing",
 ]
 
 _lib = None
@@ -91,6 +91,8 @@ def lib():
         L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
+        L.ttkv_time_tier.argtypes = [p, i32, i32]
+        L.ttkv_read_tier_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
         for name in EXPORTS:
             f = getattr(L, name)
             if name not in ("ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
@@ -197,3 +199,14 @@ def ttkv_merge_partials(h, m, l, acc, n_parts, part_stride, n_parts_row, rows, o
 def ttkv_select_blocks(h, cache, q, q_fmt, k, sel_blocks, sel_count, sel_stride, scratch, scratch_bytes, stream):
     _check(lib().ttkv_select_blocks(h, C.byref(cache), _p(q), q_fmt, k, _p(sel_blocks), _p(sel_count), sel_stride,
                                     _p(scratch), scratch_bytes, _p(stream)), "ttkv_select_blocks")
+
+
+def ttkv_time_tier(h, tier, max_samples):
+    _check(lib().ttkv_time_tier(h, tier, max_samples), "ttkv_time_tier")
+
+
+def ttkv_read_tier_timing(h, capacity=4096):
+    ms = (C.c_float * capacity)()
+    n = C.c_int32()
+    _check(lib().ttkv_read_tier_timing(h, ms, capacity, C.byref(n)), "ttkv_read_tier_timing")
+    return [ms[i] for i in range(n.value)]

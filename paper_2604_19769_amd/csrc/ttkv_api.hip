@@ -351,6 +351,9 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   Handle *h = new (std::nothrow) Handle();
   if (!h) return TTKV_ERR_INVALID_ARG;
   h->have_events = false;
+  h->time_tier = -1;
+  h->time_max = h->time_n = 0;
+  h->time_ev = nullptr;
   *out = reinterpret_cast<ttkv_handle>(h);
   return TTKV_OK;
 }
@@ -366,6 +369,8 @@ ttkv_status ttkv_destroy(ttkv_handle hh) {
     (void)hipEventDestroy(h->fence);
     (void)hipEventDestroy(h->fence2);
   }
+  for (int i = 0; i < 2 * h->time_max; ++i) (void)hipEventDestroy(h->time_ev[i]);
+  free(h->time_ev);
   delete h;
   return TTKV_OK;
 }
@@ -623,7 +628,13 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
     a.tv = make_view(T, make_layout(T, c->n_kv_heads));
     a.st = d.st;
     a.chunk_tokens = d.chunk;
+    const bool timed = d.tier == h->time_tier && h->time_n < h->time_max;
+    if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
     TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
+    if (timed) {
+      TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
+      h->time_n += 1;
+    }
   }
   // host-tier blocks (and selected blocks): copy i+1 overlaps compute on i
   int issued = 0;
@@ -745,6 +756,46 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
   TTKV_HIP(h, hipMemcpyAsync(sel_blocks, a.sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
                              hipMemcpyDeviceToHost, stream));
   TTKV_HIP(h, hipStreamSynchronize(stream));
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_time_tier(ttkv_handle hh, int32_t tier, int32_t max_samples) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || tier >= TTKV_MAX_TIERS || max_samples > 4096) return TTKV_ERR_INVALID_ARG;
+  if (tier < 0) {
+    h->time_tier = -1;
+    return TTKV_OK;
+  }
+  if (max_samples < 1) return TTKV_ERR_INVALID_ARG;
+  if (max_samples > h->time_max) {
+    hipEvent_t *ev = (hipEvent_t *)realloc(h->time_ev, sizeof(hipEvent_t) * 2 * max_samples);
+    if (!ev) return TTKV_ERR_INVALID_ARG;
+    h->time_ev = ev;
+    for (int i = 2 * h->time_max; i < 2 * max_samples; ++i) {
+      hipError_t e = hipEventCreate(&ev[i]);
+      if (e != hipSuccess) {
+        h->time_max = i / 2;
+        h->stats.last_hip_error = (int32_t)e;
+        return TTKV_ERR_HIP;
+      }
+    }
+    h->time_max = max_samples;
+  }
+  h->time_tier = tier;
+  h->time_n = 0;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_read_tier_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !ms || !n_out || capacity < 0) return TTKV_ERR_INVALID_ARG;
+  const int n = std::min<int>(capacity, h->time_n);
+  for (int i = 0; i < n; ++i) {
+    TTKV_HIP(h, hipEventSynchronize(h->time_ev[2 * i + 1]));
+    TTKV_HIP(h, hipEventElapsedTime(&ms[i], h->time_ev[2 * i], h->time_ev[2 * i + 1]));
+  }
+  *n_out = n;
+  h->time_n = 0;
   return TTKV_OK;
 }
 

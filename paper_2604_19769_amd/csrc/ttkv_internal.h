@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "ttkv.h"
 
@@ -76,6 +77,10 @@ struct Handle {
   hipEvent_t fence;     // orders the copy stream behind earlier compute work
   hipEvent_t fence2;    // orders device->host eviction copies behind the quantize kernel
   ttkv_stats stats;
+  // optional per-call timing of one device tier's partial kernel
+  int time_tier;
+  int time_max, time_n;
+  hipEvent_t *time_ev;  // 2 * time_max events
 };
 
 #define TTKV_HIP(h, expr)                                   \
