@@ -248,12 +248,12 @@ def main():
     cache, kv, steps_in, shape = build_mha32k(W + K)
     q, kn, vn = steps_in
     keep = []
-    B.ttkv_time_tier(cache.h, 1, W + K)
+    B.ttkv_time_attn(cache.h, W + K)
     timed_steps(cache, q, kn, vn, 0, W, keep=keep)
-    B.ttkv_read_tier_timing(cache.h)                       # drop warm-up samples
+    B.ttkv_read_attn_timing(cache.h)                       # drop warm-up samples
     total_bytes, by_tier = algorithmic_bytes(cache)        # state at the start of the timed region
     secs = timed_steps(cache, q, kn, vn, W, K)
-    kernel_ms = B.ttkv_read_tier_timing(cache.h)
+    kernel_ms = B.ttkv_read_attn_timing(cache.h)
     total_bytes_end, by_tier_end = algorithmic_bytes(cache)
     step_bytes = (total_bytes + total_bytes_end) / 2 + shape["B"] * shape["Hkv"] * 512   # + the appended token
     ms = secs / K * 1e3

@@ -130,8 +130,9 @@ ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *ti
  * else use ttkv_demote_workspace_bytes). */
 size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots);
 size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
-/* Parts per (sequence, query head) ttkv_decode_attn would use right now. */
-int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride);
+/* Parts per (sequence, query head) ttkv_decode_attn would use right now with this n_slots. */
+int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
+                         int32_t n_slots);
 
 /* Append n_tokens at the tail of `tier` (Sec. 4.1 "newly generated tokens are
  * appended to the fast tier"; also the bulk loader of any device tier).
@@ -168,17 +169,21 @@ ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int
                              size_t ws_bytes, void *compute, void *copy);
 
 /* One decode step of streaming attention (Alg. 1 lines 1-10, Sec. 4.3) for every
- * sequence: partial (max, sum-exp, weighted V) over each part of every device
- * tier and over each fetched host-tier block, merged by log-sum-exp.
- *   q    [device] [batch][n_q_heads][128], q_fmt F16 or BF16
+ * sequence: partial (max, sum-exp, weighted V) over each part of every tier,
+ * merged by log-sum-exp.
+ *   q    [device] [batch][n_q_heads][128], q_fmt F16 or BF16 (a BF16 tier needs BF16
+ *        queries; for the other tiers |q| must stay below 65504)
  *   out  [device] [batch][n_q_heads][128] fp32;  lse [device] [batch][n_q_heads] fp32 or NULL
  *   sel_blocks [host] [batch][sel_stride] block ids (Eq. 1) of the LAST tier to
  *        attend, ascending, sel_count [host] [batch] how many; both NULL = every
  *        live block (dense).
- * Host-tier records are copied to staging slots in `workspace` on `copy`
- * (n_slots-deep, event-chained) while `compute` attends earlier parts.
- * Both streams may be the same (then nothing overlaps).  Returns after
- * enqueuing; `out` is complete when `compute` has drained. */
+ *   n_slots == 0: host tiers are read in place by the attention kernel (loads
+ *        over PCIe stay in flight while other waves compute: the prefetch/compute
+ *        overlap of Sec. 4.3 inside one launch); `copy` is not used.
+ *   n_slots >= 1: host-tier records are copied with hipMemcpyAsync on `copy` into
+ *        n_slots staging slots of `workspace`, event-chained so that copy i+1 runs
+ *        while `compute` attends copy i (both streams equal: nothing overlaps).
+ * Returns after enqueuing; `out` is complete when `compute` has drained. */
 ttkv_status ttkv_decode_attn(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
                              float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
                              void *workspace, size_t ws_bytes, int32_t n_slots, void *compute, void *copy);
@@ -203,15 +208,15 @@ ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q
                                int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
                                size_t scratch_bytes, void *stream);
 
-/* Measurement aid (roofline of one kernel, Sec. 5.1 item 4 "latency is measured on
- * the GPU with events"): from now on every ttkv_decode_attn records a HIP event
- * pair around the partial kernel of device tier `tier` on its compute stream, for
- * at most max_samples calls (<= 4096).  tier < 0 switches it off.  Creates HIP
- * events only.  ttkv_read_tier_timing BLOCKS until the recorded kernels have
+/* Measurement aid (roofline of the attention kernel; Sec. 5.1 item 4 "latency is
+ * measured on the GPU with events"): from now on every ttkv_decode_attn records a
+ * HIP event pair around its fused attention launch(es) on the compute stream, for
+ * at most max_samples calls (<= 4096); max_samples <= 0 switches it off.  Creates
+ * HIP events only.  ttkv_read_attn_timing BLOCKS until the recorded kernels have
  * finished, writes their durations in milliseconds (oldest first, at most
  * `capacity`), returns the count in *n_out and clears the samples. */
-ttkv_status ttkv_time_tier(ttkv_handle h, int32_t tier, int32_t max_samples);
-ttkv_status ttkv_read_tier_timing(ttkv_handle h, float *ms, int32_t capacity, int32_t *n_out);
+ttkv_status ttkv_time_attn(ttkv_handle h, int32_t max_samples);
+ttkv_status ttkv_read_attn_timing(ttkv_handle h, float *ms, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus
 }

@@ -45,7 +45,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
-    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_tier", "ttkv_read_tier_timing",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing",
 ]
 
 _lib = None
@@ -83,7 +83,7 @@ def lib():
         L.ttkv_demote_workspace_bytes.restype = sz
         L.ttkv_append_host_workspace_bytes.argtypes = [cp, i32, i32, i64]
         L.ttkv_append_host_workspace_bytes.restype = sz
-        L.ttkv_count_parts.argtypes = [cp, p, p, i32]
+        L.ttkv_count_parts.argtypes = [cp, p, p, i32, i32]
         L.ttkv_count_parts.restype = i32
         L.ttkv_quantize_append.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p]
         L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
@@ -91,8 +91,8 @@ def lib():
         L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
-        L.ttkv_time_tier.argtypes = [p, i32, i32]
-        L.ttkv_read_tier_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
+        L.ttkv_time_attn.argtypes = [p, i32]
+        L.ttkv_read_attn_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
         for name in EXPORTS:
             f = getattr(L, name)
             if name not in ("ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
@@ -163,8 +163,8 @@ def ttkv_append_host_workspace_bytes(cache, tier, seq, n_tokens):
     return lib().ttkv_append_host_workspace_bytes(C.byref(cache), tier, seq, n_tokens)
 
 
-def ttkv_count_parts(cache, sel_blocks=None, sel_count=None, sel_stride=0):
-    return lib().ttkv_count_parts(C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride)
+def ttkv_count_parts(cache, sel_blocks=None, sel_count=None, sel_stride=0, n_slots=0):
+    return lib().ttkv_count_parts(C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride, n_slots)
 
 
 def ttkv_quantize_append(h, cache, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, stream):
@@ -201,12 +201,12 @@ def ttkv_select_blocks(h, cache, q, q_fmt, k, sel_blocks, sel_count, sel_stride,
                                     _p(scratch), scratch_bytes, _p(stream)), "ttkv_select_blocks")
 
 
-def ttkv_time_tier(h, tier, max_samples):
-    _check(lib().ttkv_time_tier(h, tier, max_samples), "ttkv_time_tier")
+def ttkv_time_attn(h, max_samples):
+    _check(lib().ttkv_time_attn(h, max_samples), "ttkv_time_attn")
 
 
-def ttkv_read_tier_timing(h, capacity=4096):
+def ttkv_read_attn_timing(h, capacity=4096):
     ms = (C.c_float * capacity)()
     n = C.c_int32()
-    _check(lib().ttkv_read_tier_timing(h, ms, capacity, C.byref(n)), "ttkv_read_tier_timing")
+    _check(lib().ttkv_read_attn_timing(h, ms, capacity, C.byref(n)), "ttkv_read_attn_timing")
     return [ms[i] for i in range(n.value)]

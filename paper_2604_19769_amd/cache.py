@@ -27,7 +27,7 @@ _SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 
 
 
 class TieredCache:
-    def __init__(self, batch, n_q_heads, n_kv_heads, tiers, device="cuda:0", softmax_scale=None, n_slots=2):
+    def __init__(self, batch, n_q_heads, n_kv_heads, tiers, device="cuda:0", softmax_scale=None, n_slots=0):
         self.B, self.Hq, self.Hkv = batch, n_q_heads, n_kv_heads
         self.cfg = list(tiers)
         self.device = torch.device(device)
@@ -127,12 +127,12 @@ class TieredCache:
                                self._copy(overlap))
 
     def _workspace(self, parts):
-        if self.ws is None or parts > self.ws_parts:
+        if self.ws is None or parts > self.ws_parts or self.ws_slots != self.n_slots:
             parts = max(parts + 16, int(parts * 1.25))
             need = B.ttkv_workspace_bytes(self.c, parts, self.n_slots)
             assert need > 0
             self.ws = torch.empty(need, dtype=torch.uint8, device=self.device)
-            self.ws_parts = parts
+            self.ws_parts, self.ws_slots = parts, self.n_slots
         return self.ws
 
     def decode(self, q, selected=None, overlap=True):
@@ -144,7 +144,7 @@ class TieredCache:
         if selected is not None:
             sb, sc = selected
             stride = sb.shape[1]
-        parts = B.ttkv_count_parts(self.c, sb, sc, stride)
+        parts = B.ttkv_count_parts(self.c, sb, sc, stride, self.n_slots)
         if parts < 0:
             raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
         ws = self._workspace(max(parts, 1))

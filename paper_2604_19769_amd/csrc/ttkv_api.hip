@@ -83,11 +83,16 @@ int copy_granule(int64_t rec_bytes) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(8, g));
 }
 
-struct DevLaunch {
-  int tier;
-  int chunk;
-  SeqTable st;
+// One run of consecutive tokens of one (tier, sequence) attended by the fused
+// kernel in place: a device tier, a host tier read over PCIe by the kernel itself,
+// or a run of selected blocks.
+struct Run {
+  int tier, b;
+  int32_t rec_base, first_tok, len;
+  bool no_table;
+  int part_base, n_chunks;
 };
+// One staged copy: consecutive pool records of a host tier brought into a slot.
 struct Fetch {
   int tier, b;
   int64_t rec;     // first pool record
@@ -97,8 +102,9 @@ struct Fetch {
   int chunk;
 };
 struct Plan {
-  std::vector<DevLaunch> dev;
+  std::vector<Run> runs;
   std::vector<Fetch> fetch;
+  int chunk[TTKV_MAX_TIERS];
   int parts[TTKV_MAX_BATCH];
   int max_parts;
   size_t slot_bytes;
@@ -111,14 +117,17 @@ int pick_chunk(const ttkv_cache *c, int t) {
   for (int b = 0; b < c->batch; ++b) total += T.len[b];
   const int G = c->n_q_heads / c->n_kv_heads;
   const int n_hg = G % 4 == 0 ? G / 4 : (G % 2 == 0 ? G / 2 : G);
-  // aim at ~4096 workgroups (16 per CU) with chunks of 256..2048 tokens
-  int64_t want = total * c->n_kv_heads * n_hg / 4096;
+  // aim at ~3072 workgroups (12 per CU) with chunks of 256..4096 tokens
+  int64_t want = total * c->n_kv_heads * n_hg / 3072;
   int64_t lo = is_fp(T.k_fmt) ? 128 : 256;
-  want = std::max<int64_t>(lo, std::min<int64_t>(2048, want));
+  want = std::max<int64_t>(lo, std::min<int64_t>(4096, want));
   return (int)((want + 63) / 64 * 64);
 }
 
-void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, Plan *P) {
+// staged: host tiers are copied block by block into staging slots (one kernel per
+// copy); otherwise the fused kernel reads them in place.
+void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, bool staged,
+                Plan *P) {
   P->status = TTKV_OK;
   P->slot_bytes = 0;
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
@@ -127,33 +136,28 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const ttkv_tier &T = c->tier[t];
     const Layout L = make_layout(T, c->n_kv_heads);
     const bool sparse = sel_blocks && t == last;
-    if (T.mem == TTKV_MEM_DEVICE && !sparse) {
-      DevLaunch d{};
-      d.tier = t;
-      d.chunk = pick_chunk(c, t);
-      int items = 0;
+    const bool host = T.mem == TTKV_MEM_HOST_PINNED;
+    P->chunk[t] = (host || sparse) ? std::min(L.bt, 256) : pick_chunk(c, t);
+    const int chunk = P->chunk[t];
+    if (!sparse && !(host && staged)) {
       for (int b = 0; b < c->batch; ++b) {
         if (T.len[b] == 0) continue;
-        const int j = d.st.n_seq++;
-        d.st.seq_id[j] = b;
-        d.st.rec_base[j] = (int32_t)((int64_t)b * T.ring_blocks);
-        d.st.first_tok[j] = (int32_t)(T.start[b] % ring_tokens(T));
-        d.st.len[j] = (int32_t)T.len[b];
-        d.st.item_start[j] = items;
-        d.st.part_base[j] = P->parts[b];
-        const int n = (int)((T.len[b] + d.chunk - 1) / d.chunk);
-        items += n;
-        P->parts[b] += n;
+        Run r{};
+        r.tier = t; r.b = b;
+        r.rec_base = (int32_t)((int64_t)b * T.ring_blocks);
+        r.first_tok = (int32_t)(T.start[b] % ring_tokens(T));
+        r.len = (int32_t)T.len[b];
+        r.no_table = false;
+        r.part_base = P->parts[b];
+        r.n_chunks = (int)((T.len[b] + chunk - 1) / chunk);
+        P->parts[b] += r.n_chunks;
+        P->runs.push_back(r);
       }
-      d.st.item_start[d.st.n_seq] = items;
-      if (d.st.n_seq) P->dev.push_back(d);
       continue;
     }
-    // host tier, or a sparse (selected-blocks) pass over the last tier: one part
-    // group per fetched / selected block
-    const int gran = T.mem == TTKV_MEM_HOST_PINNED ? copy_granule(L.rec_bytes) : 1;
-    if (T.mem == TTKV_MEM_HOST_PINNED) P->slot_bytes = std::max(P->slot_bytes, align256((size_t)gran * L.rec_bytes));
-    const int chunk = std::min(L.bt, 256);
+    // block by block: selected blocks of the last tier, or staged host blocks
+    const int gran = host && staged ? copy_granule(L.rec_bytes) : (1 << 20);
+    if (host && staged) P->slot_bytes = std::max(P->slot_bytes, align256((size_t)gran * L.rec_bytes));
     for (int b = 0; b < c->batch; ++b) {
       if (T.len[b] == 0 && !sparse) continue;
       const int64_t first_id = T.start[b] / L.bt;
@@ -169,20 +173,43 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
         prev_id = id;
         const int64_t rec = record_of(T, b, id % T.ring_blocks);
         const int ntok = (int)std::min<int64_t>(L.bt, T.start[b] + T.len[b] - id * L.bt);
-        if (!P->fetch.empty()) {
-          Fetch &f = P->fetch.back();
-          if (f.tier == t && f.b == b && f.nrec < gran && f.rec + f.nrec == rec && f.ntok == f.nrec * L.bt) {
-            f.nrec += 1;
-            f.ntok += ntok;
-            P->parts[b] += (ntok + chunk - 1) / chunk;
-            continue;
+        const int nparts = (ntok + chunk - 1) / chunk;
+        if (host && staged) {
+          if (!P->fetch.empty()) {
+            Fetch &f = P->fetch.back();
+            if (f.tier == t && f.b == b && f.nrec < gran && f.rec + f.nrec == rec && f.ntok == f.nrec * L.bt) {
+              f.nrec += 1;
+              f.ntok += ntok;
+              P->parts[b] += nparts;
+              continue;
+            }
           }
+          Fetch f{};
+          f.tier = t; f.b = b; f.rec = rec; f.nrec = 1; f.ntok = ntok; f.chunk = chunk;
+          f.part_base = P->parts[b];
+          P->parts[b] += nparts;
+          P->fetch.push_back(f);
+        } else {
+          if (!P->runs.empty()) {
+            Run &r = P->runs.back();
+            if (r.tier == t && r.b == b && r.no_table && (int64_t)r.rec_base + r.len / L.bt == rec && r.len % L.bt == 0) {
+              r.len += ntok;
+              r.n_chunks += nparts;
+              P->parts[b] += nparts;
+              continue;
+            }
+          }
+          Run r{};
+          r.tier = t; r.b = b;
+          r.rec_base = (int32_t)rec;
+          r.first_tok = 0;
+          r.len = ntok;
+          r.no_table = true;
+          r.part_base = P->parts[b];
+          r.n_chunks = nparts;
+          P->parts[b] += nparts;
+          P->runs.push_back(r);
         }
-        Fetch f{};
-        f.tier = t; f.b = b; f.rec = rec; f.nrec = 1; f.ntok = ntok; f.chunk = chunk;
-        f.part_base = P->parts[b];
-        P->parts[b] += (ntok + chunk - 1) / chunk;
-        P->fetch.push_back(f);
       }
     }
   }
@@ -351,7 +378,7 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   Handle *h = new (std::nothrow) Handle();
   if (!h) return TTKV_ERR_INVALID_ARG;
   h->have_events = false;
-  h->time_tier = -1;
+  h->time_on = false;
   h->time_max = h->time_n = 0;
   h->time_ev = nullptr;
   *out = reinterpret_cast<ttkv_handle>(h);
@@ -453,10 +480,11 @@ size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32
   return (size_t)(seq < 0 ? c->batch : 1) * touched * L.rec_bytes;
 }
 
-int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride) {
+int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
+                         int32_t n_slots) {
   if (validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
 }
 
@@ -585,13 +613,17 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   st = check_sel(c, sel_blocks, sel_count, sel_stride);
   if (st != TTKV_OK) return st;
   if (n_slots < 0 || n_slots > TTKV_MAX_SLOTS) return TTKV_ERR_INVALID_ARG;
+  for (int t = 0; t < c->n_tiers; ++t) {
+    const ttkv_tier &T = c->tier[t];
+    if (T.k_fmt == TTKV_BF16 && q_fmt != TTKV_BF16) return TTKV_ERR_UNSUPPORTED;   // a bf16 tier takes bf16 queries
+    if (n_slots == 0 && T.block_table && !T.block_table_dev) return TTKV_ERR_INVALID_ARG;
+  }
   hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
+  const bool staged = n_slots > 0;
 
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, staged, &P);
   if (P.status != TTKV_OK) return P.status;
-  const bool any_host_fetch = std::any_of(P.fetch.begin(), P.fetch.end(), [&](const Fetch &f) { return c->tier[f.tier].mem == TTKV_MEM_HOST_PINNED; });
-  if (any_host_fetch && n_slots < 1) return TTKV_ERR_WORKSPACE;
   if (!workspace) return TTKV_ERR_WORKSPACE;
   // workspace = [n_slots staging slots][m][l][acc]
   const size_t slots_bytes = (size_t)n_slots * P.slot_bytes;
@@ -601,14 +633,14 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   const int64_t stride = (int64_t)((ws_bytes - mis - slots_bytes) / (rows * 130 * sizeof(float)));
   if (stride < std::max(1, P.max_parts)) return TTKV_ERR_WORKSPACE;
   const int32_t part_stride = (int32_t)std::min<int64_t>(stride, 1 << 20);
-  if (any_host_fetch && (st = ensure_events(h)) != TTKV_OK) return st;
+  if (!P.fetch.empty() && copy != compute && (st = ensure_events(h)) != TTKV_OK) return st;
   uint8_t *ws = (uint8_t *)workspace + mis;
   float *pm = (float *)(ws + slots_bytes);
   float *pl = pm + rows * part_stride;
   float *pacc = pl + rows * part_stride;
 
   int nk = 0;
-  AttnArgs a{};
+  FusedArgs a{};
   a.q = q;
   a.q_fmt = q_fmt;
   a.pm = pm; a.pl = pl; a.pacc = pacc;
@@ -617,65 +649,80 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   a.Hkv = c->n_kv_heads;
   a.scale = c->softmax_scale;
 
-  if (any_host_fetch && copy != compute) {
+  if (!P.fetch.empty() && copy != compute) {
     // staging slots may still be read by earlier work on `compute`
     TTKV_HIP(h, hipEventRecord(h->fence, compute));
     TTKV_HIP(h, hipStreamWaitEvent(copy, h->fence, 0));
   }
-  // device-resident tiers first: they run while the first host blocks are in flight
-  for (const DevLaunch &d : P.dev) {
-    const ttkv_tier &T = c->tier[d.tier];
-    a.tv = make_view(T, make_layout(T, c->n_kv_heads));
-    a.st = d.st;
-    a.chunk_tokens = d.chunk;
-    const bool timed = d.tier == h->time_tier && h->time_n < h->time_max;
-    if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
-    TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
-    if (timed) {
-      TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
-      h->time_n += 1;
-    }
+  // every run that is attended in place goes into one launch (split only when the entry table is full)
+  for (int t = 0; t < c->n_tiers; ++t) {
+    const ttkv_tier &T = c->tier[t];
+    a.tv[t] = make_view(T, make_layout(T, c->n_kv_heads));
+    a.chunk[t] = P.chunk[t];
   }
-  // host-tier blocks (and selected blocks): copy i+1 overlaps compute on i
+  const bool timed = h->time_on && h->time_n < h->time_max && !P.runs.empty();
+  if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
+  for (size_t r0 = 0; r0 < P.runs.size(); r0 += TTKV_MAX_ENTRIES) {
+    const size_t r1 = std::min(P.runs.size(), r0 + TTKV_MAX_ENTRIES);
+    a.n_entries = (int32_t)(r1 - r0);
+    int items = 0;
+    for (size_t i = r0; i < r1; ++i) {
+      const Run &r = P.runs[i];
+      Entry &e = a.e[i - r0];
+      e.tier_seq = (r.no_table ? (1 << 24) : 0) | (r.tier << 16) | r.b;
+      e.rec_base = r.rec_base;
+      e.first_tok = r.first_tok;
+      e.len = r.len;
+      e.item_start = items;
+      e.part_base = r.part_base;
+      items += r.n_chunks;
+    }
+    a.n_items = items;
+    TTKV_HIP(h, launch_attn(a, compute, &nk));
+  }
+  if (timed) {
+    TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
+    h->time_n += 1;
+  }
+  // staged host-tier blocks: copy i+1 overlaps compute on i
   int issued = 0;
   for (const Fetch &f : P.fetch) {
     const ttkv_tier &T = c->tier[f.tier];
     const Layout L = make_layout(T, c->n_kv_heads);
-    a.st = SeqTable{};
-    a.st.n_seq = 1;
-    a.st.seq_id[0] = f.b;
-    a.st.len[0] = f.ntok;
-    a.st.item_start[0] = 0;
-    a.st.item_start[1] = (f.ntok + f.chunk - 1) / f.chunk;
-    a.st.part_base[0] = f.part_base;
-    a.chunk_tokens = f.chunk;
-    if (T.mem == TTKV_MEM_HOST_PINNED) {
-      const int slot = issued % n_slots;
-      uint8_t *dst = ws + (size_t)slot * P.slot_bytes;
-      if (issued >= n_slots && copy != compute) TTKV_HIP(h, hipStreamWaitEvent(copy, h->freed[slot], 0));
-      const size_t bytes = (size_t)f.nrec * L.rec_bytes;
-      TTKV_HIP(h, hipMemcpyAsync(dst, (const uint8_t *)T.data + f.rec * L.rec_bytes, bytes, hipMemcpyHostToDevice, copy));
-      if (copy != compute) {
-        TTKV_HIP(h, hipEventRecord(h->ready[slot], copy));
-        TTKV_HIP(h, hipStreamWaitEvent(compute, h->ready[slot], 0));
-      }
-      a.tv = make_slot_view(T, L, dst, f.nrec);
-      a.st.rec_base[0] = 0;
-      a.st.first_tok[0] = 0;
-      TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
-      if (copy != compute) TTKV_HIP(h, hipEventRecord(h->freed[slot], compute));
-      h->stats.h2d_bytes += bytes;
-      h->stats.blocks_fetched += f.nrec;
-      ++issued;
-    } else {
-      // selected block of a device-resident last tier: attend it in place
-      a.tv = make_view(T, L);
-      a.tv.table = nullptr;
-      a.tv.ring_blocks = 1;
-      a.st.rec_base[0] = (int32_t)f.rec;
-      a.st.first_tok[0] = 0;
-      TTKV_HIP(h, launch_attn_partial(a, compute, &nk));
+    const int slot = issued % n_slots;
+    uint8_t *dst = ws + (size_t)slot * P.slot_bytes;
+    if (issued >= n_slots && copy != compute) TTKV_HIP(h, hipStreamWaitEvent(copy, h->freed[slot], 0));
+    const size_t bytes = (size_t)f.nrec * L.rec_bytes;
+    TTKV_HIP(h, hipMemcpyAsync(dst, (const uint8_t *)T.data + f.rec * L.rec_bytes, bytes, hipMemcpyHostToDevice, copy));
+    if (copy != compute) {
+      TTKV_HIP(h, hipEventRecord(h->ready[slot], copy));
+      TTKV_HIP(h, hipStreamWaitEvent(compute, h->ready[slot], 0));
     }
+    a.tv[0] = make_slot_view(T, L, dst, f.nrec);
+    a.chunk[0] = f.chunk;
+    a.n_entries = 1;
+    a.e[0].tier_seq = (1 << 24) | f.b;
+    a.e[0].rec_base = 0;
+    a.e[0].first_tok = 0;
+    a.e[0].len = f.ntok;
+    a.e[0].item_start = 0;
+    a.e[0].part_base = f.part_base;
+    a.n_items = (f.ntok + f.chunk - 1) / f.chunk;
+    TTKV_HIP(h, launch_attn(a, compute, &nk));
+    if (copy != compute) TTKV_HIP(h, hipEventRecord(h->freed[slot], compute));
+    ++issued;
+  }
+  // host-tier traffic (Sec. 5.1 item 5): whole records, whether copied or read in place
+  for (const Fetch &f : P.fetch) {
+    h->stats.h2d_bytes += (uint64_t)f.nrec * make_layout(c->tier[f.tier], c->n_kv_heads).rec_bytes;
+    h->stats.blocks_fetched += f.nrec;
+  }
+  for (const Run &r : P.runs) {
+    const ttkv_tier &T = c->tier[r.tier];
+    if (T.mem != TTKV_MEM_HOST_PINNED) continue;
+    const int nrec = (r.len + T.block_tokens - 1) / T.block_tokens;
+    h->stats.h2d_bytes += (uint64_t)nrec * make_layout(T, c->n_kv_heads).rec_bytes;
+    h->stats.blocks_fetched += nrec;
   }
   MergeArgs m{};
   m.m = pm; m.l = pl; m.acc = pacc;
@@ -759,14 +806,13 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
   return TTKV_OK;
 }
 
-ttkv_status ttkv_time_tier(ttkv_handle hh, int32_t tier, int32_t max_samples) {
+ttkv_status ttkv_time_attn(ttkv_handle hh, int32_t max_samples) {
   Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || tier >= TTKV_MAX_TIERS || max_samples > 4096) return TTKV_ERR_INVALID_ARG;
-  if (tier < 0) {
-    h->time_tier = -1;
+  if (!h || max_samples > 4096) return TTKV_ERR_INVALID_ARG;
+  if (max_samples <= 0) {
+    h->time_on = false;
     return TTKV_OK;
   }
-  if (max_samples < 1) return TTKV_ERR_INVALID_ARG;
   if (max_samples > h->time_max) {
     hipEvent_t *ev = (hipEvent_t *)realloc(h->time_ev, sizeof(hipEvent_t) * 2 * max_samples);
     if (!ev) return TTKV_ERR_INVALID_ARG;
@@ -781,12 +827,12 @@ ttkv_status ttkv_time_tier(ttkv_handle hh, int32_t tier, int32_t max_samples) {
     }
     h->time_max = max_samples;
   }
-  h->time_tier = tier;
+  h->time_on = true;
   h->time_n = 0;
   return TTKV_OK;
 }
 
-ttkv_status ttkv_read_tier_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
+ttkv_status ttkv_read_attn_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || !ms || !n_out || capacity < 0) return TTKV_ERR_INVALID_ARG;
   const int n = std::min<int>(capacity, h->time_n);

@@ -1,16 +1,29 @@
-// Split-K decode attention partials over one tier (Alg. 1: Attn on the fast
-// tier, Decompress + Attn per slow-tier block) and the log-sum-exp merge of the
-// partials (the "+" of Alg. 1, normalised once at the end).
+// Split-K decode attention partials over every tier in ONE launch (Alg. 1: Attn on
+// the fast tier, Decompress + Attn per slow-tier block) and the log-sum-exp merge
+// of the partials (the "+" of Alg. 1, normalised once at the end).
 //
-// Mapping (wave64): a K or V row of one token-head is ROWB bytes = LPT lanes x
-// 16 B, so one 128-bit load per lane brings TPL = 64/LPT whole rows per wave,
-// fully coalesced.  Lane L holds elements [slice*EPL, slice*EPL+EPL) of token
-// L/LPT; codes are decompressed in registers; the q.k dot is finished with
-// log2(LPT) lane shuffles; the lane that owns a token's K slice also owns its
-// V slice, so softmax weights never leave their lane (K 8-bit + V 4-bit needs
-// one shuffle per V row).  Scale/zero are factored out of the inner loops:
-//   q.k  = s_g * sum_i q_i c_i + z_g * sum_i q_i         (per group g)
-//   sum_t p_t v_t = sum_t (p_t s_t) c_t + sum_t p_t z_t
+// Work item = (tier, sequence, chunk of tokens, KV head[, query-head group]); one
+// workgroup of four wave64 per item, each wave streaming 1/4 of the chunk's tiles.
+//
+// Lane mapping: a K or V row of one token-head is ROWB bytes = LPT lanes x 16 B, so
+// one 128-bit load per lane brings TPL = 64/LPT whole rows per wave, fully
+// coalesced.  Lane L holds elements [slice*EPL, +EPL) of token L/LPT.  The lane
+// that owns a token's K slice also owns its V slice, so softmax weights never
+// leave their lane (K 8-bit + V 4-bit needs one lane shuffle per V row).
+//
+// Arithmetic: codes are never expanded to fp32.  int4 nibbles and int8 bytes are
+// spliced into the mantissa of an fp16 constant (1024+n, 64+n, 1152+c), giving
+// packed half pairs for v_dot2_f32_f16 (q.k) and v_fma_mix_f32 (p.v); the known
+// offsets and the per-group scale/zero are factored out of the inner loops:
+//   q.k  = s_g * (sum_i q_i (c_i + o_i) - sum_i q_i o_i) + z_g * sum_i q_i
+//   sum_t p_t v_t = sum_t (p_t s_t)(c_t + o) - o * sum_t p_t s_t + sum_t p_t z_t
+// Accumulation is fp32 throughout.  Query values are held as fp16 for the fp16 and
+// quantized tiers (bf16 queries are converted; |q| must stay below 65504) and as
+// bf16 pairs for the bf16 tier.
+//
+// The host tier needs no separate path: pinned host memory is read by the same
+// loads (PCIe reads in flight while other waves compute), or from a staging slot
+// in HBM when the caller asks for explicit block copies.
 #include "ttkv_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -22,6 +35,9 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+
 template <int F> struct Fmt;
 template <> struct Fmt<TTKV_F16> { static constexpr int ROWB = 256, LPT = 16, TPL = 4, EPL = 8; };
 template <> struct Fmt<TTKV_BF16> { static constexpr int ROWB = 256, LPT = 16, TPL = 4, EPL = 8; };
@@ -29,42 +45,73 @@ template <> struct Fmt<TTKV_I8_SYM_G32> { static constexpr int ROWB = 128, LPT =
 template <> struct Fmt<TTKV_I4_ASYM_G64> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };
 
 __device__ __forceinline__ float h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ b2 as_b2(uint32_t u) { return __builtin_bit_cast(b2, u); }
 
-// 16 bytes of one row -> EPL raw element values (codes as floats; fp formats: the value).
+// Position of element e of a lane's 16-byte slice inside the packed pair registers:
+// register e/2-ish and half, per format (see unpack16).
+//   F16 / BF16 / I8 : pair r = e/2 holds (e, e+1)                      -> natural
+//   I4              : dword d = e/8, pairs (0,4) (1,5) (2,6) (3,7)     -> r = 4d + e%4, half = (e%8)/4
 template <int F>
-__device__ __forceinline__ void decode16(const uint4 &w, float *x) {
+__device__ __forceinline__ constexpr int pair_reg(int e) {
+  return F == TTKV_I4_ASYM_G64 ? 4 * (e / 8) + (e % 4) : e / 2;
+}
+template <int F>
+__device__ __forceinline__ constexpr int pair_half(int e) {
+  return F == TTKV_I4_ASYM_G64 ? (e % 8) / 4 : e % 2;
+}
+// Offset o_e that unpack16 leaves on element e.
+template <int F>
+__device__ __forceinline__ constexpr float elem_offset(int e) {
+  return F == TTKV_I4_ASYM_G64 ? ((e % 2) ? 64.0f : 1024.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
+}
+
+// 16 bytes of a row -> EPL/2 registers of packed 16-bit pairs (fp16, or bf16 for the bf16 tier).
+template <int F>
+__device__ __forceinline__ void unpack16(const uint4 &w, uint32_t *r) {
   const uint32_t u[4] = {w.x, w.y, w.z, w.w};
-  if constexpr (F == TTKV_F16) {
+  if constexpr (F == TTKV_F16 || F == TTKV_BF16) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[2 * i] = h2f((uint16_t)(u[i] & 0xffff));
-      x[2 * i + 1] = h2f((uint16_t)(u[i] >> 16));
-    }
-  } else if constexpr (F == TTKV_BF16) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[2 * i] = __uint_as_float(u[i] << 16);
-      x[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
-    }
+    for (int i = 0; i < 4; ++i) r[i] = u[i];
   } else if constexpr (F == TTKV_I8_SYM_G32) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      x[4 * i + 0] = (float)((int)(u[i] << 24) >> 24);
-      x[4 * i + 1] = (float)((int)(u[i] << 16) >> 24);
-      x[4 * i + 2] = (float)((int)(u[i] << 8) >> 24);
-      x[4 * i + 3] = (float)((int)u[i] >> 24);
+      const uint32_t x = u[i] ^ 0x80808080u;                       // byte -> code + 128 in [1, 255]
+      r[2 * i] = __builtin_amdgcn_perm(0x64646464u, x, 0x04010400u);      // (1024 + b0, 1024 + b1)
+      r[2 * i + 1] = __builtin_amdgcn_perm(0x64646464u, x, 0x04030402u);  // (1024 + b2, 1024 + b3)
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int n = 0; n < 8; ++n) x[8 * i + n] = (float)((u[i] >> (4 * n)) & 0xf);
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t x = u[i], y = u[i] >> 8;
+      r[4 * i + 0] = (x & 0x000F000Fu) | 0x64006400u;   // (1024 + n0, 1024 + n4)
+      r[4 * i + 1] = (x & 0x00F000F0u) | 0x54005400u;   // (  64 + n1,   64 + n5)
+      r[4 * i + 2] = (y & 0x000F000Fu) | 0x64006400u;   // (1024 + n2, 1024 + n6)
+      r[4 * i + 3] = (y & 0x00F000F0u) | 0x54005400u;   // (  64 + n3,   64 + n7)
+    }
   }
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// sum / max over groups of LPT consecutive lanes (LPT = 4, 8, 16) -- every lane gets the result
+template <int LPT>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp<0xB1>(v);                       // quad_perm [1,0,3,2]
+  v += dpp<0x4E>(v);                       // quad_perm [2,3,0,1]: every lane holds its quad's sum
+  if constexpr (LPT >= 8) v += dpp<0x141>(v);   // row_half_mirror: lane i <- lane 7-i = the other quad's sum
+  if constexpr (LPT >= 16) v += dpp<0x140>(v);  // row_mirror: lane i <- lane 15-i = the other half's sum
+  return v;
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+  v = fmaxf(v, dpp<0xB1>(v));
+  v = fmaxf(v, dpp<0x4E>(v));
+  v = fmaxf(v, dpp<0x124>(v));             // row_ror:4
+  v = fmaxf(v, dpp<0x128>(v));             // row_ror:8
+  v = fmaxf(v, __shfl_xor(v, 16));
+  v = fmaxf(v, __shfl_xor(v, 32));
   return v;
 }
 __device__ __forceinline__ float wave_sum(float v) {
@@ -73,80 +120,84 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Everything one wave accumulates for one item.
 template <int KF, int VF, int G>
-__global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
+__device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
+                                        int chunk, int seq, int hkv, int hq0, float (*s_acc)[4][G][128], float (*s_m)[G],
+                                        float (*s_l)[G]) {
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   static_assert(FV::TPL % FK::TPL == 0, "V rows must not be wider than K rows");
-  constexpr int TT = 4 * FK::TPL;          // tokens per wave tile (K is the wider or equal row)
+  constexpr int TT = 4 * FK::TPL;          // tokens per wave tile
   constexpr int NLK = 4;                   // K loads per lane per tile
   constexpr int NLV = TT / FV::TPL;        // V loads per lane per tile
   constexpr int R = FV::TPL / FK::TPL;     // K loads covered by one V load
+  constexpr int QN = FK::EPL / 2;          // packed q registers per head
   constexpr bool KQ = (KF == TTKV_I8_SYM_G32 || KF == TTKV_I4_ASYM_G64);
   constexpr bool VQ = (VF == TTKV_I8_SYM_G32 || VF == TTKV_I4_ASYM_G64);
 
-  __shared__ float s_acc[4][G][128];
-  __shared__ float s_m[4][G], s_l[4][G];
-
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int item = blockIdx.x;
-  const int hkv = blockIdx.y;
-  const int Gtot = a.Hq / a.Hkv;
-  const int hq0 = hkv * Gtot + blockIdx.z * G;
-
-  int j = 0;
-  while (j + 1 < a.st.n_seq && item >= a.st.item_start[j + 1]) ++j;
-  const int chunk = item - a.st.item_start[j];
-  const int seq = a.st.seq_id[j];
-  const int len = a.st.len[j];
-  const int c0 = chunk * a.chunk_tokens;
-  const int c1 = min(len, c0 + a.chunk_tokens);
-  const int ring_tokens = a.tv.ring_blocks * a.tv.bt;
-
+  const int c0 = chunk * chunk_tokens;
+  const int c1 = min(en.len, c0 + chunk_tokens);
+  const int ring_tokens = tv.ring_blocks * tv.bt;
   const int kslice = lane % FK::LPT, ktok = lane / FK::LPT;
   const int vslice = lane % FV::LPT, vtok = lane / FV::LPT;
+  const float cs = a.scale * kLog2e;       // scores are kept in the log2 domain
 
-  // q slice of this lane for every head of the group, pre-multiplied by
-  // softmax_scale * log2(e) so that the softmax runs on exp2.
-  float q[G][FK::EPL];
-  float qsum[G];
-  {
-    const float qs = a.scale * kLog2e;
+  // ---- q slice of this lane, packed to match unpack16<KF>; offset and plain sums for the factored terms
+  uint32_t qp[G][QN];
+  float qoff[G], qsum[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const uint16_t *qp = (const uint16_t *)a.q + ((int64_t)seq * a.Hq + hq0 + g) * 128 + kslice * FK::EPL;
-      qsum[g] = 0.0f;
+  for (int g = 0; g < G; ++g) {
+    const uint16_t *qsrc = (const uint16_t *)a.q + ((int64_t)seq * a.Hq + hq0 + g) * 128 + kslice * FK::EPL;
+    uint16_t qb[FK::EPL];
+    float so = 0.0f, ss = 0.0f;
 #pragma unroll
-      for (int e = 0; e < FK::EPL; ++e) {
-        float v = a.q_fmt == TTKV_F16 ? h2f(qp[e]) : __uint_as_float((uint32_t)qp[e] << 16);
-        q[g][e] = v * qs;
-        qsum[g] += q[g][e];
+    for (int e = 0; e < FK::EPL; ++e) {
+      uint16_t raw = qsrc[e];
+      float v;
+      if constexpr (KF == TTKV_BF16) {
+        v = __uint_as_float((uint32_t)raw << 16);   // a bf16 tier is only ever given bf16 queries (checked on the host)
+      } else {
+        if (a.q_fmt == TTKV_BF16) {
+          const float f = fminf(fmaxf(__uint_as_float((uint32_t)raw << 16), -65504.0f), 65504.0f);
+          raw = __half_as_ushort(__float2half_rn(f));
+        }
+        v = h2f(raw);
       }
+      qb[e] = raw;
+      ss += v;
+      so = fmaf(v, elem_offset<KF>(e), so);
     }
+#pragma unroll
+    for (int r = 0; r < QN; ++r) qp[g][r] = 0;
+#pragma unroll
+    for (int e = 0; e < FK::EPL; ++e) qp[g][pair_reg<KF>(e)] |= (uint32_t)qb[e] << (16 * pair_half<KF>(e));
+    qoff[g] = so;
+    qsum[g] = ss * cs;
   }
 
-  float m[G], l[G], zacc[G];
+  float m[G], l[G], zacc[G], psum[G];
   float acc[G][FV::EPL];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     m[g] = -INFINITY;
-    l[g] = 0.0f;
-    zacc[g] = 0.0f;
+    l[g] = zacc[g] = psum[g] = 0.0f;
 #pragma unroll
     for (int e = 0; e < FV::EPL; ++e) acc[g][e] = 0.0f;
   }
 
   for (int i0 = c0 + wave * TT; i0 < c1; i0 += 4 * TT) {
     const int nv = min(TT, c1 - i0);
-    int tok0 = a.st.first_tok[j] + i0;
+    int tok0 = en.first_tok + i0;
     if (tok0 >= ring_tokens) tok0 -= ring_tokens;
-    const int r = tok0 / a.tv.bt;
-    const int row0 = tok0 - r * a.tv.bt;
-    const int64_t rec = a.tv.table ? (int64_t)a.tv.table[(int64_t)seq * a.tv.ring_blocks + r] : (int64_t)a.st.rec_base[j] + r;
-    const uint8_t *head = a.tv.base + rec * a.tv.rec_bytes + (int64_t)hkv * a.tv.head_bytes;
+    const int rb = tok0 / tv.bt;
+    const int row0 = tok0 - rb * tv.bt;
+    const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
+    const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
 
-    // ---- issue all loads of the tile
+    // ---- issue every load of the tile
     uint4 kw[NLK], vw[NLV];
     uint32_t kmeta[NLK], vmeta[NLV];
 #pragma unroll
@@ -154,57 +205,66 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
       const int t = min(n * FK::TPL + ktok, nv - 1);
       kw[n] = *(const uint4 *)(head + (row0 + t) * FK::ROWB + kslice * 16);
       if constexpr (KF == TTKV_I8_SYM_G32)
-        kmeta[n] = *(const uint16_t *)(head + a.tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 2);
+        kmeta[n] = *(const uint16_t *)(head + tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 2);
       else if constexpr (KF == TTKV_I4_ASYM_G64)
-        kmeta[n] = *(const uint32_t *)(head + a.tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 4);
+        kmeta[n] = *(const uint32_t *)(head + tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 4);
     }
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
       const int t = min(n * FV::TPL + vtok, nv - 1);
-      vw[n] = *(const uint4 *)(head + a.tv.v_off + (row0 + t) * FV::ROWB + vslice * 16);
+      vw[n] = *(const uint4 *)(head + tv.v_off + (row0 + t) * FV::ROWB + vslice * 16);
       if constexpr (VF == TTKV_I8_SYM_G32)
-        vmeta[n] = *(const uint16_t *)(head + a.tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 2);
+        vmeta[n] = *(const uint16_t *)(head + tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 2);
       else if constexpr (VF == TTKV_I4_ASYM_G64)
-        vmeta[n] = *(const uint32_t *)(head + a.tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 4);
+        vmeta[n] = *(const uint32_t *)(head + tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 4);
     }
 
-    // ---- scores (log2 domain)
+    // ---- scores
     float s[G][NLK];
 #pragma unroll
     for (int n = 0; n < NLK; ++n) {
-      float x[FK::EPL];
-      decode16<KF>(kw[n], x);
-      float ks = 1.0f, kz = 0.0f;
-      if constexpr (KF == TTKV_I8_SYM_G32) ks = h2f((uint16_t)kmeta[n]);
+      uint32_t kr[QN];
+      unpack16<KF>(kw[n], kr);
+      float ks = cs, kz = 0.0f;
+      if constexpr (KF == TTKV_I8_SYM_G32) ks = h2f((uint16_t)kmeta[n]) * cs;
       if constexpr (KF == TTKV_I4_ASYM_G64) {
-        ks = h2f((uint16_t)(kmeta[n] & 0xffff));
+        ks = h2f((uint16_t)(kmeta[n] & 0xffff)) * cs;
         kz = h2f((uint16_t)(kmeta[n] >> 16));
       }
       const bool valid = n * FK::TPL + ktok < nv;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float d = 0.0f;
+        float d0 = 0.0f, d1 = 0.0f;
 #pragma unroll
-        for (int e = 0; e < FK::EPL; ++e) d = fmaf(x[e], q[g][e], d);
-        if constexpr (KQ) d = d * ks + kz * qsum[g];
-#pragma unroll
-        for (int msk = 1; msk < FK::LPT; msk <<= 1) d += __shfl_xor(d, msk);
+        for (int r = 0; r < QN; r += 2) {
+          if constexpr (KF == TTKV_BF16) {
+            d0 = __builtin_amdgcn_fdot2_f32_bf16(as_b2(kr[r]), as_b2(qp[g][r]), d0, false);
+            d1 = __builtin_amdgcn_fdot2_f32_bf16(as_b2(kr[r + 1]), as_b2(qp[g][r + 1]), d1, false);
+          } else {
+            d0 = __builtin_amdgcn_fdot2(as_h2(kr[r]), as_h2(qp[g][r]), d0, false);
+            d1 = __builtin_amdgcn_fdot2(as_h2(kr[r + 1]), as_h2(qp[g][r + 1]), d1, false);
+          }
+        }
+        float d = d0 + d1;
+        if constexpr (KQ) d -= qoff[g];
+        d *= ks;
+        if constexpr (KF == TTKV_I4_ASYM_G64) d = fmaf(kz, qsum[g], d);
+        d = group_sum<FK::LPT>(d);
         s[g][n] = valid ? d : -INFINITY;
       }
     }
 
-    // ---- online softmax
+    // ---- online softmax (base 2)
     float p[G][NLK];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float mt = s[g][0];
-#pragma unroll
-      for (int n = 1; n < NLK; ++n) mt = fmaxf(mt, s[g][n]);
+      float mt = fmaxf(fmaxf(s[g][0], s[g][1]), fmaxf(s[g][2], s[g][3]));
       mt = wave_max(mt);
       if (mt > m[g]) {  // wave-uniform
         const float alpha = exp2f(m[g] - mt);
         l[g] *= alpha;
         zacc[g] *= alpha;
+        psum[g] *= alpha;
 #pragma unroll
         for (int e = 0; e < FV::EPL; ++e) acc[g][e] *= alpha;
         m[g] = mt;
@@ -221,18 +281,17 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
     // ---- weighted V
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
-      float x[FV::EPL];
-      decode16<VF>(vw[n], x);
+      uint32_t vr[FV::EPL / 2];
+      unpack16<VF>(vw[n], vr);
       float vs = 1.0f, vz = 0.0f;
       if constexpr (VF == TTKV_I8_SYM_G32) vs = h2f((uint16_t)vmeta[n]);
       if constexpr (VF == TTKV_I4_ASYM_G64) {
         vs = h2f((uint16_t)(vmeta[n] & 0xffff));
         vz = h2f((uint16_t)(vmeta[n] >> 16));
       }
-      const bool valid = n * FV::TPL + vtok < nv;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float pv;
+        float pv;   // 0 for rows past the end of the chunk: their score is -inf
         if constexpr (R == 1) {
           pv = p[g][n];
         } else {
@@ -245,47 +304,102 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
             if (vtok / FK::TPL == rr) pv = cand;
           }
         }
-        if (!valid) pv = 0.0f;
         if constexpr (VF == TTKV_I4_ASYM_G64) zacc[g] = fmaf(pv, vz, zacc[g]);
-        if constexpr (VQ) pv *= vs;
+        if constexpr (VQ) {
+          pv *= vs;
+          psum[g] += pv;
+        }
 #pragma unroll
-        for (int e = 0; e < FV::EPL; ++e) acc[g][e] = fmaf(pv, x[e], acc[g][e]);
+        for (int e = 0; e < FV::EPL; ++e) {
+          const uint32_t reg = vr[pair_reg<VF>(e)];
+          float x;
+          if constexpr (VF == TTKV_BF16)
+            x = pair_half<VF>(e) ? __uint_as_float(reg & 0xffff0000u) : __uint_as_float(reg << 16);
+          else
+            x = pair_half<VF>(e) ? (float)as_h2(reg).y : (float)as_h2(reg).x;
+          acc[g][e] = fmaf(x, pv, acc[g][e]);
+        }
       }
     }
   }
 
-  // ---- reduce the wave: lanes with the same V slice hold partial sums over different tokens
+  // ---- reduce: lanes with the same V slice hold sums over different tokens.  Within a
+  // row of 16 lanes by DPP rotations, across the 4 rows and 4 waves through LDS.
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     l[g] = wave_sum(l[g]);
 #pragma unroll
     for (int e = 0; e < FV::EPL; ++e) {
       float v = acc[g][e] + zacc[g];
-#pragma unroll
-      for (int msk = FV::LPT; msk < 64; msk <<= 1) v += __shfl_xor(v, msk);
+      if constexpr (VQ) v = fmaf(-elem_offset<VF>(e), psum[g], v);
+      if constexpr (FV::LPT <= 4) v += dpp<0x124>(v);   // row_ror:4
+      if constexpr (FV::LPT <= 8) v += dpp<0x128>(v);   // row_ror:8  (after ror:4 this completes the 4-lane stride sum)
       acc[g][e] = v;
     }
-    if (vtok == 0) {
+    if ((lane & 15) < FV::LPT) {
 #pragma unroll
-      for (int e = 0; e < FV::EPL; ++e) s_acc[wave][g][vslice * FV::EPL + e] = acc[g][e];
+      for (int e = 0; e < FV::EPL; ++e) s_acc[wave][lane >> 4][g][vslice * FV::EPL + e] = acc[g][e];
     }
     if (lane == 0) {
       s_m[wave][g] = m[g];
       s_l[wave][g] = l[g];
     }
   }
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
+  __shared__ float s_acc[4][4][G][128];   // [wave][row of 16 lanes][head][channel]
+  __shared__ float s_m[4][G], s_l[4][G];
+
+  const int item = blockIdx.x;
+  const int hkv = blockIdx.y;
+  const int Gtot = a.Hq / a.Hkv;
+  const int hq0 = hkv * Gtot + blockIdx.z * G;
+
+  int lo = 0, hi = a.n_entries - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (a.e[mid].item_start <= item) lo = mid; else hi = mid - 1;
+  }
+  const Entry en = a.e[lo];
+  const int tier = (en.tier_seq >> 16) & 0xff, seq = en.tier_seq & 0xffff;
+  TierView tv = a.tv[tier];
+  if (en.tier_seq >> 24) tv.table = nullptr;   // the run names pool records directly
+  const int chunk_tokens = a.chunk[tier];
+  const int chunk = item - en.item_start;
+
+  const int combo = tv.k_fmt * 8 + tv.v_fmt;
+  switch (combo) {
+    case TTKV_F16 * 8 + TTKV_F16:
+      process<TTKV_F16, TTKV_F16, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+    case TTKV_BF16 * 8 + TTKV_BF16:
+      process<TTKV_BF16, TTKV_BF16, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32:
+      process<TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+    case TTKV_I4_ASYM_G64 * 8 + TTKV_I4_ASYM_G64:
+      process<TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+    default:
+      process<TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+  }
   __syncthreads();
 
-  // ---- merge the four waves and write the workgroup's partial
-  const int part = a.st.part_base[j] + chunk;
+  // ---- merge the four waves (each with its own running max) and write the item's partial
+  const int part = en.part_base + chunk;
   for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
     const int g = idx >> 7, dch = idx & 127;
-    float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
+    const float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
     float o = 0.0f, ll = 0.0f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float wgt = s_m[w][g] == -INFINITY ? 0.0f : exp2f(s_m[w][g] - M);
-      o = fmaf(s_acc[w][g][dch], wgt, o);
+      const float rows = (s_acc[w][0][g][dch] + s_acc[w][1][g][dch]) + (s_acc[w][2][g][dch] + s_acc[w][3][g][dch]);
+      o = fmaf(rows, wgt, o);
       ll = fmaf(s_l[w][g], wgt, ll);
     }
     const int64_t prow = ((int64_t)seq * a.Hq + hq0 + g) * a.part_stride + part;
@@ -297,9 +411,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const AttnArgs a) {
   }
 }
 
-// One workgroup of 128 threads per row: thread = channel.
-__global__ __launch_bounds__(128) void merge_kernel(const MergeArgs a) {
-  const int row = blockIdx.x, dch = threadIdx.x;
+// One workgroup of 256 threads per row: two halves of the parts, thread = channel.
+__global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
+  __shared__ float s_o[128], s_l2, s_M[2];
+  const int row = blockIdx.x, dch = threadIdx.x & 127, half = threadIdx.x >> 7;
   int n = a.n_parts;
   if (a.n_parts_row)
     n = a.n_parts_row[row];
@@ -308,28 +423,38 @@ __global__ __launch_bounds__(128) void merge_kernel(const MergeArgs a) {
   const float *pm = a.m + (int64_t)row * a.part_stride;
   const float *pl = a.l + (int64_t)row * a.part_stride;
   const float *pa = a.acc + (int64_t)row * a.part_stride * 128;
+  // global max over all parts: each thread scans a strided subset, then a block reduce
+  __shared__ float s_red[256];
   float M = -INFINITY;
-  for (int p = 0; p < n; ++p) M = fmaxf(M, pm[p]);
+  for (int p = threadIdx.x; p < n; p += 256) M = fmaxf(M, pm[p]);
+  s_red[threadIdx.x] = M;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) s_red[threadIdx.x] = fmaxf(s_red[threadIdx.x], s_red[threadIdx.x + s]);
+    __syncthreads();
+  }
+  M = s_red[0];
   float o = 0.0f, l = 0.0f;
-  for (int p = 0; p < n; ++p) {
+  const int p0 = half ? (n + 1) / 2 : 0, p1 = half ? n : (n + 1) / 2;
+#pragma unroll 4
+  for (int p = p0; p < p1; ++p) {
     const float mp = pm[p];
-    if (mp == -INFINITY) continue;
-    const float w = __expf(mp - M);
+    const float w = mp == -INFINITY ? 0.0f : __expf(mp - M);
     o = fmaf(pa[(int64_t)p * 128 + dch], w, o);
     l = fmaf(pl[p], w, l);
   }
-  a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
-  if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? M + __logf(l) : -INFINITY;
-}
-
-template <int KF, int VF>
-hipError_t launch_g(const AttnArgs &a, hipStream_t s, int G, dim3 grid) {
-  switch (G) {
-    case 1: hipLaunchKernelGGL((attn_partial_kernel<KF, VF, 1>), grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((attn_partial_kernel<KF, VF, 2>), grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((attn_partial_kernel<KF, VF, 4>), grid, dim3(256), 0, s, a); break;
+  if (half) {
+    s_o[dch] = o;
+    if (dch == 0) s_l2 = l;
   }
-  return hipGetLastError();
+  __syncthreads();
+  if (!half) {
+    o += s_o[dch];
+    l += s_l2;
+    a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
+    if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? M + __logf(l) : -INFINITY;
+  }
+  (void)s_M;
 }
 
 int group_width(int Gtot) { return Gtot % 4 == 0 ? 4 : (Gtot % 2 == 0 ? 2 : 1); }
@@ -342,26 +467,23 @@ bool attn_supported(int k_fmt, int v_fmt, int G) {
   return k_fmt == TTKV_I8_SYM_G32 && v_fmt == TTKV_I4_ASYM_G64;
 }
 
-hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s, int *n_kernels) {
-  const int items = a.st.item_start[a.st.n_seq];
-  if (items <= 0) return hipSuccess;
+hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels) {
+  if (a.n_items <= 0) return hipSuccess;
   const int Gtot = a.Hq / a.Hkv;
   const int G = group_width(Gtot);
-  dim3 grid(items, a.Hkv, Gtot / G);
+  dim3 grid(a.n_items, a.Hkv, Gtot / G);
   ++*n_kernels;
-  const int kf = a.tv.k_fmt, vf = a.tv.v_fmt;
-  if (kf == TTKV_F16 && vf == TTKV_F16) return launch_g<TTKV_F16, TTKV_F16>(a, s, G, grid);
-  if (kf == TTKV_BF16 && vf == TTKV_BF16) return launch_g<TTKV_BF16, TTKV_BF16>(a, s, G, grid);
-  if (kf == TTKV_I8_SYM_G32 && vf == TTKV_I8_SYM_G32) return launch_g<TTKV_I8_SYM_G32, TTKV_I8_SYM_G32>(a, s, G, grid);
-  if (kf == TTKV_I4_ASYM_G64 && vf == TTKV_I4_ASYM_G64) return launch_g<TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64>(a, s, G, grid);
-  if (kf == TTKV_I8_SYM_G32 && vf == TTKV_I4_ASYM_G64) return launch_g<TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64>(a, s, G, grid);
-  --*n_kernels;
-  return hipErrorInvalidValue;
+  switch (G) {
+    case 1: hipLaunchKernelGGL(attn_fused_kernel<1>, grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL(attn_fused_kernel<2>, grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL(attn_fused_kernel<4>, grid, dim3(256), 0, s, a); break;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_merge(const MergeArgs &a, hipStream_t s) {
   if (a.rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_kernel, dim3(a.rows), dim3(128), 0, s, a);
+  hipLaunchKernelGGL(merge_kernel, dim3(a.rows), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

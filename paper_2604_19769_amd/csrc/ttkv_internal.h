@@ -78,7 +78,7 @@ struct Handle {
   hipEvent_t fence2;    // orders device->host eviction copies behind the quantize kernel
   ttkv_stats stats;
   // optional per-call timing of one device tier's partial kernel
-  int time_tier;
+  bool time_on;
   int time_max, time_n;
   hipEvent_t *time_ev;  // 2 * time_max events
 };
@@ -127,18 +127,30 @@ struct ConvArgs {
 hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels);
 hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels);
 
-struct AttnArgs {
-  TierView tv;
-  SeqTable st;
+// One launch of the fused attention kernel: up to TTKV_MAX_ENTRIES runs of tokens,
+// each belonging to one (tier, sequence), all passed by value (no per-step upload).
+#define TTKV_MAX_ENTRIES 120
+struct Entry {
+  int32_t tier_seq;     // bit 24: ignore the block table (rec_base is a pool record); bits 16-23 tier; low 16 sequence
+  int32_t rec_base;     // record of ring block 0 (no table) or of the run's first block
+  int32_t first_tok;    // ring token index of the run's first token (multiple of 64)
+  int32_t len;          // tokens
+  int32_t item_start;   // first work item (chunk) of the run in this launch
+  int32_t part_base;    // first partial index of the run
+};
+struct FusedArgs {
+  TierView tv[TTKV_MAX_TIERS];
+  int32_t chunk[TTKV_MAX_TIERS];
+  Entry e[TTKV_MAX_ENTRIES];
+  int32_t n_entries, n_items;
   const void *q;
   int32_t q_fmt;
   float *pm, *pl, *pacc;
   int32_t part_stride;
   int32_t Hq, Hkv;
   float scale;
-  int32_t chunk_tokens;
 };
-hipError_t launch_attn_partial(const AttnArgs &a, hipStream_t s, int *n_kernels);
+hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels);
 bool attn_supported(int k_fmt, int v_fmt, int G);
 
 struct MergeArgs {

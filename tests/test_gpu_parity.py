@@ -76,9 +76,9 @@ def test_quantize_append_bit_exact(dtype, fmt):
         p.close()
 
 
-def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None,
+def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
                lens=None, peaked=False):
-    p = Pair(B_, Hq, Hkv, tiers, dtype)
+    p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots)
     worst = 0.0
     try:
         g = synth.rng(seed)
@@ -134,26 +134,37 @@ def test_gqa_ratios_and_ragged_lengths(Hq, Hkv):
     run_config(3, Hq, Hkv, tiers3("bf16", host=False), "bf16", None, 3, synth.SEED_BASE + 3 + Hq, lens=[1, 777, 2500])
 
 
-def test_three_tiers_with_host_streaming_and_eviction_cascade():
-    """fp16 -> int8 (HBM) -> int4 (pinned host, streamed block by block): 150 steps cross several
-    evictions of both device tiers; state compared along the way."""
-    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150, synth.SEED_BASE + 4, check_state_every=50)
+@pytest.mark.parametrize("n_slots", [0, 2, 3])
+def test_three_tiers_with_host_streaming_and_eviction_cascade(n_slots):
+    """fp16 -> int8 (HBM) -> int4 (pinned host): 150 steps cross several evictions of both device tiers;
+    state compared along the way.  n_slots 0: the kernel reads the host records in place;
+    2, 3: block copies into staging slots, event-chained with the attention kernels."""
+    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150 if n_slots != 3 else 20, synth.SEED_BASE + 4,
+               check_state_every=50, n_slots=n_slots)
 
 
 def test_host_tier_no_overlap_gives_the_same_result():
-    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 3, synth.SEED_BASE + 4, overlap=False)
+    run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 3, synth.SEED_BASE + 4, overlap=False, n_slots=2)
 
 
-def test_paged_tiers_with_ragged_batch():
+@pytest.mark.parametrize("n_slots", [0, 2])
+def test_paged_tiers_with_ragged_batch(n_slots):
     """Shuffled block tables (paged KV) on the int8 and host tiers, ragged contexts."""
     run_config(4, 8, 2, tiers3("f16", paged=True, rings=(6, 8, 12)), "f16", None, 70, synth.SEED_BASE + 5,
-               lens=[300, 1500, 2900, 2047], check_state_every=35)
+               lens=[300, 1500, 2900, 2047], check_state_every=35, n_slots=n_slots)
 
 
-def test_sparse_block_selection():
+@pytest.mark.parametrize("n_slots", [0, 2])
+def test_sparse_block_selection(n_slots):
     """Block identification: mean-key summaries, phi, top-k; only selected host blocks are fetched."""
     tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
-    run_config(2, 8, 2, tiers, "bf16", 3500, 40, synth.SEED_BASE + 6, select_k=6, check_state_every=20)
+    run_config(2, 8, 2, tiers, "bf16", 3500, 40, synth.SEED_BASE + 6, select_k=6, check_state_every=20, n_slots=n_slots)
+
+
+def test_bf16_query_on_fp16_and_quantized_tiers_and_large_batch():
+    """bf16 queries over int8/int4 tiers with more (tier, sequence) runs than one launch table holds."""
+    tiers = tiers3("bf16", host=False, bts=(64, 64, 64), caps=(128, 192), rings=(3, 5, 8))
+    run_config(48, 4, 2, tiers, "bf16", None, 2, synth.SEED_BASE + 9, lens=[50 + 11 * i for i in range(48)])
 
 
 def test_summaries_match_the_oracle_bit_for_bit():

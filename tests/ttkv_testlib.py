@@ -22,7 +22,7 @@ def dev(x, dtype, device="cuda:0"):
 class Pair:
     """tiers: list of dicts(k_fmt, v_fmt, capacity, block_tokens, ring_blocks, mem, paged_seed, summary)."""
 
-    def __init__(self, B, Hq, Hkv, tiers, dtype, oracle_max_tokens=None, n_slots=2):
+    def __init__(self, B, Hq, Hkv, tiers, dtype, oracle_max_tokens=None, n_slots=0):
         self.B, self.Hq, self.Hkv, self.dtype = B, Hq, Hkv, dtype
         self.tiers = tiers
         self.gpu = TieredCache(B, Hq, Hkv, [TierConfig(t["k_fmt"], t["v_fmt"], t["capacity"], t["block_tokens"],
