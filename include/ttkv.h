@@ -131,8 +131,12 @@ ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *ti
 size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots);
 size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
 /* Parts per (sequence, query head) ttkv_decode_attn would use right now with this n_slots. */
-int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
-                         int32_t n_slots);
+int32_t ttkv_count_parts(ttkv_handle h, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
+                         int32_t sel_stride, int32_t n_slots);
+/* Split-K granularity: ttkv_decode_attn cuts the device-resident tiers into about
+ * target_items work items of equal bytes (before multiplying by KV heads);
+ * 0 restores the default.  More items: better balance over 256 CUs, more partials. */
+ttkv_status ttkv_set_split(ttkv_handle h, int32_t target_items);
 
 /* Append n_tokens at the tail of `tier` (Sec. 4.1 "newly generated tokens are
  * appended to the fast tier"; also the bulk loader of any device tier).

@@ -45,7 +45,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
-    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing", "ttkv_set_split",
 ]
 
 _lib = None
@@ -83,7 +83,8 @@ def lib():
         L.ttkv_demote_workspace_bytes.restype = sz
         L.ttkv_append_host_workspace_bytes.argtypes = [cp, i32, i32, i64]
         L.ttkv_append_host_workspace_bytes.restype = sz
-        L.ttkv_count_parts.argtypes = [cp, p, p, i32, i32]
+        L.ttkv_count_parts.argtypes = [p, cp, p, p, i32, i32]
+        L.ttkv_set_split.argtypes = [p, i32]
         L.ttkv_count_parts.restype = i32
         L.ttkv_quantize_append.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p]
         L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
@@ -163,8 +164,12 @@ def ttkv_append_host_workspace_bytes(cache, tier, seq, n_tokens):
     return lib().ttkv_append_host_workspace_bytes(C.byref(cache), tier, seq, n_tokens)
 
 
-def ttkv_count_parts(cache, sel_blocks=None, sel_count=None, sel_stride=0, n_slots=0):
-    return lib().ttkv_count_parts(C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride, n_slots)
+def ttkv_count_parts(h, cache, sel_blocks=None, sel_count=None, sel_stride=0, n_slots=0):
+    return lib().ttkv_count_parts(h, C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride, n_slots)
+
+
+def ttkv_set_split(h, target_items):
+    _check(lib().ttkv_set_split(h, target_items), "ttkv_set_split")
 
 
 def ttkv_quantize_append(h, cache, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, stream):

@@ -144,7 +144,7 @@ class TieredCache:
         if selected is not None:
             sb, sc = selected
             stride = sb.shape[1]
-        parts = B.ttkv_count_parts(self.c, sb, sc, stride, self.n_slots)
+        parts = B.ttkv_count_parts(self.h, self.c, sb, sc, stride, self.n_slots)
         if parts < 0:
             raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
         ws = self._workspace(max(parts, 1))

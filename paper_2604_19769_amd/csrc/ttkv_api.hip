@@ -101,6 +101,8 @@ struct Fetch {
   int part_base;
   int chunk;
 };
+constexpr int kDefaultItems = 2560;   // ~10 work items per CU per (KV head) launch
+
 struct Plan {
   std::vector<Run> runs;
   std::vector<Fetch> fetch;
@@ -111,23 +113,31 @@ struct Plan {
   ttkv_status status;
 };
 
-int pick_chunk(const ttkv_cache *c, int t) {
-  const ttkv_tier &T = c->tier[t];
-  int64_t total = 0;
-  for (int b = 0; b < c->batch; ++b) total += T.len[b];
+// Tokens per work item of tier t so that every item of the fused launch streams
+// about the same number of bytes: total bytes of the in-place tiers / target_items.
+int pick_chunk(const ttkv_cache *c, int t, bool staged, int target_items) {
   const int G = c->n_q_heads / c->n_kv_heads;
   const int n_hg = G % 4 == 0 ? G / 4 : (G % 2 == 0 ? G / 2 : G);
-  // aim at ~3072 workgroups (12 per CU) with chunks of 256..4096 tokens
-  int64_t want = total * c->n_kv_heads * n_hg / 3072;
-  int64_t lo = is_fp(T.k_fmt) ? 128 : 256;
-  want = std::max<int64_t>(lo, std::min<int64_t>(4096, want));
+  int64_t total = 0;
+  for (int u = 0; u < c->n_tiers; ++u) {
+    const ttkv_tier &U = c->tier[u];
+    if (U.mem == TTKV_MEM_HOST_PINNED) continue;   // host tiers get fixed 256-token items
+    int64_t tokens = 0;
+    for (int b = 0; b < c->batch; ++b) tokens += U.len[b];
+    total += tokens * c->n_kv_heads * n_hg * (fmt_bytes(U.k_fmt).code + fmt_bytes(U.k_fmt).meta + fmt_bytes(U.v_fmt).code + fmt_bytes(U.v_fmt).meta);
+  }
+  (void)staged;
+  const ttkv_tier &T = c->tier[t];
+  const int64_t per_token = fmt_bytes(T.k_fmt).code + fmt_bytes(T.k_fmt).meta + fmt_bytes(T.v_fmt).code + fmt_bytes(T.v_fmt).meta;
+  int64_t want = total / std::max(1, target_items) / per_token;
+  want = std::max<int64_t>(256, std::min<int64_t>(8192, want));
   return (int)((want + 63) / 64 * 64);
 }
 
 // staged: host tiers are copied block by block into staging slots (one kernel per
 // copy); otherwise the fused kernel reads them in place.
 void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, bool staged,
-                Plan *P) {
+                int target_items, Plan *P) {
   P->status = TTKV_OK;
   P->slot_bytes = 0;
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
@@ -137,7 +147,7 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const Layout L = make_layout(T, c->n_kv_heads);
     const bool sparse = sel_blocks && t == last;
     const bool host = T.mem == TTKV_MEM_HOST_PINNED;
-    P->chunk[t] = (host || sparse) ? std::min(L.bt, 256) : pick_chunk(c, t);
+    P->chunk[t] = (host || sparse) ? std::min(L.bt, 256) : pick_chunk(c, t, staged, target_items);
     const int chunk = P->chunk[t];
     if (!sparse && !(host && staged)) {
       for (int b = 0; b < c->batch; ++b) {
@@ -378,6 +388,7 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   Handle *h = new (std::nothrow) Handle();
   if (!h) return TTKV_ERR_INVALID_ARG;
   h->have_events = false;
+  h->target_items = kDefaultItems;
   h->time_on = false;
   h->time_max = h->time_n = 0;
   h->time_ev = nullptr;
@@ -480,11 +491,12 @@ size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32
   return (size_t)(seq < 0 ? c->batch : 1) * touched * L.rec_bytes;
 }
 
-int32_t ttkv_count_parts(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
-                         int32_t n_slots) {
-  if (validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
+int32_t ttkv_count_parts(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
+                         int32_t sel_stride, int32_t n_slots) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items, &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
 }
 
@@ -622,7 +634,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   const bool staged = n_slots > 0;
 
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, staged, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items, &P);
   if (P.status != TTKV_OK) return P.status;
   if (!workspace) return TTKV_ERR_WORKSPACE;
   // workspace = [n_slots staging slots][m][l][acc]
@@ -803,6 +815,13 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
   TTKV_HIP(h, hipMemcpyAsync(sel_blocks, a.sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
                              hipMemcpyDeviceToHost, stream));
   TTKV_HIP(h, hipStreamSynchronize(stream));
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_set_split(ttkv_handle hh, int32_t target_items) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || target_items < 0 || target_items > (1 << 20)) return TTKV_ERR_INVALID_ARG;
+  h->target_items = target_items ? target_items : kDefaultItems;
   return TTKV_OK;
 }
 

@@ -28,6 +28,8 @@
 
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 namespace ttkv {
 
 namespace {
@@ -66,9 +68,21 @@ __device__ __forceinline__ constexpr float elem_offset(int e) {
   return F == TTKV_I4_ASYM_G64 ? ((e % 2) ? 64.0f : 1024.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
 }
 
+// Bit patterns used to splice int4 codes into fp16 mantissas.  They are kept in
+// registers the compiler cannot see through (two SGPR masks, two VGPR constants):
+// gfx9 VOP3 encodings take no literals, and with literals the compiler falls back
+// to v_and + v_or instead of one v_and_or_b32 per pair.
+struct Splice {
+  uint32_t m0, m1, c0, c1;
+  __device__ __forceinline__ void init() {
+    m0 = 0x000F000Fu; m1 = 0x00F000F0u; c0 = 0x64006400u; c1 = 0x54005400u;
+    asm volatile("" : "+s"(m0), "+s"(m1), "+v"(c0), "+v"(c1));
+  }
+};
+
 // 16 bytes of a row -> EPL/2 registers of packed 16-bit pairs (fp16, or bf16 for the bf16 tier).
 template <int F>
-__device__ __forceinline__ void unpack16(const uint4 &w, uint32_t *r) {
+__device__ __forceinline__ void unpack16(const uint4 &w, uint32_t *r, const Splice &k) {
   const uint32_t u[4] = {w.x, w.y, w.z, w.w};
   if constexpr (F == TTKV_F16 || F == TTKV_BF16) {
 #pragma unroll
@@ -84,10 +98,10 @@ __device__ __forceinline__ void unpack16(const uint4 &w, uint32_t *r) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t x = u[i], y = u[i] >> 8;
-      r[4 * i + 0] = (x & 0x000F000Fu) | 0x64006400u;   // (1024 + n0, 1024 + n4)
-      r[4 * i + 1] = (x & 0x00F000F0u) | 0x54005400u;   // (  64 + n1,   64 + n5)
-      r[4 * i + 2] = (y & 0x000F000Fu) | 0x64006400u;   // (1024 + n2, 1024 + n6)
-      r[4 * i + 3] = (y & 0x00F000F0u) | 0x54005400u;   // (  64 + n3,   64 + n7)
+      r[4 * i + 0] = (x & k.m0) | k.c0;   // (1024 + n0, 1024 + n4)
+      r[4 * i + 1] = (x & k.m1) | k.c1;   // (  64 + n1,   64 + n5)
+      r[4 * i + 2] = (y & k.m0) | k.c0;   // (1024 + n2, 1024 + n6)
+      r[4 * i + 3] = (y & k.m1) | k.c1;   // (  64 + n3,   64 + n7)
     }
   }
 }
@@ -150,23 +164,30 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
   float qoff[G], qsum[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint16_t *qsrc = (const uint16_t *)a.q + ((int64_t)seq * a.Hq + hq0 + g) * 128 + kslice * FK::EPL;
+    // EPL 16-bit values = EPL/8 aligned 128-bit loads; one wave-uniform branch on the query type
+    const uint4 *qsrc = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hq0 + g) * 128 + kslice * FK::EPL);
+    uint32_t qw[FK::EPL / 2];
+#pragma unroll
+    for (int i = 0; i < FK::EPL / 8; ++i) {
+      const uint4 w = qsrc[i];
+      qw[4 * i] = w.x; qw[4 * i + 1] = w.y; qw[4 * i + 2] = w.z; qw[4 * i + 3] = w.w;
+    }
+    if constexpr (KF != TTKV_BF16) {
+      if (a.q_fmt == TTKV_BF16) {   // bf16 -> fp16 (exact inside the fp16 normal range, clamped outside)
+#pragma unroll
+        for (int i = 0; i < FK::EPL / 2; ++i) {
+          const float lo = fminf(fmaxf(__uint_as_float(qw[i] << 16), -65504.0f), 65504.0f);
+          const float hi = fminf(fmaxf(__uint_as_float(qw[i] & 0xffff0000u), -65504.0f), 65504.0f);
+          qw[i] = (uint32_t)__half_as_ushort(__float2half_rn(lo)) | ((uint32_t)__half_as_ushort(__float2half_rn(hi)) << 16);
+        }
+      }
+    }
     uint16_t qb[FK::EPL];
     float so = 0.0f, ss = 0.0f;
 #pragma unroll
     for (int e = 0; e < FK::EPL; ++e) {
-      uint16_t raw = qsrc[e];
-      float v;
-      if constexpr (KF == TTKV_BF16) {
-        v = __uint_as_float((uint32_t)raw << 16);   // a bf16 tier is only ever given bf16 queries (checked on the host)
-      } else {
-        if (a.q_fmt == TTKV_BF16) {
-          const float f = fminf(fmaxf(__uint_as_float((uint32_t)raw << 16), -65504.0f), 65504.0f);
-          raw = __half_as_ushort(__float2half_rn(f));
-        }
-        v = h2f(raw);
-      }
-      qb[e] = raw;
+      qb[e] = (uint16_t)(qw[e / 2] >> (16 * (e % 2)));
+      const float v = KF == TTKV_BF16 ? __uint_as_float((uint32_t)qb[e] << 16) : h2f(qb[e]);
       ss += v;
       so = fmaf(v, elem_offset<KF>(e), so);
     }
@@ -188,53 +209,66 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
     for (int e = 0; e < FV::EPL; ++e) acc[g][e] = 0.0f;
   }
 
-  for (int i0 = c0 + wave * TT; i0 < c1; i0 += 4 * TT) {
-    const int nv = min(TT, c1 - i0);
+  Splice sp;
+  sp.init();
+
+  // Registers of one tile of TT tokens in flight.
+  struct TileRegs {
+    uint4 kw[NLK], vw[NLV];
+    uint32_t kmeta[NLK], vmeta[NLV];
+  };
+
+  // Issue every load of the tile at i0.  FULL: every row is live (no clamping).
+  auto load_tile = [&](TileRegs &t, int i0, int nv, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     int tok0 = en.first_tok + i0;
     if (tok0 >= ring_tokens) tok0 -= ring_tokens;
     const int rb = tok0 / tv.bt;
     const int row0 = tok0 - rb * tv.bt;
     const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
     const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
-
-    // ---- issue every load of the tile
-    uint4 kw[NLK], vw[NLV];
-    uint32_t kmeta[NLK], vmeta[NLV];
 #pragma unroll
     for (int n = 0; n < NLK; ++n) {
-      const int t = min(n * FK::TPL + ktok, nv - 1);
-      kw[n] = *(const uint4 *)(head + (row0 + t) * FK::ROWB + kslice * 16);
+      const int r = FULL ? n * FK::TPL + ktok : min(n * FK::TPL + ktok, nv - 1);
+      t.kw[n] = *(const uint4 *)(head + (row0 + r) * FK::ROWB + kslice * 16);
       if constexpr (KF == TTKV_I8_SYM_G32)
-        kmeta[n] = *(const uint16_t *)(head + tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 2);
+        t.kmeta[n] = *(const uint16_t *)(head + tv.k_meta_off + (row0 + r) * 8 + (kslice >> 1) * 2);
       else if constexpr (KF == TTKV_I4_ASYM_G64)
-        kmeta[n] = *(const uint32_t *)(head + tv.k_meta_off + (row0 + t) * 8 + (kslice >> 1) * 4);
+        t.kmeta[n] = *(const uint32_t *)(head + tv.k_meta_off + (row0 + r) * 8 + (kslice >> 1) * 4);
     }
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
-      const int t = min(n * FV::TPL + vtok, nv - 1);
-      vw[n] = *(const uint4 *)(head + tv.v_off + (row0 + t) * FV::ROWB + vslice * 16);
+      const int r = FULL ? n * FV::TPL + vtok : min(n * FV::TPL + vtok, nv - 1);
+      t.vw[n] = *(const uint4 *)(head + tv.v_off + (row0 + r) * FV::ROWB + vslice * 16);
       if constexpr (VF == TTKV_I8_SYM_G32)
-        vmeta[n] = *(const uint16_t *)(head + tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 2);
+        t.vmeta[n] = *(const uint16_t *)(head + tv.v_meta_off + (row0 + r) * 8 + (vslice >> 1) * 2);
       else if constexpr (VF == TTKV_I4_ASYM_G64)
-        vmeta[n] = *(const uint32_t *)(head + tv.v_meta_off + (row0 + t) * 8 + (vslice >> 1) * 4);
+        t.vmeta[n] = *(const uint32_t *)(head + tv.v_meta_off + (row0 + r) * 8 + (vslice >> 1) * 4);
     }
+  };
 
-    // ---- scores
+  // Scores, online softmax and weighted V of one loaded tile.
+  auto compute_tile = [&](const TileRegs &t, int nv, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const uint4 *kw = t.kw, *vw = t.vw;
+    const uint32_t *kmeta = t.kmeta, *vmeta = t.vmeta;
+    (void)kmeta; (void)vmeta;
+
+    // ---- scores (log2 domain)
     float s[G][NLK];
 #pragma unroll
     for (int n = 0; n < NLK; ++n) {
       uint32_t kr[QN];
-      unpack16<KF>(kw[n], kr);
+      unpack16<KF>(kw[n], kr, sp);
       float ks = cs, kz = 0.0f;
       if constexpr (KF == TTKV_I8_SYM_G32) ks = h2f((uint16_t)kmeta[n]) * cs;
       if constexpr (KF == TTKV_I4_ASYM_G64) {
         ks = h2f((uint16_t)(kmeta[n] & 0xffff)) * cs;
         kz = h2f((uint16_t)(kmeta[n] >> 16));
       }
-      const bool valid = n * FK::TPL + ktok < nv;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float d0 = 0.0f, d1 = 0.0f;
+        float d0 = KQ ? -qoff[g] : 0.0f, d1 = 0.0f;   // the splice offsets leave with the initial value
 #pragma unroll
         for (int r = 0; r < QN; r += 2) {
           if constexpr (KF == TTKV_BF16) {
@@ -245,12 +279,10 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
             d1 = __builtin_amdgcn_fdot2(as_h2(kr[r + 1]), as_h2(qp[g][r + 1]), d1, false);
           }
         }
-        float d = d0 + d1;
-        if constexpr (KQ) d -= qoff[g];
-        d *= ks;
+        float d = (d0 + d1) * ks;
         if constexpr (KF == TTKV_I4_ASYM_G64) d = fmaf(kz, qsum[g], d);
         d = group_sum<FK::LPT>(d);
-        s[g][n] = valid ? d : -INFINITY;
+        s[g][n] = (FULL || n * FK::TPL + ktok < nv) ? d : -INFINITY;
       }
     }
 
@@ -261,7 +293,7 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
       float mt = fmaxf(fmaxf(s[g][0], s[g][1]), fmaxf(s[g][2], s[g][3]));
       mt = wave_max(mt);
       if (mt > m[g]) {  // wave-uniform
-        const float alpha = exp2f(m[g] - mt);
+        const float alpha = __builtin_amdgcn_exp2f(m[g] - mt);
         l[g] *= alpha;
         zacc[g] *= alpha;
         psum[g] *= alpha;
@@ -272,7 +304,7 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
       float ps = 0.0f;
 #pragma unroll
       for (int n = 0; n < NLK; ++n) {
-        p[g][n] = exp2f(s[g][n] - m[g]);
+        p[g][n] = __builtin_amdgcn_exp2f(s[g][n] - m[g]);
         ps += p[g][n];
       }
       if (kslice == 0) l[g] += ps;
@@ -282,7 +314,7 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
       uint32_t vr[FV::EPL / 2];
-      unpack16<VF>(vw[n], vr);
+      unpack16<VF>(vw[n], vr, sp);
       float vs = 1.0f, vz = 0.0f;
       if constexpr (VF == TTKV_I8_SYM_G32) vs = h2f((uint16_t)vmeta[n]);
       if constexpr (VF == TTKV_I4_ASYM_G64) {
@@ -320,6 +352,19 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
           acc[g][e] = fmaf(x, pv, acc[g][e]);
         }
       }
+    }
+  };
+
+  {
+    TileRegs ra;
+    int i0 = c0 + wave * TT;
+    for (; i0 + TT <= c1; i0 += 4 * TT) {
+      load_tile(ra, i0, TT, std::true_type{});
+      compute_tile(ra, TT, std::true_type{});
+    }
+    if (i0 < c1) {
+      load_tile(ra, i0, c1 - i0, std::false_type{});
+      compute_tile(ra, c1 - i0, std::false_type{});
     }
   }
 
@@ -397,7 +442,7 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
     float o = 0.0f, ll = 0.0f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float wgt = s_m[w][g] == -INFINITY ? 0.0f : exp2f(s_m[w][g] - M);
+      const float wgt = s_m[w][g] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(s_m[w][g] - M);
       const float rows = (s_acc[w][0][g][dch] + s_acc[w][1][g][dch]) + (s_acc[w][2][g][dch] + s_acc[w][3][g][dch]);
       o = fmaf(rows, wgt, o);
       ll = fmaf(s_l[w][g], wgt, ll);

@@ -79,6 +79,7 @@ struct Handle {
   ttkv_stats stats;
   // optional per-call timing of one device tier's partial kernel
   bool time_on;
+  int target_items;     // split-K granularity of the fused launch
   int time_max, time_n;
   hipEvent_t *time_ev;  // 2 * time_max events
 };

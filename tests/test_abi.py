@@ -74,7 +74,7 @@ def test_invalid_arguments_are_status_codes():
     c.head_dim = 128
     # unsupported format pair (V wider than K)
     c.tier[1].k_fmt, c.tier[1].v_fmt = B.I4_ASYM_G64, B.I8_SYM_G32
-    assert L.ttkv_count_parts(C.byref(c), None, None, 0, 0) == -1
+    assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1
     assert L.ttkv_quantize_append(h, C.byref(c), 1, -1, dummy, dummy, B.F16, 4, 0, None) == B.ERR_UNSUPPORTED
     c.tier[1].k_fmt = c.tier[1].v_fmt = B.I8_SYM_G32
     # block_tokens not a multiple of 64, batch out of range, GQA ratio
@@ -106,8 +106,8 @@ def test_invalid_arguments_are_status_codes():
     c._keep[5][:] = 0
     cnt = np.array([3, 0], np.int32)
     ids = np.zeros((2, 2), np.int32)
-    assert L.ttkv_count_parts(C.byref(c), ids.ctypes.data, cnt.ctypes.data, 2, 0) == -1   # count > stride
-    assert L.ttkv_count_parts(C.byref(c), ids.ctypes.data, None, 2, 0) == -1
+    assert L.ttkv_count_parts(h, C.byref(c), ids.ctypes.data, cnt.ctypes.data, 2, 0) == -1   # count > stride
+    assert L.ttkv_count_parts(h, C.byref(c), ids.ctypes.data, None, 2, 0) == -1
     # locate on an empty cache, merge argument checks
     t = C.c_int32()
     assert L.ttkv_locate(C.byref(c), 0, 0, C.byref(t), None, None, None) == B.ERR_INVALID_ARG
@@ -129,5 +129,7 @@ def test_locate_and_part_count_are_host_arithmetic():
     assert B.ttkv_locate(c, 0, 2048 + 300 + 69) == (0, 0, 69, 0)
     with pytest.raises(B.TTKVError):
         B.ttkv_locate(c, 0, 2048 + 300 + 70)
-    assert B.ttkv_count_parts(c) >= 3
+    h = B.ttkv_create()
+    assert B.ttkv_count_parts(h, c) >= 3
+    B.ttkv_destroy(h)
     assert B.ttkv_workspace_bytes(c, 8, 2) >= 1 * 8 * 8 * 130 * 4
