@@ -65,12 +65,12 @@ def timed_steps(cache, q, kn, vn, first, count, overlap=True, keep=None):
 
 # ------------------------------------------------------------------ workload: MHA 32K, int4 in HBM
 
-def build_mha32k(steps_total):
+def build_mha32k(steps_total, N=32768):
     import numpy as np
     import torch
     from paper_2604_19769_amd import synth
     from paper_2604_19769_amd.cache import TierConfig, TieredCache
-    B, H, N, R, bt = 4, 32, 32768, 2048, 128
+    B, H, R, bt = 4, 32, 2048, 128
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(SEED + 2)
