@@ -4,7 +4,6 @@
 #include "ttkv_internal.h"
 
 #include <algorithm>
-#include <atomic>
 #include <new>
 #include <vector>
 
@@ -390,7 +389,6 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   if (!h) return TTKV_ERR_INVALID_ARG;
   h->have_events = false;
   h->target_items = kDefaultItems;
-  h->counters = nullptr;
   h->time_on = false;
   h->time_max = h->time_n = 0;
   h->time_ev = nullptr;
@@ -674,13 +672,6 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
     a.tv[t] = make_view(T, make_layout(T, c->n_kv_heads));
     a.chunk[t] = P.chunk[t];
   }
-  if (!P.runs.empty() && !h->counters) {
-    static std::atomic<int> next_slot{0};
-    uint32_t *base = nullptr;
-    TTKV_HIP(h, work_counters(&base));
-    h->counters = base + (size_t)(next_slot.fetch_add(1) % kCounterSlots) * kCountersPerSlot;
-  }
-  int launch_idx = 0;
   const bool timed = h->time_on && h->time_n < h->time_max && !P.runs.empty();
   if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
   for (size_t r0 = 0; r0 < P.runs.size(); r0 += TTKV_MAX_ENTRIES) {
@@ -699,12 +690,8 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
       items += r.n_chunks;
     }
     a.n_items = items;
-    // persistent launch while this call still has a cleared counter to give it
-    a.counter = launch_idx < kCountersPerSlot ? h->counters + launch_idx : nullptr;
-    ++launch_idx;
     TTKV_HIP(h, launch_attn(a, compute, &nk));
   }
-  a.counter = nullptr;
   if (timed) {
     TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
     h->time_n += 1;
@@ -759,8 +746,6 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   for (int b = 0; b < c->batch; ++b) m.cnt[b] = P.parts[b];
   m.out = out;
   m.lse = lse;
-  m.clear = h->counters;
-  m.n_clear = h->counters ? std::min(launch_idx, (int)kCountersPerSlot) : 0;
   TTKV_HIP(h, launch_merge(m, compute));
   h->stats.kernels += nk + 1;
   return TTKV_OK;

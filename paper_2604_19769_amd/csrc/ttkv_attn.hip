@@ -32,10 +32,6 @@
 
 namespace ttkv {
 
-// Work counters of the persistent attention launches: static device memory, zero at
-// module load, cleared again by every merge kernel.
-__device__ uint32_t g_work_counters[kCounterSlots * kCountersPerSlot];
-
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -396,12 +392,15 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
   }
 }
 
-// One work item: (chunk `item` of some run, KV head hkv, query-head group hz).
 template <int G>
-__device__ __forceinline__ void do_item(const FusedArgs &a, int item, int hkv, int hz, float (*s_acc)[4][G][128],
-                                        float (*s_m)[G], float (*s_l)[G]) {
+__global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
+  __shared__ float s_acc[4][4][G][128];   // [wave][row of 16 lanes][head][channel]
+  __shared__ float s_m[4][G], s_l[4][G];
+
+  const int item = blockIdx.x;
+  const int hkv = blockIdx.y;
   const int Gtot = a.Hq / a.Hkv;
-  const int hq0 = hkv * Gtot + hz * G;
+  const int hq0 = hkv * Gtot + blockIdx.z * G;
 
   int lo = 0, hi = a.n_entries - 1;
   while (lo < hi) {
@@ -457,33 +456,6 @@ __device__ __forceinline__ void do_item(const FusedArgs &a, int item, int hkv, i
   }
 }
 
-// a.counter == nullptr: one work item per workgroup, taken from the grid position.
-// Otherwise the grid holds only as many workgroups as the GPU keeps resident and each
-// pulls flat item numbers (query-head group fastest, then KV head, then chunk) from
-// the counter until they run out: no slot waits for a new workgroup to be placed
-// and all of them finish within one item of each other.  The counter must be zero
-// at launch; the merge kernel that follows every attention launch clears it again.
-template <int G>
-__global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
-  __shared__ float s_acc[4][4][G][128];   // [wave][row of 16 lanes][head][channel]
-  __shared__ float s_m[4][G], s_l[4][G];
-  __shared__ uint32_t s_next;
-  if (!a.counter) {
-    do_item<G>(a, blockIdx.x, blockIdx.y, blockIdx.z, s_acc, s_m, s_l);
-    return;
-  }
-  const uint32_t n_hz = (a.Hq / a.Hkv) / G;
-  const uint32_t total = (uint32_t)a.n_items * a.Hkv * n_hz;
-  for (;;) {
-    if (threadIdx.x == 0) s_next = atomicAdd(a.counter, 1u);
-    __syncthreads();   // also: every thread is done reading s_acc of the previous item
-    const uint32_t flat = s_next;
-    if (flat >= total) break;
-    const uint32_t hz = flat % n_hz, rest = flat / n_hz;
-    do_item<G>(a, (int)(rest / a.Hkv), (int)(rest % a.Hkv), (int)hz, s_acc, s_m, s_l);
-  }
-}
-
 // One workgroup of 256 threads per row: two halves of the parts, thread = channel.
 __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
   __shared__ float s_o[128], s_l2, s_M[2];
@@ -527,7 +499,6 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
     a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
     if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? M + __logf(l) : -INFINITY;
   }
-  if (blockIdx.x == 0 && (int)threadIdx.x < a.n_clear) a.clear[threadIdx.x] = 0u;
   (void)s_M;
 }
 
@@ -541,38 +512,11 @@ bool attn_supported(int k_fmt, int v_fmt, int G) {
   return k_fmt == TTKV_I8_SYM_G32 && v_fmt == TTKV_I4_ASYM_G64;
 }
 
-hipError_t work_counters(uint32_t **base) {
-  return hipGetSymbolAddress((void **)base, HIP_SYMBOL(g_work_counters));
-}
-
-// Workgroups the device keeps resident for the kernel of group width G (cached per process).
-template <int G>
-int resident_workgroups() {
-  static int cached = 0;
-  if (cached) return cached;
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_fused_kernel<G>, 256, 0) != hipSuccess) return 0;
-  if (cus <= 0 || per_cu <= 0) return 0;
-  cached = cus * per_cu;
-  return cached;
-}
-
-hipError_t launch_attn(const FusedArgs &a_in, hipStream_t s, int *n_kernels) {
-  if (a_in.n_items <= 0) return hipSuccess;
-  FusedArgs a = a_in;
+hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels) {
+  if (a.n_items <= 0) return hipSuccess;
   const int Gtot = a.Hq / a.Hkv;
   const int G = group_width(Gtot);
   dim3 grid(a.n_items, a.Hkv, Gtot / G);
-  if (a.counter) {
-    const int res = G == 1 ? resident_workgroups<1>() : (G == 2 ? resident_workgroups<2>() : resident_workgroups<4>());
-    const int64_t total = (int64_t)a.n_items * a.Hkv * (Gtot / G);
-    if (res <= 0 || total <= res)
-      a.counter = nullptr;   // everything fits at once: the plain grid is the same thing
-    else
-      grid = dim3(res, 1, 1);
-  }
   ++*n_kernels;
   switch (G) {
     case 1: hipLaunchKernelGGL(attn_fused_kernel<1>, grid, dim3(256), 0, s, a); break;

@@ -80,7 +80,6 @@ struct Handle {
   // optional per-call timing of one device tier's partial kernel
   bool time_on;
   int target_items;     // split-K granularity of the fused launch
-  uint32_t *counters;   // this handle's kCountersPerSlot work counters (device), set on first use
   int time_max, time_n;
   hipEvent_t *time_ev;  // 2 * time_max events
 };
@@ -151,12 +150,8 @@ struct FusedArgs {
   int32_t part_stride;
   int32_t Hq, Hkv;
   float scale;
-  uint32_t *counter;    // device work counter (zero at launch) or nullptr = one item per workgroup
 };
 hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels);
-// Device address of this process's work counters (kCounterSlots x kCountersPerSlot, zero-initialised).
-constexpr int kCounterSlots = 64, kCountersPerSlot = 8;
-hipError_t work_counters(uint32_t **base);
 bool attn_supported(int k_fmt, int v_fmt, int G);
 
 struct MergeArgs {
@@ -166,8 +161,6 @@ struct MergeArgs {
   int32_t rows_per_seq;         // > 0: use cnt[row / rows_per_seq]
   int32_t cnt[TTKV_MAX_BATCH];
   float *out, *lse;
-  uint32_t *clear;              // work counters to reset for the next attention launch (nullable)
-  int32_t n_clear;
 };
 hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
 
