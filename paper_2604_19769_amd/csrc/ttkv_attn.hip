@@ -211,6 +211,10 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
 
   Splice sp;
   sp.init();
+  // per-lane byte offsets of its row slice inside a tile's sections (loop invariant)
+  const uint32_t kvoff = ktok * FK::ROWB + kslice * 16, vvoff = vtok * FV::ROWB + vslice * 16;
+  const uint32_t kmoff = ktok * 8 + (kslice >> 1) * (KF == TTKV_I8_SYM_G32 ? 2 : 4);
+  const uint32_t vmoff = vtok * 8 + (vslice >> 1) * (VF == TTKV_I8_SYM_G32 ? 2 : 4);
 
   // Registers of one tile of TT tokens in flight.
   struct TileRegs {
@@ -227,23 +231,32 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
     const int row0 = tok0 - rb * tv.bt;
     const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
     const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
+    // wave-uniform section bases of the tile + per-lane 32-bit offsets: the loads below can
+    // use the scalar-base + vector-offset + immediate addressing form
+    const uint8_t *kb = head + row0 * FK::ROWB, *kmb = head + tv.k_meta_off + row0 * 8;
+    const uint8_t *vb = head + tv.v_off + row0 * FV::ROWB, *vmb = head + tv.v_meta_off + row0 * 8;
+    constexpr uint32_t KMW = KF == TTKV_I8_SYM_G32 ? 2 : 4, VMW = VF == TTKV_I8_SYM_G32 ? 2 : 4;
 #pragma unroll
     for (int n = 0; n < NLK; ++n) {
-      const int r = FULL ? n * FK::TPL + ktok : min(n * FK::TPL + ktok, nv - 1);
-      t.kw[n] = *(const uint4 *)(head + (row0 + r) * FK::ROWB + kslice * 16);
+      const uint32_t r = FULL ? n * FK::TPL + ktok : min(n * FK::TPL + ktok, nv - 1);
+      const uint32_t co = FULL ? kvoff + n * FK::TPL * FK::ROWB : r * FK::ROWB + kslice * 16;
+      const uint32_t mo = FULL ? kmoff + n * FK::TPL * 8 : r * 8 + (kslice >> 1) * KMW;
+      t.kw[n] = *(const uint4 *)(kb + co);
       if constexpr (KF == TTKV_I8_SYM_G32)
-        t.kmeta[n] = *(const uint16_t *)(head + tv.k_meta_off + (row0 + r) * 8 + (kslice >> 1) * 2);
+        t.kmeta[n] = *(const uint16_t *)(kmb + mo);
       else if constexpr (KF == TTKV_I4_ASYM_G64)
-        t.kmeta[n] = *(const uint32_t *)(head + tv.k_meta_off + (row0 + r) * 8 + (kslice >> 1) * 4);
+        t.kmeta[n] = *(const uint32_t *)(kmb + mo);
     }
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
-      const int r = FULL ? n * FV::TPL + vtok : min(n * FV::TPL + vtok, nv - 1);
-      t.vw[n] = *(const uint4 *)(head + tv.v_off + (row0 + r) * FV::ROWB + vslice * 16);
+      const uint32_t r = FULL ? n * FV::TPL + vtok : min(n * FV::TPL + vtok, nv - 1);
+      const uint32_t co = FULL ? vvoff + n * FV::TPL * FV::ROWB : r * FV::ROWB + vslice * 16;
+      const uint32_t mo = FULL ? vmoff + n * FV::TPL * 8 : r * 8 + (vslice >> 1) * VMW;
+      t.vw[n] = *(const uint4 *)(vb + co);
       if constexpr (VF == TTKV_I8_SYM_G32)
-        t.vmeta[n] = *(const uint16_t *)(head + tv.v_meta_off + (row0 + r) * 8 + (vslice >> 1) * 2);
+        t.vmeta[n] = *(const uint16_t *)(vmb + mo);
       else if constexpr (VF == TTKV_I4_ASYM_G64)
-        t.vmeta[n] = *(const uint32_t *)(head + tv.v_meta_off + (row0 + r) * 8 + (vslice >> 1) * 4);
+        t.vmeta[n] = *(const uint32_t *)(vmb + mo);
     }
   };
 
