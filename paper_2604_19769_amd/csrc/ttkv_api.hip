@@ -147,7 +147,9 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const Layout L = make_layout(T, c->n_kv_heads);
     const bool sparse = sel_blocks && t == last;
     const bool host = T.mem == TTKV_MEM_HOST_PINNED;
-    P->chunk[t] = (host || sparse) ? std::min(L.bt, 256) : pick_chunk(c, t, staged, target_items);
+    // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured);
+    // staged slots and selected blocks of a device tier: 256-token items for parallelism
+    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : pick_chunk(c, t, staged, target_items);
     const int chunk = P->chunk[t];
     if (!sparse && !(host && staged)) {
       for (int b = 0; b < c->batch; ++b) {
