@@ -26,6 +26,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+# HBM bytes per mha32k attention launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, each scaled by
+# a plain copy kernel's reading (profiles/attn_fused_mha32k_hbm_traffic_pmc.txt); 1.004 x algorithmic
+MHA32K_MEASURED_TRAFFIC_BYTES = 697.2e6
 PCIE_PEAK_GBS = 64.0        # PCIe Gen5 x16 per direction, nominal
 SEED = 1976900
 
@@ -39,6 +42,8 @@ def parse():
     ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offload-steps", type=int, default=20)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -245,6 +250,13 @@ def main():
     B.lib()      # fails loudly if the HIP library has not been built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     W, K = args.warmup, args.steps
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB per launch
+        torch.cuda.synchronize()
+        del src, dst
 
     if args.workload == "offload128k":
         r = run_offload128k(K, W)
@@ -274,7 +286,7 @@ def main():
     k_bytes = (total_bytes + total_bytes_end) / 2      # the fused launch streams every tier once
     roofline = {"bound": "hbm", "kernel": "attn_fused_kernel<G=1>: fp16 tier + int4 tier in one launch",
                 "achieved": round(k_bytes / (kms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(k_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(k_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": MHA32K_MEASURED_TRAFFIC_BYTES,
                 "kernel_us": round(kms * 1e3, 2), "bytes_per_launch": int(k_bytes), "launches_timed": len(kernel_ms)}
     cpu = None
     if not args.no_cpu_baseline:
