@@ -190,9 +190,11 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
           if (!P->fetch.empty()) {
             Fetch &f = P->fetch.back();
             if (f.tier == t && f.b == b && f.nrec < gran && f.rec + f.nrec == rec && f.ntok == f.nrec * L.bt) {
+              // the merged copy is cut into chunks as one run of tokens: recount its parts
+              P->parts[b] -= (f.ntok + chunk - 1) / chunk;
               f.nrec += 1;
               f.ntok += ntok;
-              P->parts[b] += nparts;
+              P->parts[b] += (f.ntok + chunk - 1) / chunk;
               continue;
             }
           }
@@ -205,9 +207,10 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
           if (!P->runs.empty()) {
             Run &r = P->runs.back();
             if (r.tier == t && r.b == b && r.no_table && (int64_t)r.rec_base + r.len / L.bt == rec && r.len % L.bt == 0) {
+              P->parts[b] -= r.n_chunks;
               r.len += ntok;
-              r.n_chunks += nparts;
-              P->parts[b] += nparts;
+              r.n_chunks = (r.len + chunk - 1) / chunk;
+              P->parts[b] += r.n_chunks;
               continue;
             }
           }
