@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offload-steps", type=int, default=20)
+    ap.add_argument("--no-extra", action="store_true", help="skip the ragged-serving and sparse-recall objects")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -163,6 +164,126 @@ def build_offload128k(steps_total):
     vn = device_normal(gen, (steps_total, B, Hkv, 1, 128), torch.bfloat16)
     torch.cuda.synchronize()
     return cache, (K, V), (q, kn, vn), dict(B=B, Hq=Hq, Hkv=Hkv, N=N)
+
+
+# ------------------------------------------------------------------ workload: ragged paged serving batch
+
+def build_serving_ragged(steps_total, batch=16):
+    """BASELINE config 4: batch 16, 32 q / 8 kv heads, contexts uniform in [16K, 64K], 256-token pages with
+    shuffled page tables; 4K fp16 + 12K int8 in HBM, the rest int4 in pinned host memory."""
+    import numpy as np
+    import torch
+    from paper_2604_19769_amd import synth
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    Hq, Hkv, page = 32, 8, 256
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 4)
+    ctx = synth.rng(SEED + 4).integers(16384, 65537, batch)
+    tiers = [TierConfig("f16", "f16", 4096, page, 4096 // page + 1, paged_seed=SEED + 40),
+             TierConfig("i8", "i8", 12288, page, 12288 // page + 2, paged_seed=SEED + 41),
+             TierConfig("i4", "i4", 10**9, page, (65536 - 16384) // page + 4, mem="host", paged_seed=SEED + 42)]
+    cache = TieredCache(batch, Hq, Hkv, tiers)
+    kv = []
+    for b in range(batch):
+        n = int(ctx[b]) - 1
+        K = device_normal(gen, (Hkv, n, 128), torch.float16)
+        V = device_normal(gen, (Hkv, n, 128), torch.float16)
+        n2 = n - 4095 - 12288                      # oldest tokens -> host tier (>= 0 since ctx >= 16384)
+        if n2 > 0:
+            cache.append(2, K[:, :n2].contiguous(), V[:, :n2].contiguous(), seq=b, through_tiers=True)
+        cache.append(1, K[:, n2:n2 + 12288].contiguous(), V[:, n2:n2 + 12288].contiguous(), seq=b, through_tiers=True)
+        cache.append(0, K[:, n2 + 12288:].contiguous(), V[:, n2 + 12288:].contiguous(), seq=b)
+        kv.append((K, V))
+    q = device_normal(gen, (steps_total, batch, Hq, 128), torch.float16)
+    kn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.float16)
+    vn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.float16)
+    torch.cuda.synchronize()
+    return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, ctx=ctx)
+
+
+def run_serving_ragged(steps, warmup):
+    cache, kv, (q, kn, vn), shape = build_serving_ragged(steps + warmup)
+    del kv
+    try:
+        timed_steps(cache, q, kn, vn, 0, warmup)
+        total, by_tier = algorithmic_bytes(cache)
+        s0 = cache.stats()
+        t = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        h2d = (cache.stats()["h2d_bytes"] - s0["h2d_bytes"]) / steps
+        return {"workload": "batch 16, 32 q / 8 kv heads, contexts U[16K, 64K] (mean %d), 256-token pages, 4K fp16 + 12K int8 in HBM, "
+                            "rest int4 in pinned host memory" % int(shape["ctx"].mean()),
+                "ms_per_step": round(t * 1e3, 3), "tokens_per_s": round(shape["B"] / t, 1),
+                "host_tier_bytes_per_step": int(h2d), "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
+                "pcie_h2d_GBs": round(h2d / t / 1e9, 2), "pcie_frac_of_nominal_64": round(h2d / t / 1e9 / PCIE_PEAK_GBS, 4)}
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ workload: sparse recall of the host tier
+
+def build_sparse128k(steps_total, batch=4, planted=8):
+    """BASELINE config 5: batch 4, 128K tokens, tiers as the offload workload (1024-token host blocks) plus fp16
+    mean-key summaries; only the top-64 of 96 host blocks by q . summary are fetched.  `planted` seeded host blocks per
+    sequence have their keys shifted along the mean query of each KV head's group (of the first step's query)."""
+    import numpy as np
+    import torch
+    from paper_2604_19769_amd import synth
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    Hq, Hkv, N = 32, 8, 131072
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 5)
+    tiers = [TierConfig("bf16", "bf16", 4096, 128, 33),
+             TierConfig("i8", "i8", 28672, 1024, 28672 // 1024 + 2),
+             TierConfig("i4", "i4", 10**9, 1024, 98304 // 1024 + 3, mem="host", summary=True)]
+    cache = TieredCache(batch, Hq, Hkv, tiers)
+    q = device_normal(gen, (steps_total, batch, Hq, 128), torch.bfloat16)
+    g = synth.rng(SEED + 5)
+    kv, plant_ids = [], []
+    a, b2 = 98304, 98304 + 28672
+    for b in range(batch):
+        K = torch.randn((Hkv, N - 1, 128), generator=gen, device=dev, dtype=torch.float32)
+        V = device_normal(gen, (Hkv, N - 1, 128), torch.bfloat16)
+        ids = np.sort(g.choice(96, size=planted, replace=False))
+        u = q[0, b].float().view(Hkv, Hq // Hkv, 128).mean(1)
+        u = u / u.norm(dim=1, keepdim=True)
+        for j in ids:
+            K[:, j * 1024:(j + 1) * 1024] += u[:, None, :]
+        K = K.to(torch.bfloat16)
+        cache.append(2, K[:, :a].contiguous(), V[:, :a].contiguous(), seq=b, through_tiers=True)
+        cache.append(1, K[:, a:b2].contiguous(), V[:, a:b2].contiguous(), seq=b, through_tiers=True)
+        cache.append(0, K[:, b2:].contiguous(), V[:, b2:].contiguous(), seq=b)
+        kv.append((K, V))
+        plant_ids.append(ids)
+    kn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.bfloat16)
+    vn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.bfloat16)
+    torch.cuda.synchronize()
+    return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, N=N, planted=plant_ids)
+
+
+def run_sparse128k(steps, warmup, k=64):
+    cache, kv, (q, kn, vn), shape = build_sparse128k(steps + warmup)
+    del kv
+    try:
+        for s in range(warmup):
+            cache.step(q[s], kn[s], vn[s], select_k=k)
+        total, by_tier = algorithmic_bytes(cache)
+        s0 = cache.stats()
+        t0 = sync_time()
+        for s in range(warmup, warmup + steps):
+            cache.step(q[s], kn[s], vn[s], select_k=k)
+        t = (sync_time() - t0) / steps
+        st = cache.stats()
+        h2d = (st["h2d_bytes"] - s0["h2d_bytes"]) / steps
+        return {"workload": "batch 4, 32 q / 8 kv heads, 131072 tokens: 4K bf16 + 28K int8 in HBM, 96K int4 on the host in "
+                            "1024-token blocks with mean-key summaries; top-64 of 96 blocks fetched per sequence",
+                "ms_per_step": round(t * 1e3, 3), "blocks_fetched_per_step": (st["blocks_fetched"] - s0["blocks_fetched"]) / steps,
+                "host_tier_bytes_per_step": int(h2d), "dense_host_tier_bytes": 4 * 96 * 1179648,
+                "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
+                "pcie_h2d_GBs": round(h2d / t / 1e9, 2), "pcie_frac_of_nominal_64": round(h2d / t / 1e9 / PCIE_PEAK_GBS, 4)}
+    finally:
+        cache.close()
 
 
 def measure_h2d_peak():
@@ -305,6 +426,8 @@ def main():
                                "(group 64, asymmetric) in HBM, append + attend + evict per step",
                    "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
+        "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
+        "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),
     }
     print(json.dumps(line))
 

@@ -104,3 +104,71 @@ def test_offload128k_full_size_sampled_heads():
         assert torch.allclose(ref, got, rtol=1e-3, atol=2e-5)    # another split order: fp32 rounding only
     finally:
         cache.close()
+
+
+def test_serving_ragged_full_size_sampled():
+    """BASELINE config 4: batch 16, ragged contexts in [16K, 64K], paged 256-token blocks on every tier."""
+    steps = 2
+    cache, kv, (q, kn, vn), shape = bench.build_serving_ragged(steps)
+    try:
+        heads, G = [0, 5], 4
+        rows = q_rows(heads, G)
+        ctx = shape["ctx"]
+        picks = [int(np.argmin(ctx)), int(np.argmax(ctx))]           # shortest and longest sequence
+        tiers = [TierSpec("f16", "f16", 4096, 256), TierSpec("i8", "i8", 12288, 256), TierSpec("i4", "i4", 10**9, 256, mem="host")]
+        oras = {}
+        for b in picks:
+            oras[b] = sample_oracle(tiers, 32, 8, heads, kv[b][0], kv[b][1], [4096 + 512, 12288 + 1024, 65536])
+            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), ("i4", "i4")])
+        for s in range(steps):
+            out, lse = cache.step(q[s], kn[s], vn[s])
+            torch.cuda.synchronize()
+            for b in picks:
+                ro, rl = oras[b].step(q[s, b][rows][None].float().cpu().numpy(), kn[s, b, heads, 0][None].float().cpu().numpy(),
+                                      vn[s, b, heads, 0][None].float().cpu().numpy())
+                assert_close(out[b, rows].cpu().numpy(), ro[0], f"out seq {b} step {s}")
+                assert_close(lse[b, rows].cpu().numpy(), rl[0], f"lse seq {b} step {s}")
+        for b in picks:
+            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), ("i4", "i4")])
+            total = sum(int(cache.len[t][b]) for t in range(3))
+            assert total == int(ctx[b]) - 1 + steps
+            for pos in (0, total // 3, total - 1):
+                t, blk, row, _ = cache.locate(b, pos)
+                assert (t, blk, row) == tuple(int(x) for x in oras[b].locate(0, pos))
+        assert torch.isfinite(out).all()
+    finally:
+        cache.close()
+
+
+def test_sparse_recall_full_size_one_sequence():
+    """BASELINE config 5: top-64 of 96 host blocks by q . mean-key; the oracle recomputes one whole sequence
+    (selection needs every head): selected block ids identical, planted blocks selected, outputs within tolerance."""
+    steps = 2
+    cache, kv, (q, kn, vn), shape = bench.build_sparse128k(steps)
+    try:
+        b = 1
+        tiers = [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 1024),
+                 TierSpec("i4", "i4", 10**9, 1024, mem="host", summary=True)]
+        ora = OracleCache(1, 32, 8, 128, tiers, [4096 + 256, 28672 + 2048, 98304 + 4096])
+        ora.load(0, kv[b][0].float().cpu().numpy(), kv[b][1].float().cpu().numpy())
+        for blk, mu in ora.summaries(0).items():
+            assert np.array_equal(cache.dump_summary(2, b, blk), mu), blk
+        for s in range(steps):
+            before = cache.stats()
+            out, lse = cache.step(q[s], kn[s], vn[s], select_k=64)
+            torch.cuda.synchronize()
+            after = cache.stats()
+            assert after["blocks_fetched"] - before["blocks_fetched"] == 4 * 64
+            assert after["h2d_bytes"] - before["h2d_bytes"] == 4 * 64 * 1179648
+            ro, rl, rsel = ora.step(q[s, b][None].float().cpu().numpy(), kn[s, b, :, 0][None].float().cpu().numpy(),
+                                    vn[s, b, :, 0][None].float().cpu().numpy(), select_k=64)
+            got = cache.sel_blocks.numpy()[b, :int(cache.sel_count.numpy()[b])]
+            assert np.array_equal(got, rsel[0]), (got, rsel[0])
+            if s == 0:     # the planted blocks were built from this step's query
+                for bb in range(4):
+                    sel = set(cache.sel_blocks.numpy()[bb, :64].tolist())
+                    assert set(shape["planted"][bb].tolist()) <= sel, bb
+            assert_close(out[b].cpu().numpy(), ro[0], f"out step {s}")
+            assert_close(lse[b].cpu().numpy(), rl[0], f"lse step {s}")
+    finally:
+        cache.close()
