@@ -117,7 +117,8 @@ struct Plan {
 // about the same number of bytes: total bytes of the in-place tiers / target_items.
 int pick_chunk(const ttkv_cache *c, int t, bool staged, int target_items) {
   const int G = c->n_q_heads / c->n_kv_heads;
-  const int n_hg = G % 4 == 0 ? G / 4 : (G % 2 == 0 ? G / 2 : G);
+  const int n_hg = 1;   // the query-head groups of one KV head share its bytes (second reader hits L2)
+  (void)G;
   int64_t total = 0;
   for (int u = 0; u < c->n_tiers; ++u) {
     const ttkv_tier &U = c->tier[u];

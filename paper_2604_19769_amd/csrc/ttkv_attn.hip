@@ -410,10 +410,18 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
   __shared__ float s_acc[4][4][G][128];   // [wave][row of 16 lanes][head][channel]
   __shared__ float s_m[4][G], s_l[4][G];
 
-  const int item = blockIdx.x;
-  const int hkv = blockIdx.y;
+  // Linear workgroup id -> (item, KV head, query-head group).  Workgroups are dealt round-robin
+  // to the 8 XCDs (id % 8), each with its own L2: the groups of one (item, KV head), which read
+  // the same K/V bytes, get ids 8 apart so that they land on the same XCD at the same time and
+  // the second reader is served from that L2.
   const int Gtot = a.Hq / a.Hkv;
-  const int hq0 = hkv * Gtot + blockIdx.z * G;
+  const uint32_t n_hz = Gtot / G;
+  const uint32_t id = blockIdx.x;
+  const uint32_t base = ((id >> 3) / n_hz) * 8 + (id & 7);
+  if (base >= (uint32_t)a.n_items * a.Hkv) return;
+  const int item = base / a.Hkv;
+  const int hkv = base % a.Hkv;
+  const int hq0 = hkv * Gtot + ((id >> 3) % n_hz) * G;
 
   int lo = 0, hi = a.n_entries - 1;
   while (lo < hi) {
@@ -515,9 +523,10 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
   (void)s_M;
 }
 
-int group_width(int Gtot) { return Gtot % 4 == 0 ? 4 : (Gtot % 2 == 0 ? 2 : 1); }
-
 }  // namespace
+
+// Query heads of one KV head handled together by one workgroup (register budget: 2).
+int attn_group_width(int Gtot) { return Gtot % 2 == 0 ? 2 : 1; }
 
 bool attn_supported(int k_fmt, int v_fmt, int G) {
   (void)G;
@@ -528,13 +537,13 @@ bool attn_supported(int k_fmt, int v_fmt, int G) {
 hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels) {
   if (a.n_items <= 0) return hipSuccess;
   const int Gtot = a.Hq / a.Hkv;
-  const int G = group_width(Gtot);
-  dim3 grid(a.n_items, a.Hkv, Gtot / G);
+  const int G = attn_group_width(Gtot);
+  const uint32_t bases = ((uint32_t)a.n_items * a.Hkv + 7) / 8 * 8;
+  dim3 grid(bases * (Gtot / G));
   ++*n_kernels;
   switch (G) {
     case 1: hipLaunchKernelGGL(attn_fused_kernel<1>, grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL(attn_fused_kernel<2>, grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL(attn_fused_kernel<4>, grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL(attn_fused_kernel<2>, grid, dim3(256), 0, s, a); break;
   }
   return hipGetLastError();
 }

@@ -153,6 +153,7 @@ struct FusedArgs {
 };
 hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels);
 bool attn_supported(int k_fmt, int v_fmt, int G);
+int attn_group_width(int Gtot);
 
 struct MergeArgs {
   const float *m, *l, *acc;
