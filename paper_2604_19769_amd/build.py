@@ -14,6 +14,7 @@ SOURCES = {
     "ttkv_api.hip": [],
     "ttkv_quant.hip": ["-ffp-contract=off"],
     "ttkv_attn.hip": [],
+    "ttkv_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],   # MFMA results feed vector code: keep them out of the AGPRs
     "ttkv_select.hip": ["-ffp-contract=off"],
 }
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

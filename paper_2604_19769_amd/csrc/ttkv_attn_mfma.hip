@@ -1,0 +1,407 @@
+// Grouped-query variant of the split-K decode attention partials (Alg. 1: Attn on the
+// fast tier, Decompress + Attn per slow-tier block): all query heads that share a KV
+// head are served by ONE pass over that head's K/V bytes, with the two contractions on
+// the matrix cores (v_mfma_f32_16x16x16 f16 / bf16).  Same work items, same partials
+// and same record layout as the vector kernel; only the lane mapping differs.
+//
+// One 16-token tile, lane = (c = lane % 16, kg = lane / 16):
+//   K rows are loaded in the MFMA A layout: lane (c, kg) holds channels [32 kg, 32 kg + 32)
+//   of token c (16 B int4, 32 B int8, 64 B fp16/bf16), spliced into packed 16-bit pairs as
+//   in the vector kernel.  Eight steps of 16 channels each give
+//       S[token][column] = sum_d K[token][d] * Q[d][column]
+//   where a column is (quantization group, query head): the q operand is zero outside the
+//   column's group, so every column is a per-group dot product that can be scaled by the
+//   group's fp16 scale / zero afterwards.  The splice offsets leave through the initial
+//   accumulator value.  In the MFMA result layout lane (c, kg) holds column c of tokens
+//   4 kg .. 4 kg + 3; the groups of one head are summed by DPP row rotations, which also
+//   leaves every column of the row with a valid copy of its head's scores.
+//   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg).
+//   V rows are loaded like K rows, then brought from [token][channel] to
+//   [channel][token] by a product with the identity matrix: the fp32 result has lane
+//   (c, kg) holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
+//       O[channel][column] += sum_token V^T[channel][token] * P[token][column].
+//   The dequantization of V (scale per token and group, splice offset, and for int4 a
+//   re-centring by 8 so that rounding to fp16 has no preferred sign) is applied to the
+//   transposed fp32 values before they are packed to fp16; the zero points are summed
+//   separately in fp32 (sum_t p_t (z_t + 8 s_t)).  P is rounded to fp16 once and that
+//   rounded value is used for the row sum as well, so the normalisation is consistent.
+//
+// Column budget of the 16-wide tile: groups x heads <= 16, and the V group of an output
+// row must find a column copy of its head: int4 (2 groups) serves 2, 4 or 8 heads per KV
+// head, int8 (4 groups) 2 or 4, fp16 / bf16 any count up to 16.
+#include "ttkv_attn_dev.h"
+
+#include <type_traits>
+
+namespace ttkv {
+
+namespace {
+
+using namespace dev;
+
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef short s4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+template <bool BF>
+__device__ __forceinline__ f4 mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, f4 c) {
+  const uint2 A = {a0, a1}, B = {b0, b1};
+  if constexpr (BF)
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4, A), __builtin_bit_cast(s4, B), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h4, A), __builtin_bit_cast(h4, B), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pk(float x, float y) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x, y));
+}
+
+template <int F>
+constexpr int n_groups() {
+  return F == TTKV_I4_ASYM_G64 ? 2 : (F == TTKV_I8_SYM_G32 ? 4 : 1);
+}
+// Channel, relative to the lane's 32-channel slice, of k-value i of step s: step s takes
+// the packed registers 2s and 2s+1 that unpack16 produced (int4 pairs are (0,4) (1,5) | (2,6) (3,7)).
+template <int F>
+constexpr int chan(int s, int i) {
+  if (F == TTKV_I4_ASYM_G64)
+    return 8 * (s / 2) + ((s % 2) ? (i < 2 ? 2 + 4 * i : 3 + 4 * (i - 2)) : (i < 2 ? 4 * i : 1 + 4 * (i - 2)));
+  return 4 * s + i;
+}
+// Splice offset carried by k-value i of a step.
+template <int F>
+constexpr float k_offset(int i) {
+  return F == TTKV_I4_ASYM_G64 ? (i < 2 ? 1024.0f : 64.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
+}
+
+// GT: query heads per KV head as a compile-time constant (quantized K: the group sum below
+// depends on it), or 0 to take it from the arguments (fp16 / bf16, any count up to 16).
+template <int KF, int VF, int GT>
+__device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
+                                             int chunk, int seq, int hkv, float (*s_acc)[16][128],
+                                             float (*s_m)[16], float (*s_l)[16]) {
+  const int G = GT ? GT : a.Hq / a.Hkv;
+  using FK = Fmt<KF>;
+  using FV = Fmt<VF>;
+  constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
+  constexpr int NT = 4 / NLK;                                // tiles in flight per wave
+  constexpr int TT = 16 * NT;
+  constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
+  constexpr bool KQ = NGK > 1, VQ = NGV > 1;
+  constexpr bool KBF = KF == TTKV_BF16, VBF = VF == TTKV_BF16;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, kg = lane >> 4;
+  const int c0 = chunk * chunk_tokens;
+  const int c1 = min(en.len, c0 + chunk_tokens);
+  const int ring_tokens = tv.ring_blocks * tv.bt;
+  const float cs = a.scale * kLog2e;       // scores are kept in the log2 domain
+
+  const int g = n % G;                                   // head of this column
+  const int gam = KQ ? min(n / G, NGK - 1) : 0;          // K group of this column
+  const bool active = n < NGK * G && gam == kg * NGK / 4;  // does the lane's channel slice lie in the column's group
+
+  // ---- q operand: 16 packed registers (step s: 2s, 2s+1), offset sum and plain sum of the column
+  uint32_t qB[16];
+  float off = 0.0f, qs = 0.0f;
+  {
+    const uint4 *qsrc = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * G + g) * 128 + kg * 32);
+    uint32_t qw[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 w = qsrc[i];
+      qw[4 * i] = w.x; qw[4 * i + 1] = w.y; qw[4 * i + 2] = w.z; qw[4 * i + 3] = w.w;
+    }
+    if constexpr (!KBF) {
+      if (a.q_fmt == TTKV_BF16) {   // bf16 -> fp16 (exact inside the fp16 normal range, clamped outside)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float lo = fminf(fmaxf(__uint_as_float(qw[i] << 16), -65504.0f), 65504.0f);
+          const float hi = fminf(fmaxf(__uint_as_float(qw[i] & 0xffff0000u), -65504.0f), 65504.0f);
+          qw[i] = (uint32_t)__half_as_ushort(__float2half_rn(lo)) | ((uint32_t)__half_as_ushort(__float2half_rn(hi)) << 16);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) qB[r] = 0;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = chan<KF>(s, i);
+        const uint32_t bits = (qw[j / 2] >> (16 * (j % 2))) & 0xffffu;
+        qB[2 * s + i / 2] |= bits << (16 * (i % 2));
+        const float v = KBF ? __uint_as_float(bits << 16) : h2f((uint16_t)bits);
+        qs += v;
+        off = fmaf(v, k_offset<KF>(i), off);
+      }
+    }
+    if (!active) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) qB[r] = 0;
+      off = qs = 0.0f;
+    }
+    // the column's group spans one, two or four channel slices; the others contribute zero
+    off += __shfl_xor(off, 16); off += __shfl_xor(off, 32);
+    qs += __shfl_xor(qs, 16);   qs += __shfl_xor(qs, 32);
+  }
+
+  // identity operand of the transposing product: k-value i of this lane is row 4 kg + i
+  const uint32_t one = VBF ? 0x3F80u : 0x3C00u;
+  const uint32_t id0 = (n == 4 * kg ? one : 0u) | (n == 4 * kg + 1 ? one << 16 : 0u);
+  const uint32_t id1 = (n == 4 * kg + 2 ? one : 0u) | (n == 4 * kg + 3 ? one << 16 : 0u);
+  // Selection operands that bring a token's four fp16 meta values (scale, zero per group) into the
+  // score layout: with the meta words as A operand, k-values 0..3 of the kg = 0 lanes, the product
+  // with a 0/1 column selector is exactly the scale (or zero) of the column's group, per token.
+  uint32_t bs0 = 0, bs1 = 0, bz0 = 0, bz1 = 0;
+  if (KQ && kg == 0) {
+    const int ss = KF == TTKV_I4_ASYM_G64 ? 2 * gam : gam;
+    bs0 = ss == 0 ? 0x3C00u : (ss == 1 ? 0x3C000000u : 0u);
+    bs1 = ss == 2 ? 0x3C00u : (ss == 3 ? 0x3C000000u : 0u);
+    if (KF == TTKV_I4_ASYM_G64) {
+      bz0 = gam == 0 ? 0x3C000000u : 0u;
+      bz1 = gam == 1 ? 0x3C000000u : 0u;
+    }
+  }
+  // byte selector that duplicates the fp16 scale of this lane's channel slice out of the V meta words
+  const uint32_t vh = VF == TTKV_I4_ASYM_G64 ? (kg >> 1) * 2 : kg;
+  const uint32_t vsel = (2 * vh) | ((2 * vh + 1) << 8) | ((2 * vh) << 16) | ((2 * vh + 1) << 24);
+  // minus the splice offsets, as packed fp16 pairs: -1024, -64, -1152
+  uint32_t no_a = 0xE400E400u, no_b = 0xD400D400u, no_c = 0xE480E480u;
+  asm volatile("" : "+s"(no_a), "+s"(no_b), "+s"(no_c));
+
+  const f4 zero4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  f4 acc[8], accz = zero4;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) acc[s] = zero4;
+  float m = -INFINITY, l = 0.0f;
+
+  Splice sp;
+  sp.init();
+
+  struct TileRegs {
+    uint4 kw[NT][NLK], vw[NT][NLV];
+    uint2 kmeta[NT], vmeta[NT];
+  };
+  const uint32_t kdoff = n * FK::ROWB + kg * (FK::ROWB / 4), vdoff = n * FV::ROWB + kg * (FV::ROWB / 4);
+
+  auto load_tiles = [&](TileRegs &t, int i0, int nv, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    int tok0 = en.first_tok + i0;
+    if (tok0 >= ring_tokens) tok0 -= ring_tokens;
+    const int rb = tok0 / tv.bt;
+    const int row0 = tok0 - rb * tv.bt;
+    const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
+    const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
+    const uint8_t *kb = head + row0 * FK::ROWB, *kmb = head + tv.k_meta_off + row0 * 8;
+    const uint8_t *vb = head + tv.v_off + row0 * FV::ROWB, *vmb = head + tv.v_meta_off + row0 * 8;
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      const uint32_t row = FULL ? tt * 16 + n : min(tt * 16 + n, nv - 1);   // rows past the end re-read the last live row
+      const uint32_t ko = FULL ? kdoff + tt * 16 * FK::ROWB : row * FK::ROWB + kg * (FK::ROWB / 4);
+      const uint32_t vo = FULL ? vdoff + tt * 16 * FV::ROWB : row * FV::ROWB + kg * (FV::ROWB / 4);
+#pragma unroll
+      for (int x = 0; x < NLK; ++x) t.kw[tt][x] = *(const uint4 *)(kb + ko + 16 * x);
+#pragma unroll
+      for (int x = 0; x < NLV; ++x) t.vw[tt][x] = *(const uint4 *)(vb + vo + 16 * x);
+      if constexpr (KQ) t.kmeta[tt] = *(const uint2 *)(kmb + row * 8);
+      if constexpr (VQ) t.vmeta[tt] = *(const uint2 *)(vmb + row * 8);
+    }
+  };
+
+  auto compute_tiles = [&](const TileRegs &t, int nv, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    // ---- scores (log2 domain), column n of tokens 4 kg + i
+    f4 S[NT];
+    float mt = -INFINITY;
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      uint32_t kr[16];
+#pragma unroll
+      for (int x = 0; x < NLK; ++x) unpack16<KF>(t.kw[tt][x], kr + x * (16 / NLK), sp);
+      f4 sv = f4{-off, -off, -off, -off};
+#pragma unroll
+      for (int s = 0; s < 8; ++s) sv = mma<KBF>(kr[2 * s], kr[2 * s + 1], qB[2 * s], qB[2 * s + 1], sv);
+      f4 ksv = zero4, kzv = zero4;
+      if constexpr (KQ) ksv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bs0, bs1, zero4);
+      if constexpr (KF == TTKV_I4_ASYM_G64) kzv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bz0, bz1, zero4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float x = sv[i];
+        if constexpr (KF == TTKV_I8_SYM_G32) x *= ksv[i];
+        if constexpr (KF == TTKV_I4_ASYM_G64) x = fmaf(kzv[i], qs, x * ksv[i]);
+        if constexpr (KQ) {   // sum the groups of a head: cyclic over the columns with the same n % G
+          if constexpr (GT <= 8) x += dpp<0x128>(x);
+          if constexpr (GT <= 4) x += dpp<0x124>(x);
+          if constexpr (GT <= 2) x += dpp<0x122>(x);
+        }
+        x *= cs;
+        if (!FULL && tt * 16 + 4 * kg + i >= nv) x = -INFINITY;
+        sv[i] = x;
+        mt = fmaxf(mt, x);
+      }
+      S[tt] = sv;
+    }
+
+    // ---- online softmax (base 2), per column
+    mt = fmaxf(mt, __shfl_xor(mt, 16));
+    mt = fmaxf(mt, __shfl_xor(mt, 32));
+    if (__any(mt > m)) {
+      const float mn = fmaxf(m, mt);
+      const float alpha = __builtin_amdgcn_exp2f(m - mn);
+      l *= alpha;
+      accz *= alpha;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) acc[s] *= alpha;
+      m = mn;
+    }
+
+    // ---- weighted V
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+      float p[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(S[tt][i] - m);
+      const uint32_t pB0 = pk(p[0], p[1]), pB1 = pk(p[2], p[3]);
+      l += ((float)as_h2(pB0).x + (float)as_h2(pB0).y) + ((float)as_h2(pB1).x + (float)as_h2(pB1).y);
+
+      uint32_t vr[16];
+#pragma unroll
+      for (int x = 0; x < NLV; ++x) unpack16<VF>(t.vw[tt][x], vr + x * (16 / NLV), sp);
+      if constexpr (VQ) {
+        // codes -> code * scale in fp16, one rounding (to nearest even): exact offset removal, then the product
+        const h2 vs2 = as_h2(__builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t no = VF == TTKV_I8_SYM_G32 ? no_c : ((r & 1) ? no_b : no_a);
+          vr[r] = __builtin_bit_cast(uint32_t, (as_h2(vr[r]) + as_h2(no)) * vs2);
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const f4 dt = mma<VBF>(vr[2 * s], vr[2 * s + 1], id0, id1, zero4);
+        acc[s] = mma<false>(pk(dt[0], dt[1]), pk(dt[2], dt[3]), pB0, pB1, acc[s]);
+      }
+      if constexpr (VF == TTKV_I4_ASYM_G64) {
+        // zero points: the meta words transposed like a 4-channel V; every row group of four then
+        // holds sum_t p_t * (s0, z0, s1, z1)
+        const f4 dt = mma<false>(t.vmeta[tt].x, t.vmeta[tt].y, id0, id1, zero4);
+        accz = mma<false>(pk(dt[0], dt[1]), pk(dt[2], dt[3]), pB0, pB1, accz);
+      }
+    }
+  };
+
+  {
+    TileRegs ra;
+    int i0 = c0 + wave * TT;
+    for (; i0 + TT <= c1; i0 += 4 * TT) {
+      load_tiles(ra, i0, TT, std::true_type{});
+      compute_tiles(ra, TT, std::true_type{});
+    }
+    if (i0 < c1) {
+      load_tiles(ra, i0, c1 - i0, std::false_type{});
+      compute_tiles(ra, c1 - i0, std::false_type{});
+    }
+  }
+
+  // ---- the wave's result: column n < G of lane (n, kg) holds channels 32 kg + chan(s, i)
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  float z = 0.0f;
+  if constexpr (VF == TTKV_I4_ASYM_G64) z = (kg >> 1) ? accz[3] : accz[1];   // sum_t p_t * zero of this slice's group
+  if (n < G) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s_acc[wave][n][32 * kg + chan<VF>(s, i)] = acc[s][i] + z;
+    if (kg == 0) {
+      s_m[wave][n] = m;
+      s_l[wave][n] = l;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const FusedArgs a) {
+  __shared__ float s_acc[4][16][128];   // [wave][head][channel]
+  __shared__ float s_m[4][16], s_l[4][16];
+
+  const int G = a.Hq / a.Hkv;
+  const int item = blockIdx.x / a.Hkv;
+  const int hkv = blockIdx.x % a.Hkv;
+
+  int lo = 0, hi = a.n_entries - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (a.e[mid].item_start <= item) lo = mid; else hi = mid - 1;
+  }
+  const Entry en = a.e[lo];
+  const int tier = (en.tier_seq >> 16) & 0xff, seq = en.tier_seq & 0xffff;
+  TierView tv = a.tv[tier];
+  if (en.tier_seq >> 24) tv.table = nullptr;   // the run names pool records directly
+  const int chunk_tokens = a.chunk[tier];
+  const int chunk = item - en.item_start;
+
+  const int combo = tv.k_fmt * 8 + tv.v_fmt;
+#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hkv, s_acc, s_m, s_l)
+  switch (combo) {
+    case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
+    case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32: TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, 4); break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64: TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, 4); break;
+    default:
+      if (G == 4)
+        TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, 4);
+      else
+        TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, 8);
+      break;
+  }
+#undef TTKV_MFMA_CASE
+  __syncthreads();
+
+  // ---- merge the four waves (each with its own running max) and write the item's partials
+  const int part = en.part_base + chunk;
+  for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
+    const int g = idx >> 7, dch = idx & 127;
+    const float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
+    float o = 0.0f, ll = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = s_m[w][g] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(s_m[w][g] - M);
+      o = fmaf(s_acc[w][g][dch], wgt, o);
+      ll = fmaf(s_l[w][g], wgt, ll);
+    }
+    const int64_t prow = ((int64_t)seq * a.Hq + hkv * G + g) * a.part_stride + part;
+    a.pacc[prow * 128 + dch] = o;
+    if (dch == 0) {
+      a.pm[prow] = M * kLn2;  // natural-log units outside the kernel
+      a.pl[prow] = ll;
+    }
+  }
+}
+
+// Can one 16-column tile hold every (group, head) column of this tier's formats?
+bool tier_fits(int k_fmt, int v_fmt, int G) {
+  if (G < 1 || G > 16) return false;
+  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8);
+  if (k_fmt == TTKV_I8_SYM_G32) return G == 4;
+  return true;
+}
+
+}  // namespace
+
+bool attn_mfma_eligible(const FusedArgs &a) {
+  const int G = a.Hq / a.Hkv;
+  for (int j = 0; j < a.n_entries; ++j) {
+    const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
+    if (!tier_fits(tv.k_fmt, tv.v_fmt, G)) return false;
+  }
+  return true;
+}
+
+hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s) {
+  hipLaunchKernelGGL(attn_mfma_kernel, dim3((uint32_t)a.n_items * a.Hkv), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ttkv
