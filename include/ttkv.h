@@ -134,8 +134,10 @@ size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
 int32_t ttkv_count_parts(ttkv_handle h, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
                          int32_t sel_stride, int32_t n_slots);
 /* Split-K granularity: ttkv_decode_attn cuts the device-resident tiers into about
- * target_items work items of equal bytes (before multiplying by KV heads);
- * 0 restores the default.  More items: better balance over 256 CUs, more partials. */
+ * target_items workgroups of equal bytes, counted over all sequences and KV heads;
+ * 0 restores the default (a whole number of rounds of resident workgroups, chosen by
+ * the kernel the cache's formats and head counts select).  More items: better balance
+ * over 256 CUs, more partials. */
 ttkv_status ttkv_set_split(ttkv_handle h, int32_t target_items);
 
 /* Append n_tokens at the tail of `tier` (Sec. 4.1 "newly generated tokens are

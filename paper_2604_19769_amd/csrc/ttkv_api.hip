@@ -101,7 +101,14 @@ struct Fetch {
   int part_base;
   int chunk;
 };
-constexpr int kDefaultItems = 2560;   // ~10 work items per CU per (KV head) launch
+// Default split-K granularity: a whole number of rounds of resident workgroups (256 CUs x 4 per CU
+// for the vector kernel, x 3 for the grouped-query matrix-core kernel), measured best at 2.5 / 2 rounds.
+int default_items(const ttkv_cache *c) {
+  const int G = c->n_q_heads / c->n_kv_heads;
+  for (int t = 0; t < c->n_tiers; ++t)
+    if (!attn_mfma_fits(c->tier[t].k_fmt, c->tier[t].v_fmt, G)) return 2560;
+  return 1536;
+}
 
 struct Plan {
   std::vector<Run> runs;
@@ -394,7 +401,7 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   Handle *h = new (std::nothrow) Handle();
   if (!h) return TTKV_ERR_INVALID_ARG;
   h->have_events = false;
-  h->target_items = kDefaultItems;
+  h->target_items = 0;
   h->time_on = false;
   h->time_max = h->time_n = 0;
   h->time_ev = nullptr;
@@ -502,7 +509,7 @@ int32_t ttkv_count_parts(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items ? h->target_items : default_items(c), &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
 }
 
@@ -640,7 +647,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   const bool staged = n_slots > 0;
 
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items, &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items ? h->target_items : default_items(c), &P);
   if (P.status != TTKV_OK) return P.status;
   if (!workspace) return TTKV_ERR_WORKSPACE;
   // workspace = [n_slots staging slots][m][l][acc]
@@ -827,7 +834,7 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
 ttkv_status ttkv_set_split(ttkv_handle hh, int32_t target_items) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || target_items < 0 || target_items > (1 << 20)) return TTKV_ERR_INVALID_ARG;
-  h->target_items = target_items ? target_items : kDefaultItems;
+  h->target_items = target_items;
   return TTKV_OK;
 }
 

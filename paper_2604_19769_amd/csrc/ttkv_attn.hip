@@ -438,8 +438,7 @@ hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels) {
   if (a.n_items <= 0) return hipSuccess;
   const int Gtot = a.Hq / a.Hkv;
   ++*n_kernels;
-  static const int mfma_min = getenv("TTKV_MFMA_MIN_G") ? atoi(getenv("TTKV_MFMA_MIN_G")) : 4;
-  if (Gtot >= mfma_min && attn_mfma_eligible(a)) return launch_attn_mfma(a, s);
+  if (attn_mfma_eligible(a)) return launch_attn_mfma(a, s);
   const int G = attn_group_width(Gtot);
   const uint32_t bases = ((uint32_t)a.n_items * a.Hkv + 7) / 8 * 8;
   dim3 grid(bases * (Gtot / G));

@@ -10,25 +10,27 @@
 //   in the vector kernel.  Eight steps of 16 channels each give
 //       S[token][column] = sum_d K[token][d] * Q[d][column]
 //   where a column is (quantization group, query head): the q operand is zero outside the
-//   column's group, so every column is a per-group dot product that can be scaled by the
-//   group's fp16 scale / zero afterwards.  The splice offsets leave through the initial
-//   accumulator value.  In the MFMA result layout lane (c, kg) holds column c of tokens
-//   4 kg .. 4 kg + 3; the groups of one head are summed by DPP row rotations, which also
-//   leaves every column of the row with a valid copy of its head's scores.
+//   column's group, so every column is a per-group dot product.  The splice offsets leave
+//   through the initial accumulator value.  In the MFMA result layout lane (c, kg) holds
+//   column c of tokens 4 kg .. 4 kg + 3.  The token's four fp16 meta values (scale / zero per
+//   group) reach that layout by one more product: meta words as A operand against a 0/1
+//   selector of the column's group, which is exact.  The groups of one head are then summed
+//   by DPP row rotations, which also leaves every column with its head's score.
 //   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg).
-//   V rows are loaded like K rows, then brought from [token][channel] to
-//   [channel][token] by a product with the identity matrix: the fp32 result has lane
-//   (c, kg) holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
+//   V rows are loaded like K rows and dequantized in packed fp16 while the lane still owns
+//   one token and one group: the splice offset is removed exactly, then code x scale is
+//   rounded once (to nearest even).  A product with the identity matrix brings the tile
+//   from [token][channel] to [channel][token]: the fp32 result (exact) has lane (c, kg)
+//   holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
 //       O[channel][column] += sum_token V^T[channel][token] * P[token][column].
-//   The dequantization of V (scale per token and group, splice offset, and for int4 a
-//   re-centring by 8 so that rounding to fp16 has no preferred sign) is applied to the
-//   transposed fp32 values before they are packed to fp16; the zero points are summed
-//   separately in fp32 (sum_t p_t (z_t + 8 s_t)).  P is rounded to fp16 once and that
+//   The int4 zero points ride along as a 4-channel V (the meta words transposed the same
+//   way), giving sum_t p_t z_t per group in fp32.  P is rounded to fp16 once and that
 //   rounded value is used for the row sum as well, so the normalisation is consistent.
 //
-// Column budget of the 16-wide tile: groups x heads <= 16, and the V group of an output
-// row must find a column copy of its head: int4 (2 groups) serves 2, 4 or 8 heads per KV
-// head, int8 (4 groups) 2 or 4, fp16 / bf16 any count up to 16.
+// Column budget of the 16-wide tile: groups x heads <= 16 with the head count a power of
+// two where groups are summed by rotations: int4 (2 groups) serves 4 or 8 heads per KV
+// head, int8 (4 groups) 4, fp16 / bf16 any count from 4 to 16; the rest, and fewer than 4
+// heads (where the vector kernel is faster), stay on the vector kernel.
 #include "ttkv_attn_dev.h"
 
 #include <type_traits>
@@ -84,7 +86,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
-  constexpr int NT = 4 / NLK;                                // tiles in flight per wave
+  constexpr int NT = NLK == 4 ? 2 : 4 / NLK;                 // tiles in flight per wave
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
@@ -380,21 +382,22 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const FusedArgs a) {
   }
 }
 
-// Can one 16-column tile hold every (group, head) column of this tier's formats?
-bool tier_fits(int k_fmt, int v_fmt, int G) {
-  if (G < 1 || G > 16) return false;
+}  // namespace
+
+// Can one 16-column tile hold every (group, head) column of these formats, and does the
+// single pass pay off (from four query heads per KV head on, measured)?
+bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
+  if (G < 4 || G > 16) return false;
   if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8);
   if (k_fmt == TTKV_I8_SYM_G32) return G == 4;
   return true;
 }
 
-}  // namespace
-
 bool attn_mfma_eligible(const FusedArgs &a) {
   const int G = a.Hq / a.Hkv;
   for (int j = 0; j < a.n_entries; ++j) {
     const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
-    if (!tier_fits(tv.k_fmt, tv.v_fmt, G)) return false;
+    if (!attn_mfma_fits(tv.k_fmt, tv.v_fmt, G)) return false;
   }
   return true;
 }
