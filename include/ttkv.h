@@ -100,6 +100,7 @@ typedef struct ttkv_stats {
   uint64_t blocks_fetched;  /* host-tier records fetched */
   uint64_t kernels;         /* kernels launched */
   uint64_t demotions;       /* blocks evicted, all tiers and sequences */
+  uint64_t mfma_launches;   /* attention launches served by the grouped-query matrix-core kernel */
   int32_t last_hip_error;   /* hipError_t of the last failed HIP call, 0 if none */
 } ttkv_stats;
 

@@ -37,7 +37,8 @@ class ttkv_cache(C.Structure):
 class ttkv_stats(C.Structure):
     _fields_ = [
         ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64), ("blocks_fetched", C.c_uint64),
-        ("kernels", C.c_uint64), ("demotions", C.c_uint64), ("last_hip_error", C.c_int32),
+        ("kernels", C.c_uint64), ("demotions", C.c_uint64), ("mfma_launches", C.c_uint64),
+        ("last_hip_error", C.c_int32),
     ]
 
 

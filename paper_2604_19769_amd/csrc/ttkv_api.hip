@@ -664,7 +664,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   float *pl = pm + rows * part_stride;
   float *pacc = pl + rows * part_stride;
 
-  int nk = 0;
+  int nk = 0, nm = 0;
   FusedArgs a{};
   a.q = q;
   a.q_fmt = q_fmt;
@@ -703,7 +703,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
       items += r.n_chunks;
     }
     a.n_items = items;
-    TTKV_HIP(h, launch_attn(a, compute, &nk));
+    TTKV_HIP(h, launch_attn(a, compute, &nk, &nm));
   }
   if (timed) {
     TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
@@ -733,7 +733,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
     a.e[0].item_start = 0;
     a.e[0].part_base = f.part_base;
     a.n_items = (f.ntok + f.chunk - 1) / f.chunk;
-    TTKV_HIP(h, launch_attn(a, compute, &nk));
+    TTKV_HIP(h, launch_attn(a, compute, &nk, &nm));
     if (copy != compute) TTKV_HIP(h, hipEventRecord(h->freed[slot], compute));
     ++issued;
   }
@@ -760,6 +760,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   m.out = out;
   m.lse = lse;
   TTKV_HIP(h, launch_merge(m, compute));
+  h->stats.mfma_launches += nm;
   h->stats.kernels += nk + 1;
   return TTKV_OK;
 }

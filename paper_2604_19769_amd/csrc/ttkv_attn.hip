@@ -434,11 +434,14 @@ bool attn_supported(int k_fmt, int v_fmt, int G) {
   return k_fmt == TTKV_I8_SYM_G32 && v_fmt == TTKV_I4_ASYM_G64;
 }
 
-hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels) {
+hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels, int *n_mfma) {
   if (a.n_items <= 0) return hipSuccess;
   const int Gtot = a.Hq / a.Hkv;
   ++*n_kernels;
-  if (attn_mfma_eligible(a)) return launch_attn_mfma(a, s);
+  if (attn_mfma_eligible(a)) {
+    ++*n_mfma;
+    return launch_attn_mfma(a, s);
+  }
   const int G = attn_group_width(Gtot);
   const uint32_t bases = ((uint32_t)a.n_items * a.Hkv + 7) / 8 * 8;
   dim3 grid(bases * (Gtot / G));

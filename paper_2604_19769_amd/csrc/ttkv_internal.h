@@ -151,7 +151,7 @@ struct FusedArgs {
   int32_t Hq, Hkv;
   float scale;
 };
-hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels);
+hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels, int *n_mfma);
 bool attn_supported(int k_fmt, int v_fmt, int G);
 int attn_group_width(int Gtot);
 // Grouped-query kernel on the matrix cores: all query heads of a KV head in one pass over its bytes.

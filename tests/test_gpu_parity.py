@@ -77,7 +77,7 @@ def test_quantize_append_bit_exact(dtype, fmt):
 
 
 def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
-               lens=None, peaked=False):
+               lens=None, peaked=False, want_stats=False):
     p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots)
     worst = 0.0
     try:
@@ -110,7 +110,7 @@ def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap
         assert st["demotions"] == sum(sum(d) for d in p.ora.demotions)
     finally:
         p.close()
-    return worst
+    return st if want_stats else worst
 
 
 def test_config1_tiny_fp16_plus_int8():
@@ -130,8 +130,25 @@ def test_config1_shape_other_slow_formats(fmt):
 
 @pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (8, 1), (12, 4)])
 def test_gqa_ratios_and_ragged_lengths(Hq, Hkv):
-    """Group sizes 1, 2, 8 (two passes of 4), 3; lengths that are not multiples of a tile or a block."""
-    run_config(3, Hq, Hkv, tiers3("bf16", host=False), "bf16", None, 3, synth.SEED_BASE + 3 + Hq, lens=[1, 777, 2500])
+    """Group sizes 1, 2, 8, 3 on the vector kernel (8 heads do not fit the matrix-core tile with an int8 tier);
+    lengths that are not multiples of a tile or a block."""
+    st = run_config(3, Hq, Hkv, tiers3("bf16", host=False), "bf16", None, 3, synth.SEED_BASE + 3 + Hq, lens=[1, 777, 2500],
+                    want_stats=True)
+    assert st["mfma_launches"] == 0, st
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype,slow", [(8, 1, "f16", ("i4", "i4")), (16, 2, "f16", ("i4", "i4")), (16, 1, "f16", ("f16", "f16")),
+                                                (10, 2, "f16", ("f16", "f16")), (12, 2, "bf16", ("bf16", "bf16")), (8, 2, "bf16", ("i8", "i4")),
+                                                (16, 4, "bf16", ("i8", "i8"))])
+def test_grouped_query_group_sizes_on_the_matrix_core_kernel(Hq, Hkv, dtype, slow):
+    """Every (format, heads per KV head) case of the grouped-query kernel: int4 with 8 heads, fp16 with 16 and with
+    counts that are not powers of two (5, 6), K 8-bit / V 4-bit and int8 with 4; ragged lengths leave partial
+    16-token tiles in both tiers, the rings wrap during the steps."""
+    tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=192, block_tokens=64, ring_blocks=4),
+             dict(k_fmt=slow[0], v_fmt=slow[1], capacity=10**9, block_tokens=128, ring_blocks=24)]
+    st = run_config(3, Hq, Hkv, tiers, dtype, None, 70, synth.SEED_BASE + 20 + Hq, lens=[5, 1033, 2890], check_state_every=35,
+                    peaked=True, want_stats=True)
+    assert st["mfma_launches"] == 70, st
 
 
 @pytest.mark.parametrize("n_slots", [0, 2, 3])
