@@ -50,7 +50,7 @@ extern "C" {
 #define TTKV_MAX_TIERS 4
 #define TTKV_MAX_BATCH 64
 #define TTKV_HEAD_DIM 128
-#define TTKV_MAX_SLOTS 8
+#define TTKV_MAX_SLOTS 16
 
 typedef enum {
   TTKV_OK = 0,
@@ -125,8 +125,8 @@ ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *ti
                         int32_t *row, int64_t *record);
 
 /* [device] workspace ttkv_decode_attn needs for this cache: split partials for
- * up to max_parts parts per (sequence, query head) plus n_slots staging records
- * of the largest host tier.  ttkv_tier_demote needs batch records of its
+ * up to max_parts parts per (sequence, query head) plus n_slots staging slots, each
+ * holding the largest run of adjacent host-tier records one copy moves (up to 8 MiB).  ttkv_tier_demote needs batch records of its
  * destination tier when that is a host tier (always covered when n_slots >= batch,
  * else use ttkv_demote_workspace_bytes). */
 size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots);
@@ -187,9 +187,12 @@ ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int
  *   n_slots == 0: host tiers are read in place by the attention kernel (loads
  *        over PCIe stay in flight while other waves compute: the prefetch/compute
  *        overlap of Sec. 4.3 inside one launch); `copy` is not used.
- *   n_slots >= 1: host-tier records are copied with hipMemcpyAsync on `copy` into
- *        n_slots staging slots of `workspace`, event-chained so that copy i+1 runs
- *        while `compute` attends copy i (both streams equal: nothing overlaps).
+ *   n_slots >= 1 (<= TTKV_MAX_SLOTS): host-tier records are copied with hipMemcpyAsync
+ *        on `copy` into n_slots staging slots of `workspace` (adjacent records of a
+ *        dense tier merged up to 8 MiB per copy), event-chained so that copy i+1 runs
+ *        while `compute` attends copy i (both streams equal: nothing overlaps).  A
+ *        slot is reused only after the kernel that read it has finished; enough slots
+ *        for a whole step avoid those waits.
  * Returns after enqueuing; `out` is complete when `compute` has drained. */
 ttkv_status ttkv_decode_attn(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
                              float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,

@@ -10,7 +10,7 @@ LIB_PATH = os.path.join(HERE, "libttkv.so")
 
 TTKV_MAX_TIERS = 4
 TTKV_MAX_BATCH = 64
-TTKV_MAX_SLOTS = 8
+TTKV_MAX_SLOTS = 16
 
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
 F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32 = range(5)
