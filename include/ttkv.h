@@ -221,8 +221,10 @@ ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q
 /* Measurement aid (roofline of the attention kernel; Sec. 5.1 item 4 "latency is
  * measured on the GPU with events"): from now on every ttkv_decode_attn records a
  * HIP event pair around its fused attention launch(es) on the compute stream, for
- * at most max_samples calls (<= 4096); max_samples <= 0 switches it off.  Creates
- * HIP events only.  ttkv_read_attn_timing BLOCKS until the recorded kernels have
+ * at most max_samples calls (<= 4096) in total; max_samples <= 0 pauses it (the
+ * samples taken so far are kept, so a caller can time every n-th step: each event
+ * pair costs a few microseconds of idle stream around the launch).  Creates HIP
+ * events only.  ttkv_read_attn_timing BLOCKS until the recorded kernels have
  * finished, writes their durations in milliseconds (oldest first, at most
  * `capacity`), returns the count in *n_out and clears the samples. */
 ttkv_status ttkv_time_attn(ttkv_handle h, int32_t max_samples);

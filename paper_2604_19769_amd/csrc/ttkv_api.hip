@@ -869,8 +869,7 @@ ttkv_status ttkv_time_attn(ttkv_handle hh, int32_t max_samples) {
     }
     h->time_max = max_samples;
   }
-  h->time_on = true;
-  h->time_n = 0;
+  h->time_on = true;   // samples accumulate until they are read
   return TTKV_OK;
 }
 

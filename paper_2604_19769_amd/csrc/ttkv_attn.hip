@@ -377,9 +377,11 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
   }
 }
 
-// One workgroup of 256 threads per row: two halves of the parts, thread = channel.
+// One workgroup of 256 threads per row: thread = channel, the parts split over the two halves of
+// the workgroup.  Each half scans its parts' maxima itself (the same few addresses for every
+// thread: broadcast loads), so the only exchange is the final merge of the two halves.
 __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
-  __shared__ float s_o[128], s_l2, s_M[2];
+  __shared__ float s_o[128], s_l2, s_M2;
   const int row = blockIdx.x, dch = threadIdx.x & 127, half = threadIdx.x >> 7;
   int n = a.n_parts;
   if (a.n_parts_row)
@@ -389,19 +391,10 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
   const float *pm = a.m + (int64_t)row * a.part_stride;
   const float *pl = a.l + (int64_t)row * a.part_stride;
   const float *pa = a.acc + (int64_t)row * a.part_stride * 128;
-  // global max over all parts: each thread scans a strided subset, then a block reduce
-  __shared__ float s_red[256];
-  float M = -INFINITY;
-  for (int p = threadIdx.x; p < n; p += 256) M = fmaxf(M, pm[p]);
-  s_red[threadIdx.x] = M;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) s_red[threadIdx.x] = fmaxf(s_red[threadIdx.x], s_red[threadIdx.x + s]);
-    __syncthreads();
-  }
-  M = s_red[0];
-  float o = 0.0f, l = 0.0f;
   const int p0 = half ? (n + 1) / 2 : 0, p1 = half ? n : (n + 1) / 2;
+  float M = -INFINITY;
+  for (int p = p0; p < p1; ++p) M = fmaxf(M, pm[p]);
+  float o = 0.0f, l = 0.0f;
 #pragma unroll 4
   for (int p = p0; p < p1; ++p) {
     const float mp = pm[p];
@@ -411,16 +404,20 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
   }
   if (half) {
     s_o[dch] = o;
-    if (dch == 0) s_l2 = l;
+    if (dch == 0) {
+      s_l2 = l;
+      s_M2 = M;
+    }
   }
   __syncthreads();
   if (!half) {
-    o += s_o[dch];
-    l += s_l2;
+    const float M2 = s_M2, Mt = fmaxf(M, M2);
+    const float w1 = M == -INFINITY ? 0.0f : __expf(M - Mt), w2 = M2 == -INFINITY ? 0.0f : __expf(M2 - Mt);
+    o = o * w1 + s_o[dch] * w2;
+    l = l * w1 + s_l2 * w2;
     a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
-    if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? M + __logf(l) : -INFINITY;
+    if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? Mt + __logf(l) : -INFINITY;
   }
-  (void)s_M;
 }
 
 }  // namespace
