@@ -307,6 +307,27 @@ def measure_h2d_peak():
     return n / dt / 1e9
 
 
+def measure_hbm_read_peak(h):
+    """Rate of the library's load-only kernel (the attention kernels' access pattern) over 2 GiB of device
+    memory, HIP events on the launching stream: the practical ceiling beside the nominal 8 TB/s."""
+    import torch
+    from paper_2604_19769_amd import binding as B
+    n = 2 << 30
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        B.ttkv_stream_read(h, buf.data_ptr(), n, sink.data_ptr(), stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        B.ttkv_stream_read(h, buf.data_ptr(), n, sink.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    return n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def decode_only_seconds(cache, q, reps):
     """Attention alone (no append, no eviction), mean over reps, bracketed by full synchronisation."""
     for i in range(2):
@@ -327,7 +348,16 @@ def run_offload128k(steps, warmup):
         timed_steps(cache, q, kn, vn, 0, warmup)
         total, by_tier = algorithmic_bytes(cache)
         s0 = cache.stats()
-        t_step = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        # every step bracketed by a HIP event pair on its stream as well: median and p95 (Sec. 5.1 item 4)
+        import torch
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = sync_time()
+        for s in range(steps):
+            evs[s][0].record()
+            cache.step(q[warmup + s], kn[warmup + s], vn[warmup + s])
+            evs[s][1].record()
+        t_step = (sync_time() - t0) / steps
+        per_step = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
         h2d_per_step = (cache.stats()["h2d_bytes"] - s0["h2d_bytes"]) / steps
         # copy/compute overlap: host-tier streaming alone, device tiers alone, both together, each as the duration
         # of the attention launch itself (HIP event pair on its stream), so that the merge kernel and the launch
@@ -366,6 +396,8 @@ def run_offload128k(steps, warmup):
             "workload": "batch 1, 32 q / 8 kv heads, 131072 tokens: 4K bf16 + 28K int8 in HBM, 96K int4 in pinned host "
                         "DRAM in 1024-token block records",
             "us_per_token": round(t_step * 1e6, 1),
+            "us_per_token_p50": round(per_step[len(per_step) // 2], 1),
+            "us_per_token_p95": round(per_step[min(len(per_step) - 1, int(0.95 * len(per_step)))], 1),
             "attn_only_us": round(t_all * 1e6, 1),
             "host_tier_bytes_per_step": int(h2d_per_step),
             "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
@@ -434,6 +466,9 @@ def main():
                 "achieved": round(k_bytes / (kms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(k_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": MHA32K_MEASURED_TRAFFIC_BYTES,
                 "kernel_us": round(kms * 1e3, 2), "bytes_per_launch": int(k_bytes), "launches_timed": len(kernel_ms)}
+    hbm_read = measure_hbm_read_peak(cache.h)
+    roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
+    roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_mha32k(kv, steps_in, shape, keep[:2])
@@ -449,7 +484,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16/int4 -> f32", "data": "synthetic",
         "config": {"workload": "mha32k: batch 4, 32 heads MHA, head_dim 128, 32768 tokens, recent 2048 fp16 + 30720 int4 "
                                "(group 64, asymmetric) in HBM, append + attend + evict per step",
-                   "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+                   "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+                   "fp16_equivalent_GBs": round(shape["B"] * shape["Hkv"] * shape["N"] * 512 / (secs / K) / 1e9, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
         "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
         "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),

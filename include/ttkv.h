@@ -228,6 +228,12 @@ ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q
  * finished, writes their durations in milliseconds (oldest first, at most
  * `capacity`), returns the count in *n_out and clears the samples. */
 ttkv_status ttkv_time_attn(ttkv_handle h, int32_t max_samples);
+/* Measurement aid: enqueue a load-only kernel that streams `bytes` (rounded down to a
+ * multiple of 64 KiB) of [device] memory at `src` with the attention kernels' access
+ * pattern (128-bit loads, eight in flight per lane, four wave64 per workgroup).  Timed by
+ * the caller, it gives the read rate the memory system delivers to such a kernel, the
+ * practical ceiling beside the nominal HBM peak.  sink: [device] 4 writable bytes. */
+ttkv_status ttkv_stream_read(ttkv_handle h, const void *src, size_t bytes, void *sink, void *stream);
 ttkv_status ttkv_read_attn_timing(ttkv_handle h, float *ms, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus

@@ -47,6 +47,7 @@ EXPORTS = [
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
     "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing", "ttkv_set_split",
+    "ttkv_stream_read",
 ]
 
 _lib = None
@@ -94,6 +95,7 @@ def lib():
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
         L.ttkv_time_attn.argtypes = [p, i32]
+        L.ttkv_stream_read.argtypes = [p, p, sz, p, p]
         L.ttkv_read_attn_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
         for name in EXPORTS:
             f = getattr(L, name)
@@ -167,6 +169,10 @@ def ttkv_append_host_workspace_bytes(cache, tier, seq, n_tokens):
 
 def ttkv_count_parts(h, cache, sel_blocks=None, sel_count=None, sel_stride=0, n_slots=0):
     return lib().ttkv_count_parts(h, C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride, n_slots)
+
+
+def ttkv_stream_read(h, src, nbytes, sink, stream):
+    _check(lib().ttkv_stream_read(h, _p(src), nbytes, _p(sink), _p(stream)), "ttkv_stream_read")
 
 
 def ttkv_set_split(h, target_items):

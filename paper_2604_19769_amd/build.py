@@ -16,6 +16,7 @@ SOURCES = {
     "ttkv_attn.hip": [],
     "ttkv_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],   # MFMA results feed vector code: keep them out of the AGPRs
     "ttkv_select.hip": ["-ffp-contract=off"],
+    "ttkv_probe.hip": [],
 }
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

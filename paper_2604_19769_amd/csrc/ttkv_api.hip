@@ -873,6 +873,14 @@ ttkv_status ttkv_time_attn(ttkv_handle hh, int32_t max_samples) {
   return TTKV_OK;
 }
 
+ttkv_status ttkv_stream_read(ttkv_handle hh, const void *src, size_t bytes, void *sink, void *stream) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !src || !sink) return TTKV_ERR_INVALID_ARG;
+  TTKV_HIP(h, launch_stream_read(src, (int64_t)bytes, (uint32_t *)sink, (hipStream_t)stream));
+  h->stats.kernels += bytes >= 65536;
+  return TTKV_OK;
+}
+
 ttkv_status ttkv_read_attn_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || !ms || !n_out || capacity < 0) return TTKV_ERR_INVALID_ARG;

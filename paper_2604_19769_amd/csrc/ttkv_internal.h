@@ -185,4 +185,7 @@ struct SelectArgs {
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t s);
 
+// Load-only kernel over `bytes` (rounded down to 64 KiB) of device memory; sink: 4 writable bytes.
+hipError_t launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s);
+
 }  // namespace ttkv

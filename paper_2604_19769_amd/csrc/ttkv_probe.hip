@@ -1,0 +1,39 @@
+// Measurement aid: a load-only kernel with the attention kernels' access pattern (workgroups
+// of four wave64 streaming contiguous chunks with 128-bit loads, eight in flight per lane).
+// Its rate is what this device's memory system delivers to such a kernel, the practical
+// ceiling beside the nominal HBM peak (Sec. 5.1 item 4: measured on the GPU).
+#include "ttkv_internal.h"
+
+namespace ttkv {
+
+namespace {
+
+constexpr int kChunk = 64 * 1024;   // bytes per workgroup iteration: 256 lanes x 8 loads x 16 B... x2 rounds
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src, int64_t n_chunks, uint32_t *sink) {
+  uint32_t acc = 0;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const uint4 *p = src + c * (kChunk / 16) + threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      uint4 w[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[i] = p[(r * 8 + i) * 256];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc ^= w[i].x ^ w[i].y ^ w[i].z ^ w[i].w;
+    }
+  }
+  if (acc == 0x9E3779B9u) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
+}  // namespace
+
+hipError_t launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s) {
+  const int64_t n_chunks = bytes / kChunk;
+  if (n_chunks <= 0) return hipSuccess;
+  const int grid = (int)std::min<int64_t>(n_chunks, 256 * 10);
+  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, s, (const uint4 *)src, n_chunks, sink);
+  return hipGetLastError();
+}
+
+}  // namespace ttkv
