@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k"])
+    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "ablation"])
     ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offload-steps", type=int, default=20)
@@ -416,6 +416,83 @@ def run_offload128k(steps, warmup):
         cache.close()
 
 
+# ------------------------------------------------------------------ workload: ablation variants (Sec. 5.4, Table 6)
+
+def run_ablation(steps, warmup):
+    """The ablation table's variants as cache configurations on one synthetic 64K context (32 q / 8 kv heads,
+    recent window 4096, 128-token blocks): per-step latency (median, p95), host-to-GPU bytes per step and, in
+    place of task accuracy, the attention-output error against the all-fp16 cache on the same keys and values."""
+    import torch
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    B, Hq, Hkv, N, R, bt = 1, 32, 8, 65536, 4096, 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 6)
+    K = device_normal(gen, (B, Hkv, N - 1, 128), torch.float16)
+    V = device_normal(gen, (B, Hkv, N - 1, 128), torch.float16)
+    total = steps + warmup + 2
+    q = device_normal(gen, (total, B, Hq, 128), torch.float16)
+    kn = device_normal(gen, (total, B, Hkv, 1, 128), torch.float16)
+    vn = device_normal(gen, (total, B, Hkv, 1, 128), torch.float16)
+    ring = N // bt + 4
+    variants = {
+        "fp16 (recent window in HBM, the rest fp16 on the host)":
+            ([TierConfig("f16", "f16", R, bt, R // bt + 1), TierConfig("f16", "f16", 10**9, bt, ring, mem="host")], 0, True),
+        "single tier (no fast tier beyond one landing block; K 8-bit / V 4-bit on the host)":
+            ([TierConfig("f16", "f16", bt, bt, 2), TierConfig("i8", "i4", 10**9, bt, ring, mem="host")], 0, True),
+        "uniform quantization (8, 8) on the host":
+            ([TierConfig("f16", "f16", R, bt, R // bt + 1), TierConfig("i8", "i8", 10**9, bt, ring, mem="host")], 0, True),
+        "no streaming attention (block copies and kernels serialised on one stream)":
+            ([TierConfig("f16", "f16", R, bt, R // bt + 1), TierConfig("i8", "i4", 10**9, bt, ring, mem="host")], 1, False),
+        "TTKV as in the paper (fp16 recent window, K 8-bit / V 4-bit on the host)":
+            ([TierConfig("f16", "f16", R, bt, R // bt + 1), TierConfig("i8", "i4", 10**9, bt, ring, mem="host")], 0, True),
+        "three tiers (fp16 4K, int8 12K in HBM, int4 on the host)":
+            ([TierConfig("f16", "f16", R, bt, R // bt + 1), TierConfig("i8", "i8", 12288, bt, 12288 // bt + 2),
+              TierConfig("i4", "i4", 10**9, 1024, N // 1024 + 2, mem="host")], 0, True),
+    }
+    rows, ref = [], None
+    for name, (tiers, n_slots, overlap) in variants.items():
+        cache = TieredCache(B, Hq, Hkv, tiers, n_slots=n_slots)
+        try:
+            # N - 1 tokens: tier 0 one short of its capacity, middle tiers full, the oldest rest in the last tier
+            # (whole blocks), every token having passed through the formats of the tiers above its own
+            counts = [tiers[0].capacity - 1] + [t.capacity for t in tiers[1:-1]]
+            counts.append(N - 1 - sum(counts))
+            assert counts[-1] % tiers[-1].block_tokens == 0
+            lo = 0
+            for t in range(len(tiers) - 1, -1, -1):
+                hi = lo + counts[t]
+                cache.append(t, K[:, :, lo:hi].contiguous(), V[:, :, lo:hi].contiguous(), through_tiers=t > 0)
+                lo = hi
+            torch.cuda.synchronize()
+            out0 = cache.decode(q[0], None, overlap)[0].clone()
+            torch.cuda.synchronize()
+            if ref is None:
+                ref = out0
+            err = float((out0 - ref).abs().max() / ref.abs().max())
+            for s in range(warmup):
+                cache.step(q[s], kn[s], vn[s], overlap=overlap)
+            s0 = cache.stats()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for s in range(steps):
+                evs[s][0].record()
+                cache.step(q[warmup + s], kn[warmup + s], vn[warmup + s], overlap=overlap)
+                evs[s][1].record()
+            torch.cuda.synchronize()
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            h2d = (cache.stats()["h2d_bytes"] - s0["h2d_bytes"]) / steps
+            rows.append({"variant": name, "us_per_step_p50": round(us[len(us) // 2], 1),
+                         "us_per_step_p95": round(us[min(len(us) - 1, int(0.95 * len(us)))], 1),
+                         "h2d_MB_per_step": round(h2d / 1e6, 2), "out_err_vs_fp16_rel_max": round(err, 5)})
+            print("ablation:", rows[-1], file=sys.stderr, flush=True)
+        finally:
+            cache.close()
+            torch.cuda.empty_cache()
+    return {"workload": "batch 1, 32 q / 8 kv heads, 65536 tokens, recent window 4096, 128-token blocks, one layer's decode "
+                        "attention per step (append + attend + evict); error = max |out - out_fp16| / max |out_fp16|",
+            "rows": rows}
+
+
 # ------------------------------------------------------------------ main
 
 def main():
@@ -436,6 +513,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload == "ablation":
+        r = run_ablation(K, W)
+        ttkv = [x for x in r["rows"] if x["variant"].startswith("TTKV")][0]
+        line = {"metric": "decode-attn us/step at 64K per ablation variant (Table 6 shape)", "value": ttkv["us_per_step_p50"],
+                "unit": "us", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ttkv["us_per_step_p50"] / 1e3, 4),
+                "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f16/int8/int4 -> f32",
+                "data": "synthetic", "config": {"workload": "ablation: " + r["workload"]}, "ablation": r}
+        print(json.dumps(line))
+        return
     if args.workload == "offload128k":
         r = run_offload128k(K, W)
         line = {"metric": "decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K", "value": r["effective_kv_GBs"],
