@@ -416,6 +416,51 @@ def run_offload128k(steps, warmup):
         cache.close()
 
 
+# ------------------------------------------------------------------ workload: grouped-query tiers resident in HBM
+
+def run_gqa_hbm(reps=12):
+    """32 q / 8 kv heads, batch 4, one HBM-resident tier per case (~0.55-0.6 GB per launch): the attention
+    launch alone (HIP event pair), i.e. the matrix-core kernel's rate per stored format."""
+    import torch
+    from paper_2604_19769_amd import binding as B
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 7)
+    rows = []
+    for fmt, N, dt in (("i8", 65536, torch.float16), ("i4", 131072, torch.float16), ("f16", 32768, torch.float16),
+                       ("bf16", 32768, torch.bfloat16)):
+        fp = "f16" if dt == torch.float16 else "bf16"
+        tiers = [TierConfig(fp, fp, 10**9, 128, N // 128 + 2)] if fmt in ("f16", "bf16") else \
+                [TierConfig(fp, fp, 256, 128, 3), TierConfig(fmt, fmt, 10**9, 128, N // 128 + 2)]
+        cache = TieredCache(4, 32, 8, tiers)
+        try:
+            K, V = device_normal(gen, (4, 8, N, 128), dt), device_normal(gen, (4, 8, N, 128), dt)
+            cache.append(len(tiers) - 1, K, V, through_tiers=True)
+            if len(tiers) == 2:
+                cache.append(0, K[:, :, :128].contiguous(), V[:, :, :128].contiguous())
+            q = device_normal(gen, (4, 4, 32, 128), dt)
+            total, _ = algorithmic_bytes(cache)
+            for i in range(3):
+                cache.decode(q[i])
+            s0 = cache.stats()
+            B.ttkv_time_attn(cache.h, reps)
+            for i in range(reps):
+                cache.decode(q[i % 4])
+            ms = sorted(B.ttkv_read_attn_timing(cache.h))
+            B.ttkv_time_attn(cache.h, 0)
+            us = ms[len(ms) // 2] * 1e3
+            rows.append({"tier": f"{fmt} x {N} tokens", "bytes_per_launch": int(total), "kernel_us": round(us, 1),
+                         "GBs": round(total / us / 1e3, 1), "frac_of_hbm_peak": round(total / us / 1e3 / HBM_PEAK_GBS, 4),
+                         "matrix_core_launches": cache.stats()["mfma_launches"] - s0["mfma_launches"]})
+        finally:
+            cache.close()
+            del K, V
+            torch.cuda.empty_cache()
+    return {"workload": "batch 4, 32 q / 8 kv heads (4 query heads per KV head), one tier in HBM per row, attention launch alone",
+            "rows": rows}
+
+
 # ------------------------------------------------------------------ workload: ablation variants (Sec. 5.4, Table 6)
 
 def run_ablation(steps, warmup):
@@ -575,6 +620,7 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
         "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
         "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),
+        "gqa_hbm": None if args.no_extra else run_gqa_hbm(),
     }
     print(json.dumps(line))
 
