@@ -54,6 +54,19 @@ __device__ __forceinline__ f4 mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_
     return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(h4, A), __builtin_bit_cast(h4, B), c, 0, 0, 0);
 }
 
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+// 32-deep step (v_mfma_f32_16x16x32): lane (c, kg) supplies eight k-values; which eight is free as long as
+// the A and the B lane of the same kg agree, so two 16-deep steps simply concatenate.
+template <bool BF>
+__device__ __forceinline__ f4 mma32(const uint32_t *a, const uint32_t *b, f4 c) {
+  const uint4 A = {a[0], a[1], a[2], a[3]}, B = {b[0], b[1], b[2], b[3]};
+  if constexpr (BF)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, A), __builtin_bit_cast(b8, B), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, A), __builtin_bit_cast(h8, B), c, 0, 0, 0);
+}
+
 __device__ __forceinline__ uint32_t pk(float x, float y) {
   return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x, y));
 }
@@ -169,9 +182,9 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   // byte selector that duplicates the fp16 scale of this lane's channel slice out of the V meta words
   const uint32_t vh = VF == TTKV_I4_ASYM_G64 ? (kg >> 1) * 2 : kg;
   const uint32_t vsel = (2 * vh) | ((2 * vh + 1) << 8) | ((2 * vh) << 16) | ((2 * vh + 1) << 24);
-  // minus the splice offsets, as packed fp16 pairs: -1024, -64, -1152
-  uint32_t no_a = 0xE400E400u, no_b = 0xD400D400u, no_c = 0xE480E480u;
-  asm volatile("" : "+s"(no_a), "+s"(no_b), "+s"(no_c));
+  // minus the splice offsets, as packed fp16 pairs: -1024, -64
+  uint32_t no_a = 0xE400E400u, no_b = 0xD400D400u;
+  asm volatile("" : "+s"(no_a), "+s"(no_b));
 
   const f4 zero4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
   f4 acc[8], accz = zero4;
@@ -224,7 +237,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       for (int x = 0; x < NLK; ++x) unpack16<KF>(t.kw[tt][x], kr + x * (16 / NLK), sp);
       f4 sv = f4{-off, -off, -off, -off};
 #pragma unroll
-      for (int s = 0; s < 8; ++s) sv = mma<KBF>(kr[2 * s], kr[2 * s + 1], qB[2 * s], qB[2 * s + 1], sv);
+      for (int s = 0; s < 4; ++s) sv = mma32<KBF>(kr + 4 * s, qB + 4 * s, sv);
       f4 ksv = zero4, kzv = zero4;
       if constexpr (KQ) ksv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bs0, bs1, zero4);
       if constexpr (KF == TTKV_I4_ASYM_G64) kzv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bz0, bz1, zero4);
@@ -238,7 +251,6 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
           if constexpr (GT <= 4) x += dpp<0x124>(x);
           if constexpr (GT <= 2) x += dpp<0x122>(x);
         }
-        x *= cs;
         if (!FULL && tt * 16 + 4 * kg + i >= nv) x = -INFINITY;
         sv[i] = x;
         mt = fmaxf(mt, x);
@@ -246,50 +258,75 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       S[tt] = sv;
     }
 
-    // ---- online softmax (base 2), per column
+    // ---- online softmax (base 2) per column; m is kept in raw score units, the scale enters the exponent
     mt = fmaxf(mt, __shfl_xor(mt, 16));
     mt = fmaxf(mt, __shfl_xor(mt, 32));
     if (__any(mt > m)) {
       const float mn = fmaxf(m, mt);
-      const float alpha = __builtin_amdgcn_exp2f(m - mn);
+      const float alpha = __builtin_amdgcn_exp2f((m - mn) * cs);
       l *= alpha;
       accz *= alpha;
 #pragma unroll
       for (int s = 0; s < 8; ++s) acc[s] *= alpha;
       m = mn;
     }
+    const float mcs = -m * cs;
+    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 
-    // ---- weighted V
+    // ---- weighted V, two 16-token tiles per 32-deep product
 #pragma unroll
-    for (int tt = 0; tt < NT; ++tt) {
-      float p[4];
+    for (int tp = 0; tp < NT; tp += 2) {
+      uint32_t pB[4];          // softmax weights of the pair, rounded to fp16: the B operand
+      uint32_t vr[2][16];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(S[tt][i] - m);
-      const uint32_t pB0 = pk(p[0], p[1]), pB1 = pk(p[2], p[3]);
-      l += ((float)as_h2(pB0).x + (float)as_h2(pB0).y) + ((float)as_h2(pB1).x + (float)as_h2(pB1).y);
+      for (int u = 0; u < 2; ++u) {
+        const int tt = tp + u;
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(S[tt][i], cs, mcs));
+        pB[2 * u] = pk(p[0], p[1]);
+        pB[2 * u + 1] = pk(p[2], p[3]);
+        l = __builtin_amdgcn_fdot2(as_h2(pB[2 * u]), ones, l, false);       // the row sum uses the rounded weights
+        l = __builtin_amdgcn_fdot2(as_h2(pB[2 * u + 1]), ones, l, false);
 
-      uint32_t vr[16];
 #pragma unroll
-      for (int x = 0; x < NLV; ++x) unpack16<VF>(t.vw[tt][x], vr + x * (16 / NLV), sp);
-      if constexpr (VQ) {
-        // codes -> code * scale in fp16, one rounding (to nearest even): exact offset removal, then the product
-        const h2 vs2 = as_h2(__builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel));
+        for (int x = 0; x < NLV; ++x) unpack16<VF>(t.vw[tt][x], vr[u] + x * (16 / NLV), sp);
+        if constexpr (VQ) {
+          // codes -> code * scale in fp16 with one rounding (to nearest even), while the lane still owns one
+          // token and one group.  (o + n) * s - o * s in one fused step, o = 1024 or 64: o * s is exact while
+          // |s| <= 60; beyond that the offset is removed first.  int8 bytes come out as (code + 128) * s, the
+          // 128 leaves with the zero-point sum below.
+          const uint32_t vsb = __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel);
+          const h2 vs2 = as_h2(vsb);
+          if (!__any((vsb & 0x7fffu) > 0x5380u)) {
+            const h2 na = as_h2(no_a) * vs2, nb = as_h2(no_b) * vs2;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t no = VF == TTKV_I8_SYM_G32 ? no_c : ((r & 1) ? no_b : no_a);
-          vr[r] = __builtin_bit_cast(uint32_t, (as_h2(vr[r]) + as_h2(no)) * vs2);
+            for (int r = 0; r < 16; ++r)
+              vr[u][r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_h2(vr[u][r]), vs2,
+                                                                               (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? nb : na));
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const uint32_t no = (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? no_b : no_a;
+              vr[u][r] = __builtin_bit_cast(uint32_t, (as_h2(vr[u][r]) + as_h2(no)) * vs2);
+            }
+          }
         }
       }
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        const f4 dt = mma<VBF>(vr[2 * s], vr[2 * s + 1], id0, id1, zero4);
-        acc[s] = mma<false>(pk(dt[0], dt[1]), pk(dt[2], dt[3]), pB0, pB1, acc[s]);
+        const f4 d0 = mma<VBF>(vr[0][2 * s], vr[0][2 * s + 1], id0, id1, zero4);
+        const f4 d1 = mma<VBF>(vr[1][2 * s], vr[1][2 * s + 1], id0, id1, zero4);
+        const uint32_t A[4] = {pk(d0[0], d0[1]), pk(d0[2], d0[3]), pk(d1[0], d1[1]), pk(d1[2], d1[3])};
+        acc[s] = mma32<false>(A, pB, acc[s]);
       }
-      if constexpr (VF == TTKV_I4_ASYM_G64) {
-        // zero points: the meta words transposed like a 4-channel V; every row group of four then
-        // holds sum_t p_t * (s0, z0, s1, z1)
-        const f4 dt = mma<false>(t.vmeta[tt].x, t.vmeta[tt].y, id0, id1, zero4);
-        accz = mma<false>(pk(dt[0], dt[1]), pk(dt[2], dt[3]), pB0, pB1, accz);
+      if constexpr (VQ) {
+        // the meta words transposed like a 4-channel V: every row group of four then accumulates
+        // sum_t p_t * (s0, z0, s1, z1) (int4) or sum_t p_t * (s0, s1, s2, s3) (int8)
+        const f4 d0 = mma<false>(t.vmeta[tp].x, t.vmeta[tp].y, id0, id1, zero4);
+        const f4 d1 = mma<false>(t.vmeta[tp + 1].x, t.vmeta[tp + 1].y, id0, id1, zero4);
+        const uint32_t A[4] = {pk(d0[0], d0[1]), pk(d0[2], d0[3]), pk(d1[0], d1[1]), pk(d1[2], d1[3])};
+        accz = mma32<false>(A, pB, accz);
       }
     }
   };
@@ -312,19 +349,21 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   l += __shfl_xor(l, 32);
   float z = 0.0f;
   if constexpr (VF == TTKV_I4_ASYM_G64) z = (kg >> 1) ? accz[3] : accz[1];   // sum_t p_t * zero of this slice's group
+  if constexpr (VF == TTKV_I8_SYM_G32)                                      // -128 * sum_t p_t * scale of this slice's group
+    z = -128.0f * (kg == 0 ? accz[0] : kg == 1 ? accz[1] : kg == 2 ? accz[2] : accz[3]);
   if (n < G) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
       for (int i = 0; i < 4; ++i) s_acc[wave][n][32 * kg + chan<VF>(s, i)] = acc[s][i] + z;
     if (kg == 0) {
-      s_m[wave][n] = m;
+      s_m[wave][n] = m * cs;   // log2 domain
       s_l[wave][n] = l;
     }
   }
 }
 
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const FusedArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_mfma_kernel(const FusedArgs a) {
   __shared__ float s_acc[4][16][128];   // [wave][head][channel]
   __shared__ float s_m[4][16], s_l[4][16];
 
