@@ -1,8 +1,9 @@
 // Grouped-query variant of the split-K decode attention partials (Alg. 1: Attn on the
 // fast tier, Decompress + Attn per slow-tier block): all query heads that share a KV
 // head are served by ONE pass over that head's K/V bytes, with the two contractions on
-// the matrix cores (v_mfma_f32_16x16x16 f16 / bf16).  Same work items, same partials
-// and same record layout as the vector kernel; only the lane mapping differs.
+// the matrix cores (v_mfma_f32_16x16x32 f16 / bf16 for q.k and p.v, v_mfma_f32_16x16x16 for
+// the layout changes).  Same work items, same partials and same record layout as the vector
+// kernel; only the lane mapping differs.
 //
 // One 16-token tile, lane = (c = lane % 16, kg = lane / 16):
 //   K rows are loaded in the MFMA A layout: lane (c, kg) holds channels [32 kg, 32 kg + 32)
@@ -18,13 +19,14 @@
 //   by DPP row rotations, which also leaves every column with its head's score.
 //   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg).
 //   V rows are loaded like K rows and dequantized in packed fp16 while the lane still owns
-//   one token and one group: the splice offset is removed exactly, then code x scale is
-//   rounded once (to nearest even).  A product with the identity matrix brings the tile
+//   one token and one group: (o + n) * s - o * s in one fused multiply-add (o a power of two),
+//   i.e. code x scale rounded once, to nearest even.  A product with the identity matrix brings the tile
 //   from [token][channel] to [channel][token]: the fp32 result (exact) has lane (c, kg)
 //   holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
 //       O[channel][column] += sum_token V^T[channel][token] * P[token][column].
-//   The int4 zero points ride along as a 4-channel V (the meta words transposed the same
-//   way), giving sum_t p_t z_t per group in fp32.  P is rounded to fp16 once and that
+//   Two 16-token tiles feed one 32-deep product.  The int4 zero points, and the 128 that the
+//   int8 splice leaves on every code, ride along as a 4-channel V (the meta words transposed
+//   the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32.  P is rounded to fp16 once and that
 //   rounded value is used for the row sum as well, so the normalisation is consistent.
 //
 // Column budget of the 16-wide tile: groups x heads <= 16 with the head count a power of
