@@ -69,8 +69,11 @@ __device__ __forceinline__ f4 mma32(const uint32_t *a, const uint32_t *b, f4 c) 
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, A), __builtin_bit_cast(h8, B), c, 0, 0, 0);
 }
 
+// two fp32 values -> packed fp16, round to nearest even (v_cvt_pk_f16_f32)
+typedef float f2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk(float x, float y) {
-  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x, y));
+  const f2 v = {x, y};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h2));
 }
 
 template <int F>

@@ -1,0 +1,94 @@
+"""GPU parity on the degenerate and extreme cases of the path: an empty cache, one-token
+sequences, the maximum batch with empty members, selection of no block and of every
+block, rings that wrap many times, more query heads per KV head than any kernel groups."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_19769_amd import binding as B
+from paper_2604_19769_amd import synth
+from ttkv_testlib import Pair, assert_close, dev
+from test_gpu_parity import run_config, tiers3
+
+pytestmark = pytest.mark.gpu
+
+
+def test_empty_cache_then_single_token():
+    """No live token: out = 0, lse = -inf (the identity of the merge).  After one step the only
+    token carries all the weight: out equals its value row, lse its score."""
+    p = Pair(2, 8, 2, tiers3("f16", host=False), "f16")
+    try:
+        g = synth.rng(synth.SEED_BASE + 40)
+        q = synth.normal(g, (2, 8, 128), "f16")
+        out, lse = p.gpu.decode(dev(q, "f16"))
+        torch.cuda.synchronize()
+        assert torch.all(out == 0) and torch.all(torch.isinf(lse) & (lse < 0))
+        kn, vn = synth.normal(g, (2, 2, 128), "f16"), synth.normal(g, (2, 2, 128), "f16")
+        r = p.step(q, kn, vn)
+        assert_close(r[0], r[2], "out")
+        assert_close(r[1], r[3], "lse")
+        want = np.repeat(vn, 4, axis=1)                       # query head h reads KV head h // 4
+        assert np.max(np.abs(r[0] - want)) <= 1e-6
+        score = np.einsum("bhd,bhd->bh", q.astype(np.float64), np.repeat(kn, 4, axis=1).astype(np.float64)) / np.sqrt(128.0)
+        assert np.max(np.abs(r[1] - score)) <= 1e-4
+        p.assert_state_equal()
+    finally:
+        p.close()
+
+
+def test_maximum_batch_with_empty_and_one_token_members():
+    """TTKV_MAX_BATCH sequences, some empty, some with one token, the rest ragged: more (tier, sequence) runs
+    than one launch table holds, empty rows merge to the identity."""
+    n = B.TTKV_MAX_BATCH if hasattr(B, "TTKV_MAX_BATCH") else 64
+    lens = [0 if i % 9 == 0 else 1 if i % 9 == 1 else 30 + 53 * i for i in range(n)]
+    tiers = tiers3("f16", host=False, bts=(64, 64, 64), caps=(128, 256), rings=(3, 6, 60))
+    run_config(n, 4, 2, tiers, "f16", None, 2, synth.SEED_BASE + 41, lens=lens)
+
+
+@pytest.mark.parametrize("n_slots", [0, 2])
+def test_selecting_no_block_and_every_block(n_slots):
+    """k = 0: only the device tiers are attended, nothing crosses PCIe.  k >= live blocks: identical to dense."""
+    tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
+    for k in (0, 1000):
+        p = Pair(2, 8, 2, tiers, "bf16", n_slots=n_slots)
+        try:
+            g = synth.rng(synth.SEED_BASE + 42)
+            for b in range(2):
+                kk, vv = synth.kv((synth.SEED_BASE + 42) * 31 + b, 2, 3000, "bf16")
+                p.load(b, kk, vv)
+            for s in range(3):
+                q = synth.normal(g, (2, 8, 128), "bf16")
+                kn, vn = synth.normal(g, (2, 2, 128), "bf16"), synth.normal(g, (2, 2, 128), "bf16")
+                before = p.gpu.stats()["h2d_bytes"]
+                r = p.step(q, kn, vn, select_k=k)
+                assert_close(r[0], r[2], f"out k={k} step {s}")
+                assert_close(r[1], r[3], f"lse k={k} step {s}")
+                for b in range(2):
+                    assert np.array_equal(r[4][b], r[5][b])
+                moved = p.gpu.stats()["h2d_bytes"] - before
+                if k == 0:
+                    assert moved == 0 and all(len(x) == 0 for x in r[4])
+                else:       # every live block of the last tier, in ascending order
+                    assert moved > 0
+                    for b in range(2):
+                        assert len(r[4][b]) >= 16 and np.array_equal(r[4][b], np.arange(r[4][b][0], r[4][b][0] + len(r[4][b])))
+            assert p.gpu.stats()["h2d_bytes"] == p.ora.h2d_bytes
+        finally:
+            p.close()
+
+
+def test_rings_wrap_many_times():
+    """Small rings on every tier (host included): 700 steps wrap the fp16 ring 11 times and the int8 ring
+    5 times while blocks fall off nothing (the last tier is large enough); state compared along the way."""
+    tiers = tiers3("f16", bts=(64, 64, 128), caps=(128, 256), rings=(3, 5, 12))
+    run_config(2, 8, 2, tiers, "f16", None, 700, synth.SEED_BASE + 43, lens=[100, 611], check_state_every=175,
+               oracle_max_tokens=[1600, 1600, 1600])     # the oracle keeps every token a tier ever held
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype", [(64, 2, "f16"), (40, 2, "bf16"), (6, 2, "f16")])
+def test_many_query_heads_per_kv_head(Hq, Hkv, dtype):
+    """32 and 20 query heads per KV head exceed the matrix-core tile: head pairs on the vector kernel;
+    3 heads per KV head run one by one."""
+    st = run_config(2, Hq, Hkv, tiers3(dtype, host=False), dtype, None, 3, synth.SEED_BASE + 44 + Hq, lens=[333, 2100],
+                    want_stats=True)
+    assert st["mfma_launches"] == 0

@@ -77,8 +77,8 @@ def test_quantize_append_bit_exact(dtype, fmt):
 
 
 def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
-               lens=None, peaked=False, want_stats=False):
-    p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots)
+               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None):
+    p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots, oracle_max_tokens=oracle_max_tokens)
     worst = 0.0
     try:
         g = synth.rng(seed)
