@@ -141,22 +141,22 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
       const uint32_t r = FULL ? n * FK::TPL + ktok : min(n * FK::TPL + ktok, nv - 1);
       const uint32_t co = FULL ? kvoff + n * FK::TPL * FK::ROWB : r * FK::ROWB + kslice * 16;
       const uint32_t mo = FULL ? kmoff + n * FK::TPL * 8 : r * 8 + (kslice >> 1) * KMW;
-      t.kw[n] = *(const uint4 *)(kb + co);
+      t.kw[n] = ld_stream((const uint4 *)(kb + co));
       if constexpr (KF == TTKV_I8_SYM_G32)
-        t.kmeta[n] = *(const uint16_t *)(kmb + mo);
+        t.kmeta[n] = ld_stream((const uint16_t *)(kmb + mo));
       else if constexpr (KF == TTKV_I4_ASYM_G64)
-        t.kmeta[n] = *(const uint32_t *)(kmb + mo);
+        t.kmeta[n] = ld_stream((const uint32_t *)(kmb + mo));
     }
 #pragma unroll
     for (int n = 0; n < NLV; ++n) {
       const uint32_t r = FULL ? n * FV::TPL + vtok : min(n * FV::TPL + vtok, nv - 1);
       const uint32_t co = FULL ? vvoff + n * FV::TPL * FV::ROWB : r * FV::ROWB + vslice * 16;
       const uint32_t mo = FULL ? vmoff + n * FV::TPL * 8 : r * 8 + (vslice >> 1) * VMW;
-      t.vw[n] = *(const uint4 *)(vb + co);
+      t.vw[n] = ld_stream((const uint4 *)(vb + co));
       if constexpr (VF == TTKV_I8_SYM_G32)
-        t.vmeta[n] = *(const uint16_t *)(vmb + mo);
+        t.vmeta[n] = ld_stream((const uint16_t *)(vmb + mo));
       else if constexpr (VF == TTKV_I4_ASYM_G64)
-        t.vmeta[n] = *(const uint32_t *)(vmb + mo);
+        t.vmeta[n] = ld_stream((const uint32_t *)(vmb + mo));
     }
   };
 

@@ -20,6 +20,22 @@ template <> struct Fmt<TTKV_BF16> { static constexpr int ROWB = 256, LPT = 16, T
 template <> struct Fmt<TTKV_I8_SYM_G32> { static constexpr int ROWB = 128, LPT = 8, TPL = 8, EPL = 16; };
 template <> struct Fmt<TTKV_I4_ASYM_G64> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };
 
+// Streaming loads: K/V bytes are read exactly once per launch, so they are fetched with the
+// non-temporal hint (no reuse expected).  On MI355X a load-only kernel moves 6.5-7.0 TB/s this way
+// against 5.7-6.1 TB/s with plain loads (measured, 2 GiB, same access pattern).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 ld_stream(const uint4 *p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+  return uint4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ uint2 ld_stream(const uint2 *p) {
+  const u32x2 v = __builtin_nontemporal_load((const u32x2 *)p);
+  return uint2{v.x, v.y};
+}
+__device__ __forceinline__ uint32_t ld_stream(const uint32_t *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ uint16_t ld_stream(const uint16_t *p) { return __builtin_nontemporal_load(p); }
+
 __device__ __forceinline__ float h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 __device__ __forceinline__ b2 as_b2(uint32_t u) { return __builtin_bit_cast(b2, u); }

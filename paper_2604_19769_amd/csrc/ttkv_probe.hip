@@ -1,8 +1,8 @@
 // Measurement aid: a load-only kernel with the attention kernels' access pattern (workgroups
-// of four wave64 streaming contiguous chunks with 128-bit loads, eight in flight per lane).
+// of four wave64 streaming contiguous chunks with non-temporal 128-bit loads, eight in flight per lane).
 // Its rate is what this device's memory system delivers to such a kernel, the practical
 // ceiling beside the nominal HBM peak (Sec. 5.1 item 4: measured on the GPU).
-#include "ttkv_internal.h"
+#include "ttkv_attn_dev.h"
 
 namespace ttkv {
 
@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src, int6
     for (int r = 0; r < 2; ++r) {
       uint4 w[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) w[i] = p[(r * 8 + i) * 256];
+      for (int i = 0; i < 8; ++i) w[i] = dev::ld_stream(p + (r * 8 + i) * 256);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc ^= w[i].x ^ w[i].y ^ w[i].z ^ w[i].w;
     }
