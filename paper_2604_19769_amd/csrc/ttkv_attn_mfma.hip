@@ -88,6 +88,16 @@ constexpr int chan(int s, int i) {
     return 8 * (s / 2) + ((s % 2) ? (i < 2 ? 2 + 4 * i : 3 + 4 * (i - 2)) : (i < 2 ? 4 * i : 1 + 4 * (i - 2)));
   return 4 * s + i;
 }
+// A lane's 32 channels of a row are the 16-byte pieces kg, kg + 4, ... of it (piece x of the lane = bytes
+// [64 x + 16 kg, + 16) of the row), so that every load instruction of a tile reads 64 contiguous bytes per row
+// (measured on a load-only kernel: 6.3 TB/s, against 5.3 TB/s when a lane's pieces are adjacent).  Element j
+// of the lane's slice (j = 4 s + i in unpack order for fp16 / bf16 / int8) is therefore row channel:
+template <int F>
+__device__ __forceinline__ constexpr int slice_channel(int kg, int j) {
+  if (F == TTKV_I4_ASYM_G64) return 32 * kg + j;                          // one piece of 32 channels
+  if (F == TTKV_I8_SYM_G32) return 64 * (j / 16) + 16 * kg + j % 16;      // two pieces of 16
+  return 32 * (j / 8) + 8 * kg + j % 8;                                   // four pieces of 8
+}
 // Splice offset carried by k-value i of a step.
 template <int F>
 constexpr float k_offset(int i) {
@@ -120,17 +130,18 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 
   const int g = n % G;                                   // head of this column
   const int gam = KQ ? min(n / G, NGK - 1) : 0;          // K group of this column
-  const bool active = n < NGK * G && gam == kg * NGK / 4;  // does the lane's channel slice lie in the column's group
+  const bool col_on = n < NGK * G;
 
-  // ---- q operand: 16 packed registers (step s: 2s, 2s+1), offset sum and plain sum of the column
+  // ---- q operand: 16 packed registers (step s: 2s, 2s+1), offset sum and plain sum of the column.  Element j
+  // of the lane's slice enters only if its channel lies in the column's group.
   uint32_t qB[16];
   float off = 0.0f, qs = 0.0f;
   {
-    const uint4 *qsrc = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * G + g) * 128 + kg * 32);
+    const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * G + g) * 128);
     uint32_t qw[16];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint4 w = qsrc[i];
+    for (int i = 0; i < 4; ++i) {     // 8 channels per 16-byte load
+      const uint4 w = qrow[slice_channel<KF>(kg, 8 * i) / 8];
       qw[4 * i] = w.x; qw[4 * i + 1] = w.y; qw[4 * i + 2] = w.z; qw[4 * i + 3] = w.w;
     }
     if constexpr (!KBF) {
@@ -150,19 +161,15 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = chan<KF>(s, i);
-        const uint32_t bits = (qw[j / 2] >> (16 * (j % 2))) & 0xffffu;
+        const bool on = col_on && slice_channel<KF>(kg, j) / (128 / NGK) == gam;
+        const uint32_t bits = on ? (qw[j / 2] >> (16 * (j % 2))) & 0xffffu : 0u;
         qB[2 * s + i / 2] |= bits << (16 * (i % 2));
         const float v = KBF ? __uint_as_float(bits << 16) : h2f((uint16_t)bits);
         qs += v;
         off = fmaf(v, k_offset<KF>(i), off);
       }
     }
-    if (!active) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) qB[r] = 0;
-      off = qs = 0.0f;
-    }
-    // the column's group spans one, two or four channel slices; the others contribute zero
+    // the column's group is spread over the channel slices of several lanes; the others contributed zero
     off += __shfl_xor(off, 16); off += __shfl_xor(off, 32);
     qs += __shfl_xor(qs, 16);   qs += __shfl_xor(qs, 32);
   }
@@ -184,9 +191,14 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       bz1 = gam == 1 ? 0x3C000000u : 0u;
     }
   }
-  // byte selector that duplicates the fp16 scale of this lane's channel slice out of the V meta words
-  const uint32_t vh = VF == TTKV_I4_ASYM_G64 ? (kg >> 1) * 2 : kg;
-  const uint32_t vsel = (2 * vh) | ((2 * vh + 1) << 8) | ((2 * vh) << 16) | ((2 * vh + 1) << 24);
+  // byte selectors that duplicate the fp16 scale of the group of this lane's piece x out of the V meta words:
+  // int4 (s0, z0, s1, z1): one piece, group kg / 2; int8 (s0, s1, s2, s3): piece x lies in group 2 x + kg / 2
+  uint32_t vsel[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const uint32_t vh = VF == TTKV_I4_ASYM_G64 ? (kg >> 1) * 2 : 2 * x + (kg >> 1);
+    vsel[x] = (2 * vh) | ((2 * vh + 1) << 8) | ((2 * vh) << 16) | ((2 * vh + 1) << 24);
+  }
   // minus the splice offsets, as packed fp16 pairs: -1024, -64
   uint32_t no_a = 0xE400E400u, no_b = 0xD400D400u;
   asm volatile("" : "+s"(no_a), "+s"(no_b));
@@ -204,11 +216,11 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     uint4 kw[NT][NLK], vw[NT][NLV];
     uint2 kmeta[NT], vmeta[NT];
   };
-  const uint32_t kdoff = n * FK::ROWB + kg * (FK::ROWB / 4), vdoff = n * FV::ROWB + kg * (FV::ROWB / 4);
+  const uint32_t kdoff = n * FK::ROWB + kg * 16, vdoff = n * FV::ROWB + kg * 16;
 
-  // Plain loads here, not the non-temporal ones of the vector kernel: the 16-byte pieces of a lane's 32 or 64
-  // bytes share cache lines between the load instructions of a tile, and lines fetched with the streaming hint
-  // do not survive until the next instruction (fp16 tiers: 3.4 instead of 5.3 TB/s, measured).
+  // Plain loads here, not the non-temporal ones of the vector kernel: the load instructions of a tile share
+  // cache lines (each reads 64 of a line's 128 bytes), and lines fetched with the streaming hint do not
+  // survive until the next instruction.
   auto load_tiles = [&](TileRegs &t, int i0, int nv, auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
     int tok0 = en.first_tok + i0;
@@ -222,12 +234,12 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
       const uint32_t row = FULL ? tt * 16 + n : min(tt * 16 + n, nv - 1);   // rows past the end re-read the last live row
-      const uint32_t ko = FULL ? kdoff + tt * 16 * FK::ROWB : row * FK::ROWB + kg * (FK::ROWB / 4);
-      const uint32_t vo = FULL ? vdoff + tt * 16 * FV::ROWB : row * FV::ROWB + kg * (FV::ROWB / 4);
+      const uint32_t ko = FULL ? kdoff + tt * 16 * FK::ROWB : row * FK::ROWB + kg * 16;
+      const uint32_t vo = FULL ? vdoff + tt * 16 * FV::ROWB : row * FV::ROWB + kg * 16;
 #pragma unroll
-      for (int x = 0; x < NLK; ++x) t.kw[tt][x] = *(const uint4 *)(kb + ko + 16 * x);
+      for (int x = 0; x < NLK; ++x) t.kw[tt][x] = *(const uint4 *)(kb + ko + 64 * x);
 #pragma unroll
-      for (int x = 0; x < NLV; ++x) t.vw[tt][x] = *(const uint4 *)(vb + vo + 16 * x);
+      for (int x = 0; x < NLV; ++x) t.vw[tt][x] = *(const uint4 *)(vb + vo + 64 * x);
       if constexpr (KQ) t.kmeta[tt] = *(const uint2 *)(kmb + row * 8);
       if constexpr (VQ) t.vmeta[tt] = *(const uint2 *)(vmb + row * 8);
     }
@@ -304,19 +316,21 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
           // token and one group.  (o + n) * s - o * s in one fused step, o = 1024 or 64: o * s is exact while
           // |s| <= 60; beyond that the offset is removed first.  int8 bytes come out as (code + 128) * s, the
           // 128 leaves with the zero-point sum below.
-          const uint32_t vsb = __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel);
-          const h2 vs2 = as_h2(vsb);
-          if (!__any((vsb & 0x7fffu) > 0x5380u)) {
-            const h2 na = as_h2(no_a) * vs2, nb = as_h2(no_b) * vs2;
+          const uint32_t vsb0 = __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel[0]);
+          const uint32_t vsb1 = VF == TTKV_I8_SYM_G32 ? __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel[1]) : vsb0;
+          const h2 vs2[2] = {as_h2(vsb0), as_h2(vsb1)};
+          if (!__any(((vsb0 | vsb1) & 0x7fffu) > 0x5380u)) {   // (an upper bound of both magnitudes)
+            const h2 na[2] = {as_h2(no_a) * vs2[0], as_h2(no_a) * vs2[1]};
+            const h2 nb = as_h2(no_b) * vs2[0];
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-              vr[u][r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_h2(vr[u][r]), vs2,
-                                                                               (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? nb : na));
+              vr[u][r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_h2(vr[u][r]), vs2[r / 8],
+                                                                               (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? nb : na[r / 8]));
           } else {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const uint32_t no = (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? no_b : no_a;
-              vr[u][r] = __builtin_bit_cast(uint32_t, (as_h2(vr[u][r]) + as_h2(no)) * vs2);
+              vr[u][r] = __builtin_bit_cast(uint32_t, (as_h2(vr[u][r]) + as_h2(no)) * vs2[r / 8]);
             }
           }
         }
@@ -352,18 +366,21 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
   }
 
-  // ---- the wave's result: column n < G of lane (n, kg) holds channels 32 kg + chan(s, i)
+  // ---- the wave's result: column n < G of lane (n, kg) holds, in acc[s][i], the row channel of slice element
+  // chan(s, i); the zero-point sums of that channel's group are added here
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  float z = 0.0f;
-  if constexpr (VF == TTKV_I4_ASYM_G64) z = (kg >> 1) ? accz[3] : accz[1];   // sum_t p_t * zero of this slice's group
-  if constexpr (VF == TTKV_I8_SYM_G32)                                      // -128 * sum_t p_t * scale of this slice's group
-    z = -128.0f * (kg == 0 ? accz[0] : kg == 1 ? accz[1] : kg == 2 ? accz[2] : accz[3]);
+  float z[2] = {0.0f, 0.0f};   // for the channels of piece 0 / piece 1 (int8), of the one piece (int4)
+  if constexpr (VF == TTKV_I4_ASYM_G64) z[0] = z[1] = (kg >> 1) ? accz[3] : accz[1];   // sum_t p_t * zero
+  if constexpr (VF == TTKV_I8_SYM_G32) {                                               // -128 * sum_t p_t * scale
+    z[0] = -128.0f * ((kg >> 1) ? accz[1] : accz[0]);
+    z[1] = -128.0f * ((kg >> 1) ? accz[3] : accz[2]);
+  }
   if (n < G) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s_acc[wave][n][32 * kg + chan<VF>(s, i)] = acc[s][i] + z;
+      for (int i = 0; i < 4; ++i) s_acc[wave][n][slice_channel<VF>(kg, chan<VF>(s, i))] = acc[s][i] + z[s / 4];
     if (kg == 0) {
       s_m[wave][n] = m * cs;   // log2 domain
       s_l[wave][n] = l;
