@@ -114,7 +114,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
-  constexpr int NT = NLK == 4 ? 2 : 4 / NLK;                 // tiles in flight per wave
+  constexpr int NT = NLK == 4 ? 2 : 4 / NLK;                 // tiles in flight per wave (int4: 4; with 2 the kernel is 10 % slower)
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
