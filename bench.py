@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 # HBM bytes per mha32k attention launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, each scaled by
 # a plain copy kernel's reading (profiles/attn_fused_mha32k_hbm_traffic_pmc.txt); 1.004 x algorithmic
-MHA32K_MEASURED_TRAFFIC_BYTES = 697.2e6
+MHA32K_MEASURED_TRAFFIC_BYTES = 697.0e6
 PCIE_PEAK_GBS = 64.0        # PCIe Gen5 x16 per direction, nominal
 SEED = 1976900
 
