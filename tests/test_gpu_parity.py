@@ -151,6 +151,19 @@ def test_grouped_query_group_sizes_on_the_matrix_core_kernel(Hq, Hkv, dtype, slo
     assert st["mfma_launches"] == 70, st
 
 
+@pytest.mark.parametrize("fast_cap,slow,n_slots,overlap", [(256, ("f16", "f16"), 0, True), (256, ("i8", "i4"), 0, True),
+                                                          (64, ("i8", "i4"), 0, True), (256, ("i8", "i8"), 0, True),
+                                                          (256, ("i8", "i4"), 1, False), (256, ("f16", "f16"), 2, True)])
+def test_two_tier_layouts_of_the_ablation_table(fast_cap, slow, n_slots, overlap):
+    """The paper's two-tier layouts (Sec. 5.4): fp16 window in HBM + everything older on the host as fp16 (the
+    FP16 baseline), as K 8-bit / V 4-bit (TTKV), with no fast tier beyond one landing block, as uniform (8, 8),
+    and without streaming (copies and kernels serialised on one stream)."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=fast_cap, block_tokens=64, ring_blocks=fast_cap // 64 + 1),
+             dict(k_fmt=slow[0], v_fmt=slow[1], capacity=10**9, block_tokens=64, ring_blocks=50, mem="host")]
+    run_config(2, 8, 2, tiers, "f16", None, 70, synth.SEED_BASE + 30 + fast_cap, lens=[900, 2777], check_state_every=35,
+               n_slots=n_slots, overlap=overlap)
+
+
 @pytest.mark.parametrize("n_slots", [0, 2, 3])
 def test_three_tiers_with_host_streaming_and_eviction_cascade(n_slots):
     """fp16 -> int8 (HBM) -> int4 (pinned host): 150 steps cross several evictions of both device tiers;
