@@ -27,6 +27,8 @@ def lib():
         L.o_dequant_i8_sym_g32.argtypes = [p, p, i64, i32, p]
         L.o_quant_i4_asym_g64.argtypes = [p, i64, i32, p, p, p]
         L.o_dequant_i4_asym_g64.argtypes = [p, p, p, i64, i32, p]
+        L.o_quant_i4_asym_t128.argtypes = [p, i64, i32, p, p, p]
+        L.o_dequant_i4_asym_t128.argtypes = [p, p, p, i64, i32, p]
         L.o_attn_partial.argtypes = [p, i32, i32, i32, p, p, i64, i64, i64, f64, p, p, p]
         L.o_merge_into.argtypes = [p, p, p, p, p, p, i32, i32]
         L.o_finalize.argtypes = [p, p, p, i32, i32, p, p]
@@ -102,6 +104,36 @@ def dequant_i4(packed, scale, zero):
     d = packed.shape[-1] * 2
     out = np.empty(packed.shape[:-1] + (d,), np.float32)
     lib().o_dequant_i4_asym_g64(_ptr(packed), _ptr(scale), _ptr(zero), out.size // d, d, _ptr(out))
+    return out
+
+
+def quant_i4_tokens(x):
+    """Q2 with groups of 128 consecutive tokens per channel, on x [..., n, d] fp32 (n a multiple of 128)
+    -> (packed uint8 [..., n, d/2], scale bits, zero bits [..., n/128, d])."""
+    x = _c(x, np.float32)
+    n, d = x.shape[-2], x.shape[-1]
+    assert n % 128 == 0
+    lead = x.shape[:-2]
+    packed = np.zeros(lead + (n, d // 2), np.uint8)
+    scale = np.empty(lead + (n // 128, d), np.uint16)
+    zero = np.empty(lead + (n // 128, d), np.uint16)
+    xs, ps = x.reshape(-1, n, d), packed.reshape(-1, n, d // 2)
+    ss, zs = scale.reshape(-1, n // 128, d), zero.reshape(-1, n // 128, d)
+    for i in range(xs.shape[0]):
+        lib().o_quant_i4_asym_t128(_ptr(xs[i]), n, d, _ptr(ps[i]), _ptr(ss[i]), _ptr(zs[i]))
+    return packed, scale, zero
+
+
+def dequant_i4_tokens(packed, scale, zero):
+    packed = _c(packed, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    n, d = packed.shape[-2], packed.shape[-1] * 2
+    out = np.empty(packed.shape[:-1] + (d,), np.float32)
+    ps, os_ = packed.reshape(-1, n, d // 2), out.reshape(-1, n, d)
+    ss, zs = scale.reshape(-1, n // 128, d), zero.reshape(-1, n // 128, d)
+    for i in range(ps.shape[0]):
+        lib().o_dequant_i4_asym_t128(_ptr(ps[i]), _ptr(ss[i]), _ptr(zs[i]), n, d, _ptr(os_[i]))
     return out
 
 

@@ -24,7 +24,7 @@ FP_FORMATS = ("f16", "bf16")
 
 @dataclass
 class TierSpec:
-    k_fmt: str            # 'f16' | 'bf16' | 'i8' (Q1) | 'i4' (Q2)
+    k_fmt: str            # 'f16' | 'bf16' | 'i8' (Q1) | 'i4' (Q2) | 'i4t' (Q2 over 128 tokens per channel; keys only)
     v_fmt: str
     capacity: int         # tokens; eviction threshold (L_fast for tier 0)
     block_tokens: int     # B_blk of this tier: eviction unit out of it, attention / fetch unit in it
@@ -40,6 +40,8 @@ def bytes_per_token_head(fmt, d):
         return d + 2 * (d // 32)
     if fmt == "i4":
         return d // 2 + 4 * (d // 64)
+    if fmt == "i4t":
+        return d // 2 + 4 * d // 128          # one (scale, zero) pair per channel and 128 tokens
     raise ValueError(fmt)
 
 
@@ -66,6 +68,9 @@ class _Seq:
         if fmt == "i4":
             return {"codes": np.zeros((Hkv, M, d // 2), np.uint8), "scale": np.zeros((Hkv, M, d // 64), np.uint16),
                     "zero": np.zeros((Hkv, M, d // 64), np.uint16)}
+        if fmt == "i4t":
+            return {"codes": np.zeros((Hkv, M, d // 2), np.uint8), "scale": np.zeros((Hkv, (M + 127) // 128, d), np.uint16),
+                    "zero": np.zeros((Hkv, (M + 127) // 128, d), np.uint16)}
         return None
 
 
@@ -84,6 +89,13 @@ def _store(fmt, x, hat, q, lo, hi):
         q["scale"][:, lo:hi] = scale
         q["zero"][:, lo:hi] = zero
         hat[:, lo:hi] = O.dequant_i4(codes, scale, zero)
+    elif fmt == "i4t":
+        assert lo % 128 == 0 and (hi - lo) % 128 == 0, "token groups of 128 arrive whole and aligned"
+        codes, scale, zero = O.quant_i4_tokens(x)
+        q["codes"][:, lo:hi] = codes
+        q["scale"][:, lo // 128:hi // 128] = scale
+        q["zero"][:, lo // 128:hi // 128] = zero
+        hat[:, lo:hi] = O.dequant_i4_tokens(codes, scale, zero)
     else:
         raise ValueError(fmt)
 
@@ -283,4 +295,4 @@ def _roundtrip(fmt, x):
         return O.dequant_i8(*O.quant_i8(x))
     if fmt == "i4":
         return O.dequant_i4(*O.quant_i4(x))
-    raise ValueError(fmt)
+    raise ValueError(fmt)     # 'i4t' is a last-tier format: nothing passes through it

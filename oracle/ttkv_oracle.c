@@ -175,6 +175,61 @@ void o_dequant_i4_asym_g64(const uint8_t *packed, const uint16_t *scale, const u
     }
 }
 
+/* Q2 with the group turned by 90 degrees: asymmetric int4 where a group is the
+ * 128 values one channel takes over 128 consecutive tokens (keys have the larger
+ * variance and dynamic range, Sec. 3 "Tier Content" and Sec. 4.2, and it sits in a few
+ * channels; a group along the tokens keeps such a channel from setting the
+ * scale of its 63 neighbours).  Same arithmetic as o_quant_i4_asym_g64, same
+ * nibble packing of a token's row.  x [tokens][d], tokens a multiple of 128;
+ * packed [tokens][d/2]; scale, zero [tokens/128][d] fp16 bits. */
+void o_quant_i4_asym_t128(const float *x, int64_t tokens, int32_t d, uint8_t *packed, uint16_t *scale,
+                          uint16_t *zero) {
+  for (int64_t g = 0; g < tokens / 128; ++g)
+    for (int32_t j = 0; j < d; ++j) {
+      const float *xg = x + g * 128 * d + j; /* stride d */
+      float lo = xg[0], hi = xg[0];
+      for (int t = 1; t < 128; ++t) {
+        float v = xg[(int64_t)t * d];
+        if (v < lo) lo = v;
+        if (v > hi) hi = v;
+      }
+      if (lo == 0.0f) lo = 0.0f; /* a zero minimum is stored as +0 whatever its sign */
+      float s32 = (hi - lo) / 15.0f;
+      uint16_t sh = o_f32_to_f16(s32);
+      uint16_t zh = o_f32_to_f16(lo);
+      float s = o_f16_to_f32(sh);
+      float z = o_f16_to_f32(zh);
+      scale[g * d + j] = sh;
+      zero[g * d + j] = zh;
+      for (int t = 0; t < 128; ++t) {
+        float q = 0.0f;
+        if (s != 0.0f) {
+          q = rintf((xg[(int64_t)t * d] - z) / s);
+          if (q > 15.0f) q = 15.0f;
+          if (q < 0.0f) q = 0.0f;
+        }
+        uint8_t *byte = packed + (g * 128 + t) * (d / 2) + j / 2;
+        if (j & 1)
+          *byte = (uint8_t)((*byte & 0x0f) | ((uint8_t)q << 4));
+        else
+          *byte = (uint8_t)((*byte & 0xf0) | (uint8_t)q);
+      }
+    }
+}
+
+/* Decompress for the above: xhat = float(code) * float(scale) + float(zero),
+ * a multiply then an add, each rounded to fp32. */
+void o_dequant_i4_asym_t128(const uint8_t *packed, const uint16_t *scale, const uint16_t *zero,
+                            int64_t tokens, int32_t d, float *xhat) {
+  for (int64_t t = 0; t < tokens; ++t)
+    for (int32_t j = 0; j < d; ++j) {
+      uint8_t byte = packed[t * (d / 2) + j / 2];
+      float c = (float)((j & 1) ? (byte >> 4) : (byte & 0xf));
+      volatile float prod = c * o_f16_to_f32(scale[(t / 128) * d + j]);
+      xhat[t * d + j] = prod + o_f16_to_f32(zero[(t / 128) * d + j]);
+    }
+}
+
 /* ------------------------------------------------------------- attention */
 
 /* One un-normalised partial of Alg. 1's Attn(q, K, V) for every query head of

@@ -298,3 +298,28 @@ def test_h2d_traffic_closed_form():
     assert c.blocks_fetched == 12 and c.h2d_bytes == 12 * 64 * 2 * 144
     c.attend(q, c.select(q, 5))
     assert c.blocks_fetched == 17
+
+
+def test_two_tier_cache_with_keys_grouped_over_tokens():
+    """fp16 window of one 128-token block in front of a tier whose keys are int4 with one (scale, zero) per
+    channel and 128 tokens: whole blocks arrive by eviction, the stored codes are that quantizer's on the raw
+    keys, and a step equals plain softmax attention over the decompressed union."""
+    rng = np.random.default_rng(31)
+    tiers = [TierSpec("f16", "f16", 128, 128), TierSpec("i4t", "i4", 10**9, 128)]
+    c = OracleCache(1, 4, 2, 128, tiers, [1024, 1024])
+    hist = []
+    for _ in range(400):
+        q, k, v = rand(rng, 1, 4, 128), rand(rng, 1, 2, 128), rand(rng, 1, 2, 128)
+        hist.append((q, k, v))
+        out, lse = c.step(q, k, v)
+    s1, s0 = c.seq[1][0], c.seq[0][0]
+    assert s1.count == 384 and s0.count == 16 and c.demotions[0][0] == 3
+    k_raw = np.stack([h[1][0] for h in hist], 1)[:, :384]
+    want = O.quant_i4_tokens(k_raw)
+    assert np.array_equal(s1.kq["codes"][:, :384], want[0]) and np.array_equal(s1.kq["scale"][:, :3], want[1])
+    assert np.array_equal(s1.kq["zero"][:, :3], want[2])
+    K = np.concatenate([s1.khat[:, :384], s0.khat[:, s0.first:s0.first + 16]], 1)
+    V = np.concatenate([s1.vhat[:, :384], s0.vhat[:, s0.first:s0.first + 16]], 1)
+    ref, ref_lse = brute_attention(hist[-1][0][0], K, V, c.scale)
+    assert np.max(np.abs(out[0] - ref)) < 1e-12 and np.max(np.abs(lse[0] - ref_lse)) < 1e-11
+    assert c.record_bytes(1) == 2 * 128 * (68 + 72)

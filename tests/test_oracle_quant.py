@@ -178,3 +178,91 @@ def test_requant_chain_equals_q2_when_q1_is_exact():
     direct = O.quant_i4(x)
     for a, b in zip(chain, direct):
         assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- Q2 over 128 tokens per channel (keys)
+
+def test_q2_tokens_exact_on_grid_and_nibble_order():
+    """x[t][j] = z_j + c[t][j] * 2^e_j with every channel containing codes 0 and 15: scale = 2^e_j, zero = z_j,
+    codes and round trip exact; channel 2i in the low nibble, 2i+1 in the high nibble of byte i of a token's row."""
+    rng = np.random.default_rng(21)
+    n, d = 256, 128
+    c = rng.integers(0, 16, (n, d))
+    for g in range(n // 128):
+        for j in range(d):
+            t = rng.choice(128, 2, replace=False) + g * 128
+            c[t[0], j], c[t[1], j] = 0, 15
+    e = rng.integers(-6, 4, d)
+    z = (rng.integers(-40, 40, d) * 0.25).astype(np.float32)
+    x = (z[None, :] + c * np.exp2(e)[None, :]).astype(np.float32)
+    packed, scale, zero = O.quant_i4_tokens(x)
+    assert packed.shape == (n, d // 2) and scale.shape == (n // 128, d) and zero.shape == (n // 128, d)
+    assert np.array_equal(O.f16_bits_to_f32(scale), np.broadcast_to(np.exp2(e).astype(np.float32), (2, d)))
+    assert np.array_equal(O.f16_bits_to_f32(zero), np.broadcast_to(z, (2, d)))
+    assert np.array_equal(packed & 0xf, c[:, 0::2]) and np.array_equal(packed >> 4, c[:, 1::2])
+    assert np.array_equal(O.dequant_i4_tokens(packed, scale, zero), x)
+
+
+def test_q2_tokens_is_q2_of_the_transposed_matrix():
+    """Independent of the function under test: the pinned per-token Q2 (group of 64 along the row) applied to the
+    transposed block.  If every channel attains its minimum and its maximum in both halves of the 128 tokens, the
+    two 64-groups of a transposed row have the scale and zero of the 128-group, so codes, scales and zeros agree."""
+    rng = np.random.default_rng(22)
+    d = 128
+    x = rng.standard_normal((128, d)).astype(np.float32) * np.exp2(rng.integers(-3, 3, d)).astype(np.float32)[None, :]
+    lo, hi = x.min(axis=0), x.max(axis=0)
+    for j in range(d):
+        for half in (0, 1):
+            t = rng.choice(64, 2, replace=False) + 64 * half
+            x[t[0], j], x[t[1], j] = lo[j], hi[j]
+    packed, scale, zero = O.quant_i4_tokens(x)
+    pt, st, zt = O.quant_i4(np.ascontiguousarray(x.T))          # rows = channels, columns = tokens
+    assert np.array_equal(st[:, 0], st[:, 1]) and np.array_equal(zt[:, 0], zt[:, 1])
+    assert np.array_equal(scale[0], st[:, 0]) and np.array_equal(zero[0], zt[:, 0])
+    codes = np.empty((128, d), np.uint8)
+    codes[:, 0::2], codes[:, 1::2] = packed & 0xf, packed >> 4
+    codes_t = np.empty((d, 128), np.uint8)
+    codes_t[:, 0::2], codes_t[:, 1::2] = pt & 0xf, pt >> 4
+    assert np.array_equal(codes, codes_t.T)
+    assert np.array_equal(O.dequant_i4_tokens(packed, scale, zero), O.dequant_i4(pt, st, zt).T)
+
+
+def test_q2_tokens_code_minimises_error_degenerate_and_bound():
+    rng = np.random.default_rng(23)
+    x = rng.standard_normal((384, 128)).astype(np.float32)
+    x[:, 5] *= 8.0                                     # an outlier channel
+    x[:128, 7] = 0.75                                  # constant over a group
+    x[128:256, 9] = 0.0                                # all zero over a group
+    x[:128, 11] = np.abs(x[:128, 11])
+    x[3, 11] = -0.0                                    # zero minimum with a sign
+    packed, scale, zero = O.quant_i4_tokens(x)
+    s = O.f16_bits_to_f32(scale).astype(np.float64)
+    z = O.f16_bits_to_f32(zero).astype(np.float64)
+    codes = np.empty(x.shape, np.int64)
+    codes[:, 0::2], codes[:, 1::2] = packed & 0xf, packed >> 4
+    S, Z = np.repeat(s, 128, axis=0), np.repeat(z, 128, axis=0)
+    err = np.abs(x - (codes * S + Z))
+    for c in range(16):
+        alt = np.abs(x - (c * S + Z))
+        assert np.all(err <= alt + 1e-7 * (1 + np.abs(x)))
+    assert scale[0, 7] == 0 and np.all(codes[:128, 7] == 0) and O.f16_bits_to_f32(zero)[0, 7] == 0.75
+    assert scale[1, 9] == 0 and zero[1, 9] == 0
+    assert zero[0, 11] == 0                            # +0, not 0x8000
+    xhat = O.dequant_i4_tokens(packed, scale, zero)
+    lo, hi = x.reshape(3, 128, 128).min(axis=1), x.reshape(3, 128, 128).max(axis=1)
+    bound = np.repeat(s / 2 + (np.abs(lo) + (hi - lo)) * 2.0 ** -10, 128, axis=0) + 1e-6
+    assert np.all(np.abs(x - xhat) <= bound)
+    # the outlier channel has its own groups: scaling it further changes nothing in any other channel
+    # (per-token groups of 64 channels: the 63 neighbours lose resolution)
+    x2 = x.copy()
+    x2[:, 5] *= 4.0
+    p2, s2, z2 = O.quant_i4_tokens(x2)
+    keep = np.arange(128) != 5
+    c2 = np.empty(x.shape, np.int64)
+    c2[:, 0::2], c2[:, 1::2] = p2 & 0xf, p2 >> 4
+    assert np.array_equal(c2[:, keep], codes[:, keep]) and np.array_equal(s2[:, keep], scale[:, keep])
+    assert np.array_equal(z2[:, keep], zero[:, keep])
+    others = [j for j in range(64) if j not in (5, 7, 9, 11)]
+    e_tok = np.abs(x[:, others] - O.dequant_i4(*O.quant_i4(x))[:, others]).mean()
+    e_tok2 = np.abs(x2[:, others] - O.dequant_i4(*O.quant_i4(x2))[:, others]).mean()
+    assert e_tok2 > 2.0 * e_tok > 2.0 * np.abs(x[:, others] - xhat[:, others]).mean()
