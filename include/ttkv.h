@@ -31,6 +31,9 @@
  *                    I8_SYM_G32: codes = 128 x int8, meta = 4 x fp16 scale
  *                    I4_ASYM_G64: codes = 64 B (element 2i low nibble, 2i+1 high
  *                                 nibble of byte i), meta = fp16 {s0, z0, s1, z1}
+ *                    I4_ASYM_T128 (K): codes as I4_ASYM_G64; km = 4: the meta rows of
+ *                                 tokens [128 g, 128 g + 128) of a block together hold
+ *                                 fp16 {scale, zero} x 128 channels of token group g
  *   Sequence b's token with lifetime ordinal o (o = start[b] + i for its i-th
  *   live token) sits in ring block r = (o / block_tokens) % ring_blocks at row
  *   o % block_tokens of record  block_table ? block_table[b*ring_blocks + r]
@@ -66,7 +69,13 @@ typedef enum {
   TTKV_BF16 = 1,
   TTKV_I8_SYM_G32 = 2,  /* Q_8bit: symmetric int8, group 32 along head_dim, fp16 scale */
   TTKV_I4_ASYM_G64 = 3, /* Q_4bit: asymmetric int4, group 64, fp16 scale + zero */
-  TTKV_F32 = 4          /* source format of ttkv_quantize_append only */
+  TTKV_F32 = 4,         /* source format of ttkv_quantize_append only */
+  TTKV_I4_ASYM_T128 = 5 /* keys only: asymmetric int4 where a group is one channel over 128 consecutive
+                           tokens (keys carry the larger dynamic range, Sec. 3 / 4.2, in a few channels:
+                           such a channel then sets no scale but its own).  V of the tier: I4_ASYM_G64.
+                           block_tokens a multiple of 128; tokens arrive in whole aligned groups (by
+                           eviction of whole blocks, or appends of multiples of 128); nothing passes
+                           THROUGH this format: it belongs to the last tier of a chain. */
 } ttkv_fmt;
 
 typedef enum { TTKV_MEM_DEVICE = 0, TTKV_MEM_HOST_PINNED = 1 } ttkv_mem;

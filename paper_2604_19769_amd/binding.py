@@ -13,9 +13,9 @@ TTKV_MAX_BATCH = 64
 TTKV_MAX_SLOTS = 16
 
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
-F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32 = range(5)
+F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32, I4_ASYM_T128 = range(6)
 MEM_DEVICE, MEM_HOST_PINNED = 0, 1
-FMT_NAMES = {"f16": F16, "bf16": BF16, "i8": I8_SYM_G32, "i4": I4_ASYM_G64, "f32": F32}
+FMT_NAMES = {"f16": F16, "bf16": BF16, "i8": I8_SYM_G32, "i4": I4_ASYM_G64, "f32": F32, "i4t": I4_ASYM_T128}
 
 
 class ttkv_tier(C.Structure):

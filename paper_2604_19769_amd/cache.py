@@ -13,7 +13,7 @@ from . import binding as B
 
 @dataclass
 class TierConfig:
-    k_fmt: str                 # 'f16' | 'bf16' | 'i8' | 'i4'
+    k_fmt: str                 # 'f16' | 'bf16' | 'i8' | 'i4' | 'i4t' (keys of the last tier: int4 grouped over 128 tokens per channel)
     v_fmt: str
     capacity: int              # eviction threshold in tokens (L_fast for tier 0)
     block_tokens: int          # B_blk
@@ -23,7 +23,7 @@ class TierConfig:
     summary: bool = False      # keep mean-key summaries (block identification)
 
 
-_SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 8)}
+_SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 8), "i4t": (64, 4)}
 
 
 class TieredCache:

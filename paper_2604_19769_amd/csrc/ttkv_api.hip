@@ -24,6 +24,13 @@ ttkv_status validate_cache(const ttkv_cache *c) {
     if (!attn_supported(T.k_fmt, T.v_fmt, c->n_q_heads / c->n_kv_heads)) return TTKV_ERR_UNSUPPORTED;
     if (T.mem != TTKV_MEM_DEVICE && T.mem != TTKV_MEM_HOST_PINNED) return TTKV_ERR_INVALID_ARG;
     if (T.block_tokens < 64 || T.block_tokens % 64) return TTKV_ERR_INVALID_ARG;
+    if (T.v_fmt == TTKV_I4_ASYM_T128) return TTKV_ERR_UNSUPPORTED;            // a key format
+    if (T.k_fmt == TTKV_I4_ASYM_T128) {
+      if (T.block_tokens % 128) return TTKV_ERR_INVALID_ARG;
+      if (t == 0 || t + 1 < c->n_tiers) return TTKV_ERR_UNSUPPORTED;          // whole groups arrive; nothing passes through
+      for (int b = 0; b < c->batch; ++b)
+        if (T.len[b] % 128) return TTKV_ERR_INVALID_ARG;
+    }
     if (T.ring_blocks < 1 || T.pool_blocks < 1 || !T.data || !T.start || !T.len) return TTKV_ERR_INVALID_ARG;
     if (T.ring_blocks * (int64_t)T.block_tokens >= (int64_t)1 << 30) return TTKV_ERR_INVALID_ARG;
     if (T.pool_blocks >= (int64_t)1 << 31) return TTKV_ERR_INVALID_ARG;
@@ -317,6 +324,7 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
   if ((T.mem == TTKV_MEM_HOST_PINNED) != host_variant) return TTKV_ERR_INVALID_ARG;
   if ((is_fp(T.k_fmt) && T.k_fmt != src_fmt) || (is_fp(T.v_fmt) && T.v_fmt != src_fmt)) return TTKV_ERR_UNSUPPORTED;
   if (n_tokens == 0) return TTKV_OK;
+  if (T.k_fmt == TTKV_I4_ASYM_T128 && n_tokens % 128) return TTKV_ERR_INVALID_ARG;   // whole token groups only
   const int b0 = seq < 0 ? 0 : seq, b1 = seq < 0 ? c->batch : seq + 1;
   for (int b = b0; b < b1; ++b)
     if (T.len[b] + n_tokens > ring_tokens(T)) return TTKV_ERR_CAPACITY;
@@ -541,6 +549,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   if (S.mem != TTKV_MEM_DEVICE) return TTKV_ERR_UNSUPPORTED;
   if (is_fp(D.k_fmt) && D.k_fmt != S.k_fmt) return TTKV_ERR_UNSUPPORTED;
   if (is_fp(D.v_fmt) && D.v_fmt != S.v_fmt) return TTKV_ERR_UNSUPPORTED;
+  if (D.k_fmt == TTKV_I4_ASYM_T128 && S.block_tokens % 128) return TTKV_ERR_UNSUPPORTED;   // whole token groups arrive
   hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
   const Layout LS = make_layout(S, c->n_kv_heads), LD = make_layout(D, c->n_kv_heads);
   const bool to_host = D.mem == TTKV_MEM_HOST_PINNED;

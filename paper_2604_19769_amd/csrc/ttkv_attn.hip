@@ -47,7 +47,8 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
   constexpr int NLV = TT / FV::TPL;        // V loads per lane per tile
   constexpr int R = FV::TPL / FK::TPL;     // K loads covered by one V load
   constexpr int QN = FK::EPL / 2;          // packed q registers per head
-  constexpr bool KQ = (KF == TTKV_I8_SYM_G32 || KF == TTKV_I4_ASYM_G64);
+  constexpr bool KT = KF == TTKV_I4_ASYM_T128;   // keys grouped over 128 tokens per channel: scale folds into q
+  constexpr bool KQ = (KF == TTKV_I8_SYM_G32 || KF == TTKV_I4_ASYM_G64 || KT);
   constexpr bool VQ = (VF == TTKV_I8_SYM_G32 || VF == TTKV_I4_ASYM_G64);
 
   const int lane = threadIdx.x & 63;
@@ -120,6 +121,7 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
   struct TileRegs {
     uint4 kw[NLK], vw[NLV];
     uint32_t kmeta[NLK], vmeta[NLV];
+    uint4 gm[KT ? 8 : 1];   // KT: {scale, zero} of the lane's 32 channels for the tile's token group
   };
 
   // Issue every load of the tile at i0.  FULL: every row is live (no clamping).
@@ -136,6 +138,11 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
     const uint8_t *kb = head + row0 * FK::ROWB, *kmb = head + tv.k_meta_off + row0 * 8;
     const uint8_t *vb = head + tv.v_off + row0 * FV::ROWB, *vmb = head + tv.v_meta_off + row0 * 8;
     constexpr uint32_t KMW = KF == TTKV_I8_SYM_G32 ? 2 : 4, VMW = VF == TTKV_I8_SYM_G32 ? 2 : 4;
+    if constexpr (KT) {   // a tile of 64 tokens lies inside one aligned group of 128: its 128 meta rows x 4 B
+      const uint4 *g = (const uint4 *)(head + tv.k_meta_off + (row0 & ~127) * 4 + kslice * 128);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t.gm[i] = g[i];
+    }
 #pragma unroll
     for (int n = 0; n < NLK; ++n) {
       const uint32_t r = FULL ? n * FK::TPL + ktok : min(n * FK::TPL + ktok, nv - 1);
@@ -167,6 +174,43 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
     const uint32_t *kmeta = t.kmeta, *vmeta = t.vmeta;
     (void)kmeta; (void)vmeta;
 
+    // ---- KT: q . k = sum_d (q_d s_d) (c_d - 8) + sum_d q_d (z_d + 8 s_d) with s, z of the tile's token group.
+    // q_d s_d (22 significant bits) is carried as two fp16 values, the rounded product and its exact remainder
+    // (one fused multiply-add), so the scores keep fp32 accuracy; the sums over q s and q z are exact products
+    // accumulated in fp32.
+    uint32_t qsh_[KT ? G : 1][KT ? QN : 1], qsl_[KT ? G : 1][KT ? QN : 1];
+    float qoff_t[KT ? G : 1];
+    if constexpr (KT) {
+      uint32_t sp2[QN], zp2[QN];
+#pragma unroll
+      for (int dd = 0; dd < 4; ++dd) {
+        const uint32_t m8[8] = {t.gm[2 * dd].x, t.gm[2 * dd].y, t.gm[2 * dd].z, t.gm[2 * dd].w,
+                                t.gm[2 * dd + 1].x, t.gm[2 * dd + 1].y, t.gm[2 * dd + 1].z, t.gm[2 * dd + 1].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {   // pair register 4 dd + j holds channels (8 dd + j, 8 dd + j + 4)
+          sp2[4 * dd + j] = __builtin_amdgcn_perm(m8[j + 4], m8[j], 0x05040100u);
+          zp2[4 * dd + j] = __builtin_amdgcn_perm(m8[j + 4], m8[j], 0x07060302u);
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float se = 0.0f, so = 0.0f, qz = 0.0f;   // sum q s over the registers with splice offset 1024 / 64, sum q z
+#pragma unroll
+        for (int r = 0; r < QN; ++r) {
+          const h2 q2 = as_h2(qp[g][r]), s2 = as_h2(sp2[r]);
+          const h2 hi = q2 * s2;
+          const h2 lo = __builtin_elementwise_fma(q2, s2, -hi);
+          qsh_[g][r] = __builtin_bit_cast(uint32_t, hi);
+          qsl_[g][r] = __builtin_bit_cast(uint32_t, lo);
+          if (r & 1) so = __builtin_amdgcn_fdot2(q2, s2, so, false);
+          else se = __builtin_amdgcn_fdot2(q2, s2, se, false);
+          qz = __builtin_amdgcn_fdot2(q2, as_h2(zp2[r]), qz, false);
+        }
+        // what leaves with the initial value: splice offsets 1024 / 64 plus the centre 8, minus the zero-point sum
+        qoff_t[g] = fmaf(1032.0f, se, 72.0f * so) - fmaf(8.0f, se + so, qz);
+      }
+    }
+
     // ---- scores (log2 domain)
     float s[G][NLK];
 #pragma unroll
@@ -181,15 +225,19 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
       }
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float d0 = KQ ? -qoff[g] : 0.0f, d1 = 0.0f;   // the splice offsets leave with the initial value
+        float d0 = KT ? -qoff_t[g] : (KQ ? -qoff[g] : 0.0f), d1 = 0.0f;   // the splice offsets leave with the initial value
 #pragma unroll
         for (int r = 0; r < QN; r += 2) {
           if constexpr (KF == TTKV_BF16) {
             d0 = __builtin_amdgcn_fdot2_f32_bf16(as_b2(kr[r]), as_b2(qp[g][r]), d0, false);
             d1 = __builtin_amdgcn_fdot2_f32_bf16(as_b2(kr[r + 1]), as_b2(qp[g][r + 1]), d1, false);
           } else {
-            d0 = __builtin_amdgcn_fdot2(as_h2(kr[r]), as_h2(qp[g][r]), d0, false);
-            d1 = __builtin_amdgcn_fdot2(as_h2(kr[r + 1]), as_h2(qp[g][r + 1]), d1, false);
+            d0 = __builtin_amdgcn_fdot2(as_h2(kr[r]), as_h2(KT ? qsh_[g][r] : qp[g][r]), d0, false);
+            d1 = __builtin_amdgcn_fdot2(as_h2(kr[r + 1]), as_h2(KT ? qsh_[g][r + 1] : qp[g][r + 1]), d1, false);
+            if constexpr (KT) {
+              d0 = __builtin_amdgcn_fdot2(as_h2(kr[r]), as_h2(qsl_[g][r]), d0, false);
+              d1 = __builtin_amdgcn_fdot2(as_h2(kr[r + 1]), as_h2(qsl_[g][r + 1]), d1, false);
+            }
           }
         }
         float d = (d0 + d1) * ks;
@@ -305,7 +353,10 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
   }
 }
 
-template <int G>
+// T128: the launch contains a tier whose keys are grouped over 128 tokens per channel.  That case holds 32 more
+// registers per tile (the group's scales and zeros), so it is compiled into an instantiation of its own and the
+// other formats keep their occupancy.
+template <int G, bool T128>
 __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
   __shared__ float s_acc[4][4][G][128];   // [wave][row of 16 lanes][head][channel]
   __shared__ float s_m[4][G], s_l[4][G];
@@ -348,6 +399,10 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
       break;
     case TTKV_I4_ASYM_G64 * 8 + TTKV_I4_ASYM_G64:
       process<TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      break;
+    case TTKV_I4_ASYM_T128 * 8 + TTKV_I4_ASYM_G64:
+      if constexpr (T128)
+        process<TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     default:
       process<TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
@@ -427,6 +482,7 @@ int attn_group_width(int Gtot) { return Gtot % 2 == 0 ? 2 : 1; }
 
 bool attn_supported(int k_fmt, int v_fmt, int G) {
   (void)G;
+  if (k_fmt == TTKV_I4_ASYM_T128 || v_fmt == TTKV_I4_ASYM_T128) return k_fmt == TTKV_I4_ASYM_T128 && v_fmt == TTKV_I4_ASYM_G64;
   if (k_fmt == v_fmt) return is_tier_fmt(k_fmt);
   return k_fmt == TTKV_I8_SYM_G32 && v_fmt == TTKV_I4_ASYM_G64;
 }
@@ -442,9 +498,14 @@ hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels, int *n
   const int G = attn_group_width(Gtot);
   const uint32_t bases = ((uint32_t)a.n_items * a.Hkv + 7) / 8 * 8;
   dim3 grid(bases * (Gtot / G));
-  switch (G) {
-    case 1: hipLaunchKernelGGL(attn_fused_kernel<1>, grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL(attn_fused_kernel<2>, grid, dim3(256), 0, s, a); break;
+  bool t128 = false;
+  for (int j = 0; j < a.n_entries; ++j) t128 |= a.tv[(a.e[j].tier_seq >> 16) & 0xff].k_fmt == TTKV_I4_ASYM_T128;
+  if (G == 1) {
+    if (t128) hipLaunchKernelGGL((attn_fused_kernel<1, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_fused_kernel<1, false>), grid, dim3(256), 0, s, a);
+  } else {
+    if (t128) hipLaunchKernelGGL((attn_fused_kernel<2, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_fused_kernel<2, false>), grid, dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }

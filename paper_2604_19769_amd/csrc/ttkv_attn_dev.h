@@ -19,6 +19,8 @@ template <> struct Fmt<TTKV_F16> { static constexpr int ROWB = 256, LPT = 16, TP
 template <> struct Fmt<TTKV_BF16> { static constexpr int ROWB = 256, LPT = 16, TPL = 4, EPL = 8; };
 template <> struct Fmt<TTKV_I8_SYM_G32> { static constexpr int ROWB = 128, LPT = 8, TPL = 8, EPL = 16; };
 template <> struct Fmt<TTKV_I4_ASYM_G64> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };
+template <> struct Fmt<TTKV_I4_ASYM_T128> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };   // rows as int4
+template <int F> constexpr bool is_i4() { return F == TTKV_I4_ASYM_G64 || F == TTKV_I4_ASYM_T128; }
 
 // Streaming loads: K/V bytes are read exactly once per launch, so they are fetched with the
 // non-temporal hint (no reuse expected).  On MI355X a load-only kernel moves 6.5-7.0 TB/s this way
@@ -46,16 +48,16 @@ __device__ __forceinline__ b2 as_b2(uint32_t u) { return __builtin_bit_cast(b2, 
 //   I4              : dword d = e/8, pairs (0,4) (1,5) (2,6) (3,7)     -> r = 4d + e%4, half = (e%8)/4
 template <int F>
 __device__ __forceinline__ constexpr int pair_reg(int e) {
-  return F == TTKV_I4_ASYM_G64 ? 4 * (e / 8) + (e % 4) : e / 2;
+  return is_i4<F>() ? 4 * (e / 8) + (e % 4) : e / 2;
 }
 template <int F>
 __device__ __forceinline__ constexpr int pair_half(int e) {
-  return F == TTKV_I4_ASYM_G64 ? (e % 8) / 4 : e % 2;
+  return is_i4<F>() ? (e % 8) / 4 : e % 2;
 }
 // Offset o_e that unpack16 leaves on element e.
 template <int F>
 __device__ __forceinline__ constexpr float elem_offset(int e) {
-  return F == TTKV_I4_ASYM_G64 ? ((e % 2) ? 64.0f : 1024.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
+  return is_i4<F>() ? ((e % 2) ? 64.0f : 1024.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
 }
 
 // Bit patterns used to splice int4 codes into fp16 mantissas.  They are kept in

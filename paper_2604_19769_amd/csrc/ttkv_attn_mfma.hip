@@ -452,6 +452,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // single pass pay off (from four query heads per KV head on, measured)?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
   if (G < 4 || G > 16) return false;
+  if (k_fmt == TTKV_I4_ASYM_T128) return false;   // keys grouped over tokens: vector kernel only
   if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8);
   if (k_fmt == TTKV_I8_SYM_G32) return G == 4;
   return true;

@@ -19,6 +19,7 @@ inline FmtBytes fmt_bytes(int fmt) {
     case TTKV_BF16: return {256, 0};
     case TTKV_I8_SYM_G32: return {128, 8};
     case TTKV_I4_ASYM_G64: return {64, 8};
+    case TTKV_I4_ASYM_T128: return {64, 4};   // 128 tokens x 4 B = 128 channels x fp16 {scale, zero}
     default: return {0, 0};
   }
 }
@@ -94,7 +95,7 @@ struct Handle {
   } while (0)
 
 inline bool is_fp(int f) { return f == TTKV_F16 || f == TTKV_BF16; }
-inline bool is_tier_fmt(int f) { return f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64; }
+inline bool is_tier_fmt(int f) { return (f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64) || f == TTKV_I4_ASYM_T128; }
 
 ttkv_status validate_cache(const ttkv_cache *c);
 
@@ -115,6 +116,7 @@ struct ConvArgs {
   int32_t seq_id[TTKV_MAX_BATCH];
   int32_t dst_first_tok[TTKV_MAX_BATCH];   // ring token index where the first row lands
   int32_t dst_rec_base[TTKV_MAX_BATCH];
+  int32_t which0;                          // first of {0: K, 1: V} the row kernel converts (1: V only)
   int32_t n_via;                           // intermediate formats a value passes through first
   int32_t via_k[TTKV_MAX_TIERS], via_v[TTKV_MAX_TIERS];
   // summaries of the destination tier (nullable)

@@ -191,7 +191,7 @@ __device__ __forceinline__ void store8_tier(uint8_t *head, int fmt, int code_off
 // One 16-lane group converts one row (one token of one KV head); blockIdx.y
 // picks K (0) or V (1).
 __global__ __launch_bounds__(256) void convert_rows_kernel(const ConvArgs a) {
-  const int which = blockIdx.y;
+  const int which = blockIdx.y + a.which0;
   const int l16 = threadIdx.x & 15;
   const int64_t total = (int64_t)a.n_seq * a.Hkv * a.n_tokens;
   int64_t row_id = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
@@ -223,6 +223,40 @@ __global__ __launch_bounds__(256) void convert_rows_kernel(const ConvArgs a) {
     store8_tier(head, a.dst.k_fmt, 0, a.dst.k_meta_off, row, l16, x, live);
 }
 
+// Key value of token t (of this call) of entry j, KV head h, channel i, as it arrives at the destination tier:
+// read from the flat source or from the source tier, then through the formats of the tiers in between.
+// Called by all 128 channel-threads of a head together (the round trips reduce over 32 / 64 lanes).
+__device__ __forceinline__ float arriving_key(const ConvArgs &a, int j, int seq, int h, int t, int i) {
+  float x[1];
+  if (!a.s.from_tier) {
+    int64_t row = ((int64_t)j * a.Hkv + h) * a.n_tokens + t;
+    if (a.s.flat_fmt == TTKV_F32)
+      x[0] = ((const float *)a.s.k_flat)[row * 128 + i];
+    else {
+      uint16_t w = ((const uint16_t *)a.s.k_flat)[row * 128 + i];
+      x[0] = a.s.flat_fmt == TTKV_F16 ? h2f(w) : bf2f(w);
+    }
+  } else {
+    int row;
+    const uint8_t *head = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
+    const int f = a.s.src.k_fmt;
+    if (f == TTKV_F16 || f == TTKV_BF16) {
+      uint16_t w = *(const uint16_t *)(head + row * 256 + i * 2);
+      x[0] = f == TTKV_F16 ? h2f(w) : bf2f(w);
+    } else if (f == TTKV_I8_SYM_G32) {
+      float s = h2f(*(const uint16_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 5) * 2));
+      x[0] = (float)(int)(int8_t)head[row * 128 + i] * s;
+    } else {
+      uint32_t sz = *(const uint32_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 6) * 4);
+      uint8_t byte = head[row * 64 + (i >> 1)];
+      float p = (float)(int)((i & 1) ? (byte >> 4) : (byte & 0xf)) * h2f((uint16_t)(sz & 0xffff));
+      x[0] = p + h2f((uint16_t)(sz >> 16));
+    }
+  }
+  for (int u = 0; u < a.n_via; ++u) roundtrip<1, 32, 64>(a.via_k[u], x);
+  return x[0];
+}
+
 // Running key sums per destination block, token order (one thread per channel,
 // one workgroup per sequence entry and KV head), and the fp16 mean key.
 __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
@@ -230,34 +264,7 @@ __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
   const int seq = a.seq_id[j];
   float sum = 0.0f;
   for (int t = 0; t < a.n_tokens; ++t) {
-    float x[1];
-    if (!a.s.from_tier) {
-      int64_t row = ((int64_t)j * a.Hkv + h) * a.n_tokens + t;
-      if (a.s.flat_fmt == TTKV_F32)
-        x[0] = ((const float *)a.s.k_flat)[row * 128 + i];
-      else {
-        uint16_t w = ((const uint16_t *)a.s.k_flat)[row * 128 + i];
-        x[0] = a.s.flat_fmt == TTKV_F16 ? h2f(w) : bf2f(w);
-      }
-    } else {
-      int row;
-      const uint8_t *head = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
-      const int f = a.s.src.k_fmt;
-      if (f == TTKV_F16 || f == TTKV_BF16) {
-        uint16_t w = *(const uint16_t *)(head + row * 256 + i * 2);
-        x[0] = f == TTKV_F16 ? h2f(w) : bf2f(w);
-      } else if (f == TTKV_I8_SYM_G32) {
-        float s = h2f(*(const uint16_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 5) * 2));
-        x[0] = (float)(int)(int8_t)head[row * 128 + i] * s;
-      } else {
-        uint32_t sz = *(const uint32_t *)(head + a.s.src.k_meta_off + row * 8 + (i >> 6) * 4);
-        uint8_t byte = head[row * 64 + (i >> 1)];
-        float p = (float)(int)((i & 1) ? (byte >> 4) : (byte & 0xf)) * h2f((uint16_t)(sz & 0xffff));
-        x[0] = p + h2f((uint16_t)(sz >> 16));
-      }
-    }
-    for (int u = 0; u < a.n_via; ++u) roundtrip<1, 32, 64>(a.via_k[u], x);
-
+    const float x = arriving_key(a, j, seq, h, t, i);
     const int tok = wrap(a.dst_first_tok[j] + t, a.dst);
     const int r = tok / a.dst.bt, row = tok - r * a.dst.bt;
     const int64_t rec = a.sum_table ? (int64_t)a.sum_table[(int64_t)seq * a.sum_ring_blocks + r] : (int64_t)a.sum_rec_base[j] + r;
@@ -266,11 +273,41 @@ __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
       sum = 0.0f;
     else if (t == 0)
       sum = a.k_sum[o];
-    sum = sum + x[0];
+    sum = sum + x;
     if (row == a.dst.bt - 1 || t == a.n_tokens - 1) {
       a.k_sum[o] = sum;
       a.k_summary[o] = f2h(sum * a.inv_bt);
     }
+  }
+}
+
+// Keys of a tier whose int4 groups run over 128 consecutive tokens of one channel (Q_4bit's arithmetic with the
+// group turned by 90 degrees): one workgroup per (token group, KV head, entry), thread = channel.  Two passes
+// over the group's 128 arriving rows: range, then codes; the two channels of a byte meet by a lane exchange.
+__global__ __launch_bounds__(128) void convert_keys_t128_kernel(const ConvArgs a) {
+  const int g = blockIdx.x, h = blockIdx.y, j = blockIdx.z, i = threadIdx.x;
+  const int seq = a.seq_id[j];
+  float lo = 0.0f, hi = 0.0f;
+  for (int t = 0; t < 128; ++t) {
+    const float x = arriving_key(a, j, seq, h, g * 128 + t, i);
+    lo = t ? fminf(lo, x) : x;
+    hi = t ? fmaxf(hi, x) : x;
+  }
+  if (lo == 0.0f) lo = 0.0f;  // a zero minimum is stored as +0 whatever its sign
+  const float s32 = (hi - lo) / 15.0f;
+  const uint16_t sh = f2h(s32), zh = f2h(lo);
+  const float s = h2f(sh), z = h2f(zh);
+  int row0;
+  uint8_t *head = head_ptr(a.dst, seq, a.dst_rec_base[j], wrap(a.dst_first_tok[j] + g * 128, a.dst), h, &row0);
+  // the group's 128 meta rows of 4 bytes hold {scale, zero} of the 128 channels
+  *(uint32_t *)(head + a.dst.k_meta_off + row0 * 4 + i * 4) = (uint32_t)sh | ((uint32_t)zh << 16);
+  for (int t = 0; t < 128; ++t) {
+    const float x = arriving_key(a, j, seq, h, g * 128 + t, i);
+    float q = 0.0f;
+    if (s != 0.0f) q = fminf(fmaxf(rintf((x - z) / s), 0.0f), 15.0f);
+    const int c = (int)q;
+    const int other = __shfl_xor(c, 1);
+    if (!(i & 1)) head[(row0 + t) * 64 + (i >> 1)] = (uint8_t)(c | (other << 4));
   }
 }
 
@@ -279,6 +316,15 @@ __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
 hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
   const int64_t total = (int64_t)a.n_seq * a.Hkv * a.n_tokens;
   if (total <= 0) return hipSuccess;
+  if (a.dst.k_fmt == TTKV_I4_ASYM_T128) {
+    // values row by row, keys by groups of 128 tokens per channel (the caller has checked alignment)
+    ConvArgs v = a;
+    v.which0 = 1;
+    hipLaunchKernelGGL(convert_rows_kernel, dim3((unsigned)((total + 15) / 16), 1), dim3(256), 0, s, v);
+    hipLaunchKernelGGL(convert_keys_t128_kernel, dim3(a.n_tokens / 128, a.Hkv, a.n_seq), dim3(128), 0, s, a);
+    *n_kernels += 2;
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((total + 15) / 16), 2);
   hipLaunchKernelGGL(convert_rows_kernel, grid, dim3(256), 0, s, a);
   ++*n_kernels;

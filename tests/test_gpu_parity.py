@@ -263,3 +263,45 @@ def test_capacity_error_leaves_state_untouched():
         assert e.value.status == B.ERR_CAPACITY and int(p.gpu.len[0][0]) == 64
     finally:
         p.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype,host", [(4, 4, "f16", False), (4, 2, "f16", False), (8, 2, "bf16", False), (4, 4, "f16", True)])
+def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host):
+    """Last tier with int4 keys that have one (scale, zero) per channel and 128 tokens (values int4 per token):
+    bulk load of whole groups, eviction of whole 128-token blocks, codes / scales / zeros bit-exact, outputs within
+    tolerance with outlier channels on the keys; one, two and four query heads per KV head; HBM and pinned host."""
+    tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=128, ring_blocks=3),
+             dict(k_fmt="i4t", v_fmt="i4", capacity=10**9, block_tokens=128 if not host else 256, ring_blocks=30,
+                  mem="host" if host else "device")]
+    p = Pair(2, Hq, Hkv, tiers, dtype)
+    try:
+        g = synth.rng(synth.SEED_BASE + 50 + Hq)
+        for b, n in enumerate((128 * 9 + 255, 128 * 20 + 130)):       # tier 0 takes the newest 255 / 130... rest whole groups
+            k, v = synth.kv((synth.SEED_BASE + 50) * 31 + b, Hkv, n, dtype)
+            k[:, :, 5::37] *= 8.0                                       # outlier channels
+            k = synth.round_to(k, dtype)
+            # the oracle's loader puts cap - 1 = 255 tokens into tier 0; the rest must be whole groups
+            n_old = n - 255
+            n_old -= n_old % 128
+            k, v = k[:, -(n_old + 255):], v[:, -(n_old + 255):]
+            p.load(b, k, v)
+        p.assert_state_equal()
+        worst = 0.0
+        for s in range(300):
+            q = synth.normal(g, (2, Hq, 128), dtype)
+            kn, vn = synth.normal(g, (2, Hkv, 128), dtype), synth.normal(g, (2, Hkv, 128), dtype)
+            kn[:, :, 5::37] *= 8.0
+            kn = synth.round_to(kn, dtype)
+            r = p.step(q, kn, vn)
+            assert_close(r[0], r[2], f"out step {s}")
+            assert_close(r[1], r[3], f"lse step {s}")
+            worst = max(worst, float(np.max(np.abs(r[0] - r[2]) / (2e-3 + 1e-2 * np.abs(r[2])))))
+            if s % 100 == 99:
+                p.assert_state_equal()
+        p.assert_state_equal()
+        print(f"worst error / tolerance: {worst:.3f}")
+        assert worst < 0.25        # the scaled queries are carried as fp16 hi + lo: as accurate as the other formats
+        st = p.gpu.stats()
+        assert st["demotions"] == sum(sum(d) for d in p.ora.demotions) >= 4 and st["mfma_launches"] == 0
+    finally:
+        p.close()

@@ -75,6 +75,13 @@ class Pair:
                     if fmt in ("f16", "bf16"):
                         want = synth.to_bits(hat[:, sl], fmt)
                         assert np.array_equal(d[name].view(np.uint16), want), (t, b, name, "fp bits")
+                    elif fmt == "i4t":      # 128 meta rows x 4 B of a token group = {scale, zero} x 128 channels
+                        assert s.first % 128 == 0 and s.count % 128 == 0
+                        assert np.array_equal(d[name], q["codes"][:, sl]), (t, b, name, "codes")
+                        meta = d[name + "_meta"].reshape(self.Hkv, s.count // 128, 128, 4).view(np.uint16)
+                        gsl = slice(s.first // 128, (s.first + s.count) // 128)
+                        assert np.array_equal(meta[..., 0], q["scale"][:, gsl]), (t, b, name, "scale")
+                        assert np.array_equal(meta[..., 1], q["zero"][:, gsl]), (t, b, name, "zero")
                     elif fmt == "i8":
                         assert np.array_equal(d[name], q["codes"][:, sl].view(np.uint8)), (t, b, name, "codes")
                         assert np.array_equal(d[name + "_meta"].view(np.uint16), q["scale"][:, sl]), (t, b, name, "scale")
