@@ -78,7 +78,7 @@ def timed_steps(cache, q, kn, vn, first, count, overlap=True, keep=None, sample_
 
 # ------------------------------------------------------------------ workload: MHA 32K, int4 in HBM
 
-def build_mha32k(steps_total, N=32768):
+def build_mha32k(steps_total, N=32768, slow_k="i4"):
     import numpy as np
     import torch
     from paper_2604_19769_amd import synth
@@ -88,7 +88,7 @@ def build_mha32k(steps_total, N=32768):
     gen = torch.Generator(device=dev)
     gen.manual_seed(SEED + 2)
     tiers = [TierConfig("f16", "f16", R, bt, R // bt + 1),
-             TierConfig("i4", "i4", 10**9, bt, (N - R) // bt + 2 + steps_total // bt + 1)]
+             TierConfig(slow_k, "i4", 10**9, bt, (N - R) // bt + 2 + steps_total // bt + 1)]
     cache = TieredCache(B, H, H, tiers)
     K = torch.randn((B, H, N - 1, 128), generator=gen, device=dev, dtype=torch.float32)
     V = torch.randn((B, H, N - 1, 128), generator=gen, device=dev, dtype=torch.float32)
@@ -110,7 +110,7 @@ def build_mha32k(steps_total, N=32768):
 
 def algorithmic_bytes(cache):
     """Stored bytes the step must read: codes + scales + zeros + fp K/V of every live token."""
-    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72}
+    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68}
     total, by_tier = 0, []
     for t, cfg in enumerate(cache.cfg):
         n = int(cache.len[t].sum()) * cache.Hkv * (per[cfg.k_fmt] + per[cfg.v_fmt])
@@ -469,6 +469,52 @@ def run_gqa_hbm(reps=12):
             "rows": rows}
 
 
+# ------------------------------------------------------------------ workload: int4 keys grouped over tokens
+
+def run_key_grouping(steps=12):
+    """The mha32k workload (keys with x8 on 2 % of the (head, channel) pairs) with the old tier's int4 keys grouped
+    per token over 64 channels, or per channel over 128 tokens: step time, attention launch rate and the
+    attention-output error of each against the same cache held entirely in fp16."""
+    import torch
+    from paper_2604_19769_amd import binding as B
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    rows, ref = [], None
+    for name, slow_k in (("fp16 everywhere (reference)", None), ("int4 keys, groups of 64 channels per token", "i4"),
+                         ("int4 keys, groups of 128 tokens per channel", "i4t")):
+        if slow_k is None:
+            cache, (K, V), (q, kn, vn), shape = build_mha32k(steps + 4)
+            cache.close()
+            cache = TieredCache(4, 32, 32, [TierConfig("f16", "f16", 10**9, 128, 32768 // 128 + 2)])
+            cache.append(0, K, V)
+        else:
+            cache, (K, V), (q, kn, vn), shape = build_mha32k(steps + 4, slow_k=slow_k)
+        try:
+            del K, V
+            out0 = cache.decode(q[0])[0].clone()
+            torch.cuda.synchronize()
+            if ref is None:
+                ref = out0
+            err = float((out0 - ref).abs().max() / ref.abs().max())
+            rms = float(((out0 - ref).pow(2).mean() / ref.pow(2).mean()).sqrt())
+            total, _ = algorithmic_bytes(cache)
+            if slow_k is None:
+                rows.append({"keys": name, "bytes_per_launch": int(total)})
+            else:
+                timed_steps(cache, q, kn, vn, 0, 3)
+                B.ttkv_read_attn_timing(cache.h)
+                secs = timed_steps(cache, q, kn, vn, 3, steps, sample_every=4)
+                ms = sorted(B.ttkv_read_attn_timing(cache.h))
+                us = ms[len(ms) // 2] * 1e3
+                rows.append({"keys": name, "bytes_per_launch": int(total), "us_per_step": round(secs / steps * 1e6, 1),
+                             "attn_launch_us": round(us, 1), "attn_GBs": round(total / us / 1e3, 1),
+                             "out_err_vs_fp16_rel_max": round(err, 5), "out_err_vs_fp16_rel_rms": round(rms, 5)})
+        finally:
+            cache.close()
+            torch.cuda.empty_cache()
+    return {"workload": "mha32k shapes and data (batch 4, 32 heads, 32768 tokens, recent 2048 fp16), the old tier's keys in two "
+                        "int4 groupings; error = attention output vs the all-fp16 cache", "rows": rows}
+
+
 # ------------------------------------------------------------------ workload: ablation variants (Sec. 5.4, Table 6)
 
 def run_ablation(steps, warmup):
@@ -629,6 +675,7 @@ def main():
         "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
         "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),
         "gqa_hbm": None if args.no_extra else run_gqa_hbm(),
+        "key_grouping": None if args.no_extra else run_key_grouping(),
     }
     print(json.dumps(line))
 
