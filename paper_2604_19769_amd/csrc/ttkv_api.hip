@@ -131,22 +131,19 @@ struct Plan {
 
 // Tokens per work item of tier t so that every item of the fused launch streams
 // about the same number of bytes: total bytes of the in-place tiers / target_items.
-int pick_chunk(const ttkv_cache *c, int t, bool staged, int target_items) {
-  const int G = c->n_q_heads / c->n_kv_heads;
-  const int n_hg = 1;   // the query-head groups of one KV head share its bytes (second reader hits L2)
-  (void)G;
-  int64_t total = 0;
+int pick_chunk(const ttkv_cache *c, int t, int target_items) {
+  auto per_token = [](const ttkv_tier &U) {
+    return (int64_t)fmt_bytes(U.k_fmt).code + fmt_bytes(U.k_fmt).meta + fmt_bytes(U.v_fmt).code + fmt_bytes(U.v_fmt).meta;
+  };
+  int64_t total = 0;   // bytes one pass over a KV head's tokens streams, all sequences and KV heads
   for (int u = 0; u < c->n_tiers; ++u) {
     const ttkv_tier &U = c->tier[u];
-    if (U.mem == TTKV_MEM_HOST_PINNED) continue;   // host tiers get fixed 256-token items
+    if (U.mem == TTKV_MEM_HOST_PINNED) continue;   // host tiers get fixed items
     int64_t tokens = 0;
     for (int b = 0; b < c->batch; ++b) tokens += U.len[b];
-    total += tokens * c->n_kv_heads * n_hg * (fmt_bytes(U.k_fmt).code + fmt_bytes(U.k_fmt).meta + fmt_bytes(U.v_fmt).code + fmt_bytes(U.v_fmt).meta);
+    total += tokens * c->n_kv_heads * per_token(U);
   }
-  (void)staged;
-  const ttkv_tier &T = c->tier[t];
-  const int64_t per_token = fmt_bytes(T.k_fmt).code + fmt_bytes(T.k_fmt).meta + fmt_bytes(T.v_fmt).code + fmt_bytes(T.v_fmt).meta;
-  int64_t want = total / std::max(1, target_items) / per_token;
+  int64_t want = total / std::max(1, target_items) / per_token(c->tier[t]);
   want = std::max<int64_t>(256, std::min<int64_t>(8192, want));
   return (int)((want + 63) / 64 * 64);
 }
@@ -166,7 +163,7 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const bool host = T.mem == TTKV_MEM_HOST_PINNED;
     // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured);
     // staged slots and selected blocks of a device tier: 256-token items for parallelism
-    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : pick_chunk(c, t, staged, target_items);
+    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : pick_chunk(c, t, target_items);
     const int chunk = P->chunk[t];
     if (!sparse && !(host && staged)) {
       for (int b = 0; b < c->batch; ++b) {

@@ -93,6 +93,23 @@ def test_invalid_arguments_are_status_codes():
     assert L.ttkv_quantize_append(h, C.byref(c), 3, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
     assert L.ttkv_quantize_append(h, C.byref(c), 0, 2, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
     assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 0, 0, None) == B.OK     # nothing to do
+    # keys grouped over tokens: a key format of the last tier only, whole groups of 128 tokens
+    c.tier[2].k_fmt = B.I4_ASYM_T128
+    assert L.ttkv_quantize_append_host is not None
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 100, 0, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 0, 0, None) == B.OK
+    c.tier[2].v_fmt = B.I8_SYM_G32
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 128, 0, None) == B.ERR_UNSUPPORTED   # V must be int4 g64
+    c.tier[2].v_fmt = B.I4_ASYM_T128
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 128, 0, None) == B.ERR_UNSUPPORTED   # not a value format
+    c.tier[2].k_fmt = c.tier[2].v_fmt = B.I4_ASYM_G64
+    c.tier[1].k_fmt, c.tier[1].v_fmt = B.I4_ASYM_T128, B.I4_ASYM_G64
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_UNSUPPORTED     # nothing passes through it
+    c.tier[1].k_fmt = c.tier[1].v_fmt = B.I8_SYM_G32
+    assert B.ttkv_record_bytes(c, 2) == 1024 * 2 * 144
+    c.tier[2].k_fmt = B.I4_ASYM_T128
+    assert B.ttkv_record_bytes(c, 2) == 1024 * 2 * 140          # 64 + 4 bytes of keys per token-head
+    c.tier[2].k_fmt = B.I4_ASYM_G64
     # nothing is due: demote is a no-op; src tier out of range
     assert L.ttkv_tier_demote(h, C.byref(c), 0, 0, None, 0, None, None) == B.OK
     assert L.ttkv_tier_demote(h, C.byref(c), 2, 0, None, 0, None, None) == B.ERR_INVALID_ARG

@@ -29,6 +29,16 @@ def q_rows(heads, G):
 
 def compare_codes(cache, ora, b, heads, fmts):
     for t, (kf, vf) in enumerate(fmts):
+        if kf == "i4t":                      # keys grouped over tokens: 128 meta rows x 4 B = {scale, zero} x 128 channels
+            d = cache.dump_tier(t, b)
+            s = ora.seq[t][0]
+            assert int(cache.len[t][b]) == s.count and int(cache.start[t][b]) == s.first and s.first % 128 == 0
+            sl, gsl = slice(s.first, s.first + s.count), slice(s.first // 128, (s.first + s.count) // 128)
+            assert np.array_equal(d["k"][heads], s.kq["codes"][:, sl])
+            meta = d["k_meta"][heads].reshape(len(heads), s.count // 128, 128, 4).view(np.uint16)
+            assert np.array_equal(meta[..., 0], s.kq["scale"][:, gsl]) and np.array_equal(meta[..., 1], s.kq["zero"][:, gsl])
+            assert np.array_equal(d["v"][heads], s.vq["codes"][:, sl])
+            continue
         d = cache.dump_tier(t, b)
         s = ora.seq[t][0]
         assert int(cache.len[t][b]) == s.count and int(cache.start[t][b]) == s.first, (t, b)
@@ -66,6 +76,30 @@ def test_mha32k_full_size_sampled_heads():
         assert cache.stats()["demotions"] == 4 and int(cache.len[0][b]) == shape["R"] - shape["bt"] + steps - 1
         # outputs of every row are finite and each lse exceeds that of the fp16 tier alone (more tokens, more mass)
         assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    finally:
+        cache.close()
+
+
+def test_mha32k_with_keys_grouped_over_tokens_full_size_sampled_heads():
+    """The same workload with the old tier's keys as int4 per channel over 128 tokens (values int4 per token)."""
+    steps = 3
+    cache, (K, V), (q, kn, vn), shape = bench.build_mha32k(steps, slow_k="i4t")
+    try:
+        b, heads = 1, [7, 18]
+        tiers = [TierSpec("f16", "f16", shape["R"], shape["bt"]), TierSpec("i4t", "i4", 10**9, shape["bt"])]
+        ora = sample_oracle(tiers, 32, 32, heads, K[b], V[b], [shape["R"] + 256, shape["N"] + 256])
+        compare_codes(cache, ora, b, heads, [("f16", "f16"), ("i4t", "i4")])
+        for s in range(steps):
+            out, lse = cache.step(q[s], kn[s], vn[s])
+            torch.cuda.synchronize()
+            ro, rl = ora.step(q[s, b][heads][None].float().cpu().numpy(), kn[s, b, heads, 0][None].float().cpu().numpy(),
+                              vn[s, b, heads, 0][None].float().cpu().numpy())
+            assert_close(out[b, heads].cpu().numpy(), ro[0], f"out step {s}")
+            assert_close(lse[b, heads].cpu().numpy(), rl[0], f"lse step {s}")
+            rel = np.max(np.abs(out[b, heads].cpu().numpy() - ro[0])) / np.max(np.abs(ro[0]))
+            assert rel < 2e-3, rel
+        compare_codes(cache, ora, b, heads, [("f16", "f16"), ("i4t", "i4")])
+        assert cache.stats()["demotions"] == 4 and torch.isfinite(out).all()
     finally:
         cache.close()
 
