@@ -257,13 +257,16 @@ __device__ __forceinline__ float arriving_key(const ConvArgs &a, int j, int seq,
   return x[0];
 }
 
-// Running key sums per destination block, token order (one thread per channel,
-// one workgroup per sequence entry and KV head), and the fp16 mean key.
+// Running key sums per destination block, token order, and the fp16 mean key: one thread per channel, one
+// workgroup per (sequence entry, KV head, destination block touched by this call).  A block that was partly
+// filled before continues from its stored sum.
 __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
-  const int j = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+  const int j = blockIdx.x, h = blockIdx.y, z = blockIdx.z, i = threadIdx.x;
   const int seq = a.seq_id[j];
+  const int r0 = a.dst_first_tok[j] % a.dst.bt;                 // row of the call's first token in its block
+  const int t_lo = max(0, z * a.dst.bt - r0), t_hi = min(a.n_tokens, (z + 1) * a.dst.bt - r0);
   float sum = 0.0f;
-  for (int t = 0; t < a.n_tokens; ++t) {
+  for (int t = t_lo; t < t_hi; ++t) {
     const float x = arriving_key(a, j, seq, h, t, i);
     const int tok = wrap(a.dst_first_tok[j] + t, a.dst);
     const int r = tok / a.dst.bt, row = tok - r * a.dst.bt;
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(128) void summary_kernel(const ConvArgs a) {
     const int64_t o = (rec * a.Hkv + h) * 128 + i;
     if (row == 0)
       sum = 0.0f;
-    else if (t == 0)
+    else if (t == t_lo)
       sum = a.k_sum[o];
     sum = sum + x;
     if (row == a.dst.bt - 1 || t == a.n_tokens - 1) {
@@ -335,7 +338,7 @@ hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
 // the kernel writes k_sum / k_summary, never dst.
 hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels) {
   if (a.n_seq <= 0 || a.n_tokens <= 0 || !a.k_sum) return hipSuccess;
-  hipLaunchKernelGGL(summary_kernel, dim3(a.n_seq, a.Hkv), dim3(128), 0, s, a);
+  hipLaunchKernelGGL(summary_kernel, dim3(a.n_seq, a.Hkv, a.n_tokens / a.dst.bt + 2), dim3(128), 0, s, a);
   ++*n_kernels;
   return hipGetLastError();
 }
