@@ -436,11 +436,11 @@ def run_gqa_hbm(reps=12):
     gen = torch.Generator(device=dev)
     gen.manual_seed(SEED + 7)
     rows = []
-    for fmt, N, dt in (("i8", 65536, torch.float16), ("i4", 131072, torch.float16), ("f16", 32768, torch.float16),
-                       ("bf16", 32768, torch.bfloat16)):
+    for fmt, N, dt in ((("i8", "i8"), 65536, torch.float16), (("i8", "i4"), 81920, torch.float16), (("i4", "i4"), 131072, torch.float16),
+                       (("f16", "f16"), 32768, torch.float16), (("bf16", "bf16"), 32768, torch.bfloat16)):
         fp = "f16" if dt == torch.float16 else "bf16"
-        tiers = [TierConfig(fp, fp, 10**9, 128, N // 128 + 2)] if fmt in ("f16", "bf16") else \
-                [TierConfig(fp, fp, 256, 128, 3), TierConfig(fmt, fmt, 10**9, 128, N // 128 + 2)]
+        tiers = [TierConfig(fp, fp, 10**9, 128, N // 128 + 2)] if fmt[0] in ("f16", "bf16") else \
+                [TierConfig(fp, fp, 256, 128, 3), TierConfig(fmt[0], fmt[1], 10**9, 128, N // 128 + 2)]
         cache = TieredCache(4, 32, 8, tiers)
         try:
             K, V = device_normal(gen, (4, 8, N, 128), dt), device_normal(gen, (4, 8, N, 128), dt)
@@ -458,7 +458,7 @@ def run_gqa_hbm(reps=12):
             ms = sorted(B.ttkv_read_attn_timing(cache.h))
             B.ttkv_time_attn(cache.h, 0)
             us = ms[len(ms) // 2] * 1e3
-            rows.append({"tier": f"{fmt} x {N} tokens", "bytes_per_launch": int(total), "kernel_us": round(us, 1),
+            rows.append({"tier": f"K {fmt[0]} / V {fmt[1]} x {N} tokens", "bytes_per_launch": int(total), "kernel_us": round(us, 1),
                          "GBs": round(total / us / 1e3, 1), "frac_of_hbm_peak": round(total / us / 1e3 / HBM_PEAK_GBS, 4),
                          "matrix_core_launches": cache.stats()["mfma_launches"] - s0["mfma_launches"]})
         finally:
