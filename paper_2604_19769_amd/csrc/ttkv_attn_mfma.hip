@@ -154,21 +154,31 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
         }
       }
     }
+    // Register r of the operand pairs with register r of unpack16: elements (2r, 2r+1) of the slice, or for int4
+    // (r = 4d + e) elements (8d + e, 8d + e + 4).  Both elements of a register lie in the same group.
+    float se = 0.0f, so = 0.0f;   // sums over the registers that carry splice offset 1024 / 64 (int4: even / odd)
+    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-    for (int r = 0; r < 16; ++r) qB[r] = 0;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int j = chan<KF>(s, i);
-        const bool on = col_on && slice_channel<KF>(kg, j) / (128 / NGK) == gam;
-        const uint32_t bits = on ? (qw[j / 2] >> (16 * (j % 2))) & 0xffffu : 0u;
-        qB[2 * s + i / 2] |= bits << (16 * (i % 2));
-        const float v = KBF ? __uint_as_float(bits << 16) : h2f((uint16_t)bits);
-        qs += v;
-        off = fmaf(v, k_offset<KF>(i), off);
+    for (int r = 0; r < 16; ++r) {
+      uint32_t w;
+      int j0;   // first element of the register
+      if constexpr (KF == TTKV_I4_ASYM_G64) {
+        const int dd = r / 4, e = r % 4;
+        j0 = 8 * dd + e;
+        w = __builtin_amdgcn_perm(qw[4 * dd + 2 + e / 2], qw[4 * dd + e / 2], (e & 1) ? 0x07060302u : 0x05040100u);
+      } else {
+        j0 = 2 * r;
+        w = qw[r];
+      }
+      const bool on = col_on && slice_channel<KF>(kg, j0) / (128 / NGK) == gam;
+      qB[r] = on ? w : 0u;
+      if constexpr (KQ) {   // quantized keys are dotted with fp16 queries
+        if ((r & 1) && KF == TTKV_I4_ASYM_G64) so = __builtin_amdgcn_fdot2(as_h2(qB[r]), ones, so, false);
+        else se = __builtin_amdgcn_fdot2(as_h2(qB[r]), ones, se, false);
       }
     }
+    qs = se + so;
+    off = KF == TTKV_I4_ASYM_G64 ? fmaf(1024.0f, se, 64.0f * so) : k_offset<KF>(0) * se;
     // the column's group is spread over the channel slices of several lanes; the others contributed zero
     off += __shfl_xor(off, 16); off += __shfl_xor(off, 32);
     qs += __shfl_xor(qs, 16);   qs += __shfl_xor(qs, 32);
