@@ -110,13 +110,14 @@ struct Fetch {
   int part_base;
   int chunk;
 };
-// Default split-K granularity: a whole number of rounds of resident workgroups (256 CUs x 4 per CU
-// for the vector kernel, x 3 for the grouped-query matrix-core kernel), measured best at 2.5 / 2 rounds.
+// Default split-K granularity, in workgroups resident at once on 256 CUs: 2.5 rounds of 4 per CU for the vector
+// kernel (flat between 1 and 3 rounds, measured), exactly one round of 3 per CU for the grouped-query matrix-core
+// kernel (int4: 5.1 TB/s against 4.4-4.7 with two rounds; the other formats are indifferent).
 int default_items(const ttkv_cache *c) {
   const int G = c->n_q_heads / c->n_kv_heads;
   for (int t = 0; t < c->n_tiers; ++t)
     if (!attn_mfma_fits(c->tier[t].k_fmt, c->tier[t].v_fmt, G)) return 2560;
-  return 1536;
+  return 768;
 }
 
 struct Plan {
