@@ -29,10 +29,11 @@
 //   the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32.  P is rounded to fp16 once and that
 //   rounded value is used for the row sum as well, so the normalisation is consistent.
 //
-// Column budget of the 16-wide tile: groups x heads <= 16 with the head count a power of
-// two where groups are summed by rotations: int4 (2 groups) serves 4 or 8 heads per KV
-// head, int8 (4 groups) 4, fp16 / bf16 any count from 4 to 16; the rest, and fewer than 4
-// heads (where the vector kernel is faster), stay on the vector kernel.
+// Column budget: (group, head) columns come 16 to a pass of the score product; one pass serves int4 keys
+// (2 groups) with 4 or 8 heads per KV head and int8 keys (4 groups) with 4, two passes (a second q operand and
+// selector, summed before the softmax) int8 keys with 8 heads and int4 keys with 16.  Head counts are powers of
+// two where groups are summed by rotations; fp16 / bf16 take any count from 4 to 16.  The rest, and fewer than
+// 4 heads (where the vector kernel is faster), stay on the vector kernel.
 #include "ttkv_attn_dev.h"
 
 #include <type_traits>
@@ -128,14 +129,22 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   const int ring_tokens = tv.ring_blocks * tv.bt;
   const float cs = a.scale * kLog2e;       // scores are kept in the log2 domain
 
+  // (group, head) columns: groups x heads of them, 16 per pass of the score product (NP = 2 when they exceed
+  // one tile: int8 keys with 8 heads, int4 keys with 16).  Column n of pass pp is group (16 pp + n) / G of head n % G.
+  constexpr int NP = KQ ? (NGK * GT + 15) / 16 : 1;
   const int g = n % G;                                   // head of this column
-  const int gam = KQ ? min(n / G, NGK - 1) : 0;          // K group of this column
-  const bool col_on = n < NGK * G;
+  int gam[NP];                                           // K group of this column, per pass
+  bool col_on[NP];
+#pragma unroll
+  for (int pp = 0; pp < NP; ++pp) {
+    gam[pp] = KQ ? min((16 * pp + n) / G, NGK - 1) : 0;
+    col_on[pp] = 16 * pp + n < NGK * G;
+  }
 
   // ---- q operand: 16 packed registers (step s: 2s, 2s+1), offset sum and plain sum of the column.  Element j
   // of the lane's slice enters only if its channel lies in the column's group.
-  uint32_t qB[16];
-  float off = 0.0f, qs = 0.0f;
+  uint32_t qB[NP][16];
+  float off[NP], qs[NP];
   {
     const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * G + g) * 128);
     uint32_t qw[16];
@@ -156,32 +165,35 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
     // Register r of the operand pairs with register r of unpack16: elements (2r, 2r+1) of the slice, or for int4
     // (r = 4d + e) elements (8d + e, 8d + e + 4).  Both elements of a register lie in the same group.
-    float se = 0.0f, so = 0.0f;   // sums over the registers that carry splice offset 1024 / 64 (int4: even / odd)
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      uint32_t w;
-      int j0;   // first element of the register
-      if constexpr (KF == TTKV_I4_ASYM_G64) {
-        const int dd = r / 4, e = r % 4;
-        j0 = 8 * dd + e;
-        w = __builtin_amdgcn_perm(qw[4 * dd + 2 + e / 2], qw[4 * dd + e / 2], (e & 1) ? 0x07060302u : 0x05040100u);
-      } else {
-        j0 = 2 * r;
-        w = qw[r];
+    for (int pp = 0; pp < NP; ++pp) {
+      float se = 0.0f, so = 0.0f;   // sums over the registers that carry splice offset 1024 / 64 (int4: even / odd)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        uint32_t w;
+        int j0;   // first element of the register
+        if constexpr (KF == TTKV_I4_ASYM_G64) {
+          const int dd = r / 4, e = r % 4;
+          j0 = 8 * dd + e;
+          w = __builtin_amdgcn_perm(qw[4 * dd + 2 + e / 2], qw[4 * dd + e / 2], (e & 1) ? 0x07060302u : 0x05040100u);
+        } else {
+          j0 = 2 * r;
+          w = qw[r];
+        }
+        const bool on = col_on[pp] && slice_channel<KF>(kg, j0) / (128 / NGK) == gam[pp];
+        qB[pp][r] = on ? w : 0u;
+        if constexpr (KQ) {   // quantized keys are dotted with fp16 queries
+          if ((r & 1) && KF == TTKV_I4_ASYM_G64) so = __builtin_amdgcn_fdot2(as_h2(qB[pp][r]), ones, so, false);
+          else se = __builtin_amdgcn_fdot2(as_h2(qB[pp][r]), ones, se, false);
+        }
       }
-      const bool on = col_on && slice_channel<KF>(kg, j0) / (128 / NGK) == gam;
-      qB[r] = on ? w : 0u;
-      if constexpr (KQ) {   // quantized keys are dotted with fp16 queries
-        if ((r & 1) && KF == TTKV_I4_ASYM_G64) so = __builtin_amdgcn_fdot2(as_h2(qB[r]), ones, so, false);
-        else se = __builtin_amdgcn_fdot2(as_h2(qB[r]), ones, se, false);
-      }
+      qs[pp] = se + so;
+      off[pp] = KF == TTKV_I4_ASYM_G64 ? fmaf(1024.0f, se, 64.0f * so) : k_offset<KF>(0) * se;
+      // the column's group is spread over the channel slices of several lanes; the others contributed zero
+      off[pp] += __shfl_xor(off[pp], 16); off[pp] += __shfl_xor(off[pp], 32);
+      qs[pp] += __shfl_xor(qs[pp], 16);   qs[pp] += __shfl_xor(qs[pp], 32);
     }
-    qs = se + so;
-    off = KF == TTKV_I4_ASYM_G64 ? fmaf(1024.0f, se, 64.0f * so) : k_offset<KF>(0) * se;
-    // the column's group is spread over the channel slices of several lanes; the others contributed zero
-    off += __shfl_xor(off, 16); off += __shfl_xor(off, 32);
-    qs += __shfl_xor(qs, 16);   qs += __shfl_xor(qs, 32);
   }
 
   // identity operand of the transposing product: k-value i of this lane is row 4 kg + i
@@ -191,14 +203,18 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   // Selection operands that bring a token's four fp16 meta values (scale, zero per group) into the
   // score layout: with the meta words as A operand, k-values 0..3 of the kg = 0 lanes, the product
   // with a 0/1 column selector is exactly the scale (or zero) of the column's group, per token.
-  uint32_t bs0 = 0, bs1 = 0, bz0 = 0, bz1 = 0;
-  if (KQ && kg == 0) {
-    const int ss = KF == TTKV_I4_ASYM_G64 ? 2 * gam : gam;
-    bs0 = ss == 0 ? 0x3C00u : (ss == 1 ? 0x3C000000u : 0u);
-    bs1 = ss == 2 ? 0x3C00u : (ss == 3 ? 0x3C000000u : 0u);
-    if (KF == TTKV_I4_ASYM_G64) {
-      bz0 = gam == 0 ? 0x3C000000u : 0u;
-      bz1 = gam == 1 ? 0x3C000000u : 0u;
+  uint32_t bs0[NP], bs1[NP], bz0[NP], bz1[NP];
+#pragma unroll
+  for (int pp = 0; pp < NP; ++pp) {
+    bs0[pp] = bs1[pp] = bz0[pp] = bz1[pp] = 0;
+    if (KQ && kg == 0) {
+      const int ss = KF == TTKV_I4_ASYM_G64 ? 2 * gam[pp] : gam[pp];
+      bs0[pp] = ss == 0 ? 0x3C00u : (ss == 1 ? 0x3C000000u : 0u);
+      bs1[pp] = ss == 2 ? 0x3C00u : (ss == 3 ? 0x3C000000u : 0u);
+      if (KF == TTKV_I4_ASYM_G64) {
+        bz0[pp] = gam[pp] == 0 ? 0x3C000000u : 0u;
+        bz1[pp] = gam[pp] == 1 ? 0x3C000000u : 0u;
+      }
     }
   }
   // byte selectors that duplicate the fp16 scale of the group of this lane's piece x out of the V meta words:
@@ -265,27 +281,36 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       uint32_t kr[16];
 #pragma unroll
       for (int x = 0; x < NLK; ++x) unpack16<KF>(t.kw[tt][x], kr + x * (16 / NLK), sp);
-      f4 sv = f4{-off, -off, -off, -off};
+      f4 sv[NP], ksv[NP], kzv[NP];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) sv = mma32<KBF>(kr + 4 * s, qB + 4 * s, sv);
-      f4 ksv = zero4, kzv = zero4;
-      if constexpr (KQ) ksv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bs0, bs1, zero4);
-      if constexpr (KF == TTKV_I4_ASYM_G64) kzv = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bz0, bz1, zero4);
+      for (int pp = 0; pp < NP; ++pp) {
+        sv[pp] = f4{-off[pp], -off[pp], -off[pp], -off[pp]};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sv[pp] = mma32<KBF>(kr + 4 * s, qB[pp] + 4 * s, sv[pp]);
+        ksv[pp] = kzv[pp] = zero4;
+        if constexpr (KQ) ksv[pp] = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bs0[pp], bs1[pp], zero4);
+        if constexpr (KF == TTKV_I4_ASYM_G64) kzv[pp] = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bz0[pp], bz1[pp], zero4);
+      }
+      f4 sc;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float x = sv[i];
-        if constexpr (KF == TTKV_I8_SYM_G32) x *= ksv[i];
-        if constexpr (KF == TTKV_I4_ASYM_G64) x = fmaf(kzv[i], qs, x * ksv[i]);
+        float x = 0.0f;
+#pragma unroll
+        for (int pp = 0; pp < NP; ++pp) {
+          if constexpr (KF == TTKV_I8_SYM_G32) x = fmaf(sv[pp][i], ksv[pp][i], x);
+          else if constexpr (KF == TTKV_I4_ASYM_G64) x += fmaf(kzv[pp][i], qs[pp], sv[pp][i] * ksv[pp][i]);
+          else x = sv[pp][i];
+        }
         if constexpr (KQ) {   // sum the groups of a head: cyclic over the columns with the same n % G
           if constexpr (GT <= 8) x += dpp<0x128>(x);
           if constexpr (GT <= 4) x += dpp<0x124>(x);
           if constexpr (GT <= 2) x += dpp<0x122>(x);
         }
         if (!FULL && tt * 16 + 4 * kg + i >= nv) x = -INFINITY;
-        sv[i] = x;
+        sc[i] = x;
         mt = fmaxf(mt, x);
       }
-      S[tt] = sv;
+      S[tt] = sc;
     }
 
     // ---- online softmax (base 2) per column; m is kept in raw score units, the scale enters the exponent
@@ -398,7 +423,12 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_mfma_kernel(const FusedArgs a) {
+// GQ: query heads per KV head the quantized-key cases are compiled for (4, 8 or 16; fp16 / bf16 tiers take any
+// count).  WIDE: the launch has a tier whose (group, head) columns need two passes of the score product (int8
+// keys with 8 heads, int4 keys with 16); those cases hold a second q operand, so they get instantiations of
+// their own and the one-pass cases keep their registers.
+template <int GQ, bool WIDE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 2 : 3, GQ == 16 ? 2 : 3))) void attn_mfma_kernel(const FusedArgs a) {
   __shared__ float s_acc[4][16][128];   // [wave][head][channel]
   __shared__ float s_m[4][16], s_l[4][16];
 
@@ -423,13 +453,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   switch (combo) {
     case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
     case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;
-    case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32: TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, 4); break;
-    case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64: TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, 4); break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32:
+      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, GQ);
+      break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64:
+      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, GQ);
+      break;
     default:
-      if (G == 4)
-        TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, 4);
-      else
-        TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, 8);
+      if constexpr (GQ <= 8 || WIDE) TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, GQ);
       break;
   }
 #undef TTKV_MFMA_CASE
@@ -460,13 +491,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 
 // Can one 16-column tile hold every (group, head) column of these formats, and does the
 // single pass pay off (from four query heads per KV head on, measured)?
+// Does the (group, head) column budget take these formats (one pass: groups x heads <= 16, two passes: <= 32;
+// head counts that the rotation sums handle), and does the single pass over the bytes pay off (from four query
+// heads per KV head on, measured)?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
   if (G < 4 || G > 16) return false;
   if (k_fmt == TTKV_I4_ASYM_T128) return false;   // keys grouped over tokens: vector kernel only
-  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8);
-  if (k_fmt == TTKV_I8_SYM_G32) return G == 4;
+  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8 || G == 16);
+  if (k_fmt == TTKV_I8_SYM_G32) return G == 4 || G == 8;
   return true;
 }
+
+namespace {
+bool needs_two_passes(int k_fmt, int G) {
+  return (k_fmt == TTKV_I8_SYM_G32 && G == 8) || (k_fmt == TTKV_I4_ASYM_G64 && G == 16);
+}
+}  // namespace
 
 bool attn_mfma_eligible(const FusedArgs &a) {
   const int G = a.Hq / a.Hkv;
@@ -478,7 +518,14 @@ bool attn_mfma_eligible(const FusedArgs &a) {
 }
 
 hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL(attn_mfma_kernel, dim3((uint32_t)a.n_items * a.Hkv), dim3(256), 0, s, a);
+  const int G = a.Hq / a.Hkv;
+  bool wide = false;
+  for (int j = 0; j < a.n_entries; ++j) wide |= needs_two_passes(a.tv[(a.e[j].tier_seq >> 16) & 0xff].k_fmt, G);
+  const dim3 grid((uint32_t)a.n_items * a.Hkv);
+  if (G == 16 && wide) hipLaunchKernelGGL((attn_mfma_kernel<16, true>), grid, dim3(256), 0, s, a);
+  else if (G == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true>), grid, dim3(256), 0, s, a);
+  else if (G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((attn_mfma_kernel<4, false>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
