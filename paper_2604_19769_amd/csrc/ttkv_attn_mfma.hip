@@ -85,7 +85,7 @@ constexpr int n_groups() {
 // the packed registers 2s and 2s+1 that unpack16 produced (int4 pairs are (0,4) (1,5) | (2,6) (3,7)).
 template <int F>
 constexpr int chan(int s, int i) {
-  if (F == TTKV_I4_ASYM_G64)
+  if (is_i4<F>())
     return 8 * (s / 2) + ((s % 2) ? (i < 2 ? 2 + 4 * i : 3 + 4 * (i - 2)) : (i < 2 ? 4 * i : 1 + 4 * (i - 2)));
   return 4 * s + i;
 }
@@ -95,14 +95,14 @@ constexpr int chan(int s, int i) {
 // of the lane's slice (j = 4 s + i in unpack order for fp16 / bf16 / int8) is therefore row channel:
 template <int F>
 __device__ __forceinline__ constexpr int slice_channel(int kg, int j) {
-  if (F == TTKV_I4_ASYM_G64) return 32 * kg + j;                          // one piece of 32 channels
+  if (is_i4<F>()) return 32 * kg + j;                                     // one piece of 32 channels
   if (F == TTKV_I8_SYM_G32) return 64 * (j / 16) + 16 * kg + j % 16;      // two pieces of 16
   return 32 * (j / 8) + 8 * kg + j % 8;                                   // four pieces of 8
 }
 // Splice offset carried by k-value i of a step.
 template <int F>
 constexpr float k_offset(int i) {
-  return F == TTKV_I4_ASYM_G64 ? (i < 2 ? 1024.0f : 64.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
+  return is_i4<F>() ? (i < 2 ? 1024.0f : 64.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
 }
 
 // GT: query heads per KV head as a compile-time constant (quantized K: the group sum below
@@ -119,6 +119,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
+  constexpr bool KT = KF == TTKV_I4_ASYM_T128;   // keys grouped over 128 tokens per channel: the scales fold into q
   constexpr bool KBF = KF == TTKV_BF16, VBF = VF == TTKV_BF16;
 
   const int lane = threadIdx.x & 63;
@@ -173,7 +174,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       for (int r = 0; r < 16; ++r) {
         uint32_t w;
         int j0;   // first element of the register
-        if constexpr (KF == TTKV_I4_ASYM_G64) {
+        if constexpr (is_i4<KF>()) {
           const int dd = r / 4, e = r % 4;
           j0 = 8 * dd + e;
           w = __builtin_amdgcn_perm(qw[4 * dd + 2 + e / 2], qw[4 * dd + e / 2], (e & 1) ? 0x07060302u : 0x05040100u);
@@ -241,6 +242,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   struct TileRegs {
     uint4 kw[NT][NLK], vw[NT][NLV];
     uint2 kmeta[NT], vmeta[NT];
+    uint4 gm[KT ? 8 : 1];   // KT: {scale, zero} of the lane's 32 channels for the token group of these tiles
   };
   const uint32_t kdoff = n * FK::ROWB + kg * 16, vdoff = n * FV::ROWB + kg * 16;
 
@@ -257,6 +259,11 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
     const uint8_t *kb = head + row0 * FK::ROWB, *kmb = head + tv.k_meta_off + row0 * 8;
     const uint8_t *vb = head + tv.v_off + row0 * FV::ROWB, *vmb = head + tv.v_meta_off + row0 * 8;
+    if constexpr (KT) {   // the 64 tokens in flight lie inside one aligned group of 128: its 128 meta rows x 4 B
+      const uint4 *gp = (const uint4 *)(head + tv.k_meta_off + (row0 & ~127) * 4 + kg * 128);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t.gm[i] = gp[i];
+    }
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
       const uint32_t row = FULL ? tt * 16 + n : min(tt * 16 + n, nv - 1);   // rows past the end re-read the last live row
@@ -273,6 +280,37 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 
   auto compute_tiles = [&](const TileRegs &t, int nv, auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
+    // ---- KT: q . k = sum_d (q_d s_d) (c_d - 8) + sum_d q_d (z_d + 8 s_d) with s, z of the token group.  q_d s_d
+    // is carried as two fp16 operands (rounded product and exact remainder), both multiplied with the codes;
+    // the sums over q s and q z are exact products accumulated in fp32 and leave with the initial value.
+    uint32_t qh[KT ? 16 : 1], ql[KT ? 16 : 1];
+    float off_t = 0.0f;
+    if constexpr (KT) {
+      float se = 0.0f, so = 0.0f, qz = 0.0f;
+#pragma unroll
+      for (int dd = 0; dd < 4; ++dd) {
+        const uint32_t m8[8] = {t.gm[2 * dd].x, t.gm[2 * dd].y, t.gm[2 * dd].z, t.gm[2 * dd].w,
+                                t.gm[2 * dd + 1].x, t.gm[2 * dd + 1].y, t.gm[2 * dd + 1].z, t.gm[2 * dd + 1].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {   // operand register 4 dd + j holds channels (8 dd + j, 8 dd + j + 4) of the slice
+          const int r = 4 * dd + j;
+          const h2 s2 = as_h2(__builtin_amdgcn_perm(m8[j + 4], m8[j], 0x05040100u));
+          const h2 z2 = as_h2(__builtin_amdgcn_perm(m8[j + 4], m8[j], 0x07060302u));
+          const h2 q2 = as_h2(qB[0][r]);
+          const h2 hi = q2 * s2;
+          qh[r] = __builtin_bit_cast(uint32_t, hi);
+          ql[r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(q2, s2, -hi));
+          if (r & 1) so = __builtin_amdgcn_fdot2(q2, s2, so, false);
+          else se = __builtin_amdgcn_fdot2(q2, s2, se, false);
+          qz = __builtin_amdgcn_fdot2(q2, z2, qz, false);
+        }
+      }
+      // splice offsets 1024 / 64 plus the centre 8, minus the zero-point sum; summed over the four channel slices
+      off_t = fmaf(1032.0f, se, 72.0f * so) - fmaf(8.0f, se + so, qz);
+      off_t += __shfl_xor(off_t, 16);
+      off_t += __shfl_xor(off_t, 32);
+    }
+
     // ---- scores (log2 domain), column n of tokens 4 kg + i
     f4 S[NT];
     float mt = -INFINITY;
@@ -284,9 +322,18 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       f4 sv[NP], ksv[NP], kzv[NP];
 #pragma unroll
       for (int pp = 0; pp < NP; ++pp) {
-        sv[pp] = f4{-off[pp], -off[pp], -off[pp], -off[pp]};
+        if constexpr (KT) {
+          sv[pp] = f4{-off_t, -off_t, -off_t, -off_t};
 #pragma unroll
-        for (int s = 0; s < 4; ++s) sv[pp] = mma32<KBF>(kr + 4 * s, qB[pp] + 4 * s, sv[pp]);
+          for (int s = 0; s < 4; ++s) {
+            sv[pp] = mma32<false>(kr + 4 * s, qh + 4 * s, sv[pp]);
+            sv[pp] = mma32<false>(kr + 4 * s, ql + 4 * s, sv[pp]);
+          }
+        } else {
+          sv[pp] = f4{-off[pp], -off[pp], -off[pp], -off[pp]};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) sv[pp] = mma32<KBF>(kr + 4 * s, qB[pp] + 4 * s, sv[pp]);
+        }
         ksv[pp] = kzv[pp] = zero4;
         if constexpr (KQ) ksv[pp] = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bs0[pp], bs1[pp], zero4);
         if constexpr (KF == TTKV_I4_ASYM_G64) kzv[pp] = mma<false>(t.kmeta[tt].x, t.kmeta[tt].y, bz0[pp], bz1[pp], zero4);
@@ -427,7 +474,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 // count).  WIDE: the launch has a tier whose (group, head) columns need two passes of the score product (int8
 // keys with 8 heads, int4 keys with 16); those cases hold a second q operand, so they get instantiations of
 // their own and the one-pass cases keep their registers.
-template <int GQ, bool WIDE>
+// T128: the launch has a tier whose keys are grouped over 128 tokens per channel (its own instantiations as well).
+template <int GQ, bool WIDE, bool T128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 2 : 3, GQ == 16 ? 2 : 3))) void attn_mfma_kernel(const FusedArgs a) {
   __shared__ float s_acc[4][16][128];   // [wave][head][channel]
   __shared__ float s_m[4][16], s_l[4][16];
@@ -458,6 +506,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
       break;
     case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64:
       if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, GQ);
+      break;
+    case TTKV_I4_ASYM_T128 * 8 + TTKV_I4_ASYM_G64:
+      if constexpr (T128) TTKV_MFMA_CASE(TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, 0);
       break;
     default:
       if constexpr (GQ <= 8 || WIDE) TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, GQ);
@@ -492,15 +543,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
 // Can one 16-column tile hold every (group, head) column of these formats, and does the
 // single pass pay off (from four query heads per KV head on, measured)?
 // Does the (group, head) column budget take these formats (one pass: groups x heads <= 16, two passes: <= 32;
-// head counts that the rotation sums handle), and does the single pass over the bytes pay off (from four query
-// heads per KV head on, measured)?
+// head counts that the rotation sums handle)?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
-  if (G < 4 || G > 16) return false;
-  if (k_fmt == TTKV_I4_ASYM_T128) return false;   // keys grouped over tokens: vector kernel only
+  if (G < 2 || G > 16) return false;
+  if (k_fmt == TTKV_I4_ASYM_T128) return true;    // no channel groups: one column per head
   if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8 || G == 16);
   if (k_fmt == TTKV_I8_SYM_G32) return G == 4 || G == 8;
   return true;
 }
+
+// Does the single pass over the bytes pay off?  From four query heads per KV head on (measured: with two the
+// vector kernel's head pair is as fast or faster); with keys grouped over tokens already from two (the vector
+// kernel's pair needs 238 registers there: 3.5 against 4.4 TB/s).
+bool attn_mfma_pays(int G, bool has_t128) { return G >= (has_t128 ? 2 : 4); }
 
 namespace {
 bool needs_two_passes(int k_fmt, int G) {
@@ -510,22 +565,31 @@ bool needs_two_passes(int k_fmt, int G) {
 
 bool attn_mfma_eligible(const FusedArgs &a) {
   const int G = a.Hq / a.Hkv;
+  bool wide = false, t128 = false;
   for (int j = 0; j < a.n_entries; ++j) {
     const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
     if (!attn_mfma_fits(tv.k_fmt, tv.v_fmt, G)) return false;
+    wide |= needs_two_passes(tv.k_fmt, G);
+    t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
   }
-  return true;
+  return attn_mfma_pays(G, t128) && !(wide && t128);   // wide with T128 has no instantiation: vector kernel
 }
 
 hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  bool wide = false;
-  for (int j = 0; j < a.n_entries; ++j) wide |= needs_two_passes(a.tv[(a.e[j].tier_seq >> 16) & 0xff].k_fmt, G);
+  bool wide = false, t128 = false;
+  for (int j = 0; j < a.n_entries; ++j) {
+    const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
+    wide |= needs_two_passes(tv.k_fmt, G);
+    t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
+  }
   const dim3 grid((uint32_t)a.n_items * a.Hkv);
-  if (G == 16 && wide) hipLaunchKernelGGL((attn_mfma_kernel<16, true>), grid, dim3(256), 0, s, a);
-  else if (G == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true>), grid, dim3(256), 0, s, a);
-  else if (G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((attn_mfma_kernel<4, false>), grid, dim3(256), 0, s, a);
+  if (t128 && G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, true>), grid, dim3(256), 0, s, a);
+  else if (t128) hipLaunchKernelGGL((attn_mfma_kernel<4, false, true>), grid, dim3(256), 0, s, a);
+  else if (G == 16 && wide) hipLaunchKernelGGL((attn_mfma_kernel<16, true, false>), grid, dim3(256), 0, s, a);
+  else if (G == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true, false>), grid, dim3(256), 0, s, a);
+  else if (G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, false>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((attn_mfma_kernel<4, false, false>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

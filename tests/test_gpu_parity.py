@@ -267,11 +267,13 @@ def test_capacity_error_leaves_state_untouched():
         p.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv,dtype,host", [(4, 4, "f16", False), (4, 2, "f16", False), (8, 2, "bf16", False), (4, 4, "f16", True)])
+@pytest.mark.parametrize("Hq,Hkv,dtype,host", [(4, 4, "f16", False), (4, 2, "f16", False), (8, 2, "bf16", False), (4, 4, "f16", True),
+                                               (16, 2, "f16", False), (10, 2, "f16", True)])
 def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host):
     """Last tier with int4 keys that have one (scale, zero) per channel and 128 tokens (values int4 per token):
     bulk load of whole groups, eviction of whole 128-token blocks, codes / scales / zeros bit-exact, outputs within
-    tolerance with outlier channels on the keys; one, two and four query heads per KV head; HBM and pinned host."""
+    tolerance with outlier channels on the keys; one query head per KV head on the vector kernel, two, four, five
+    and eight on the matrix-core kernel; HBM and pinned host."""
     tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=128, ring_blocks=3),
              dict(k_fmt="i4t", v_fmt="i4", capacity=10**9, block_tokens=128 if not host else 256, ring_blocks=30,
                   mem="host" if host else "device")]
@@ -302,8 +304,9 @@ def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host):
                 p.assert_state_equal()
         p.assert_state_equal()
         print(f"worst error / tolerance: {worst:.3f}")
-        assert worst < 0.25        # the scaled queries are carried as fp16 hi + lo: as accurate as the other formats
+        assert worst < (0.5 if Hq // Hkv >= 2 else 0.25)   # scaled queries as fp16 hi + lo: as accurate as the other formats of each kernel
         st = p.gpu.stats()
-        assert st["demotions"] == sum(sum(d) for d in p.ora.demotions) >= 4 and st["mfma_launches"] == 0
+        assert st["demotions"] == sum(sum(d) for d in p.ora.demotions) >= 4
+        assert (st["mfma_launches"] > 0) == (Hq // Hkv >= 2)
     finally:
         p.close()
