@@ -150,3 +150,29 @@ def test_locate_and_part_count_are_host_arithmetic():
     assert B.ttkv_count_parts(h, c) >= 3
     B.ttkv_destroy(h)
     assert B.ttkv_workspace_bytes(c, 8, 2) >= 1 * 8 * 8 * 130 * 4
+
+
+def golden_sizes():
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "tier_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, kf, vf, hkv, tokens, nbytes, _ = [x.strip() for x in line.split("|")]
+        rows.append((name, kf, vf, int(hkv), int(tokens), int(nbytes)))
+    return rows
+
+
+def test_sizes_of_the_layout_formula():
+    """Sec. 4.1's M = L x d_kv x b with the stored formats' byte widths, worked out by hand in
+    tests/golden/tier_sizes.txt: the library's record size and the oracle's agree with it."""
+    from oracle import OracleCache, TierSpec
+    rows = golden_sizes()
+    assert len(rows) >= 9
+    for name, kf, vf, hkv, tokens, nbytes in rows:
+        bt = 128 if tokens % 1024 else 1024
+        assert tokens % bt == 0
+        c = host_cache(batch=1, Hq=hkv, Hkv=hkv, fmts=((kf if kf != "i4t" else "f16", vf if kf != "i4t" else "f16"), (kf, vf)), bt=(128, bt))
+        assert B.ttkv_record_bytes(c, 1) * (tokens // bt) == nbytes, name
+        fp = "bf16" if kf == "bf16" else "f16"
+        ora = OracleCache(1, hkv, hkv, 128, [TierSpec(fp, fp, 128, 128), TierSpec(kf, vf, 10**9, bt)], [128, 128])
+        assert ora.record_bytes(1) * (tokens // bt) == nbytes, name
