@@ -267,17 +267,18 @@ def test_capacity_error_leaves_state_untouched():
         p.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv,dtype,host", [(4, 4, "f16", False), (4, 2, "f16", False), (8, 2, "bf16", False), (4, 4, "f16", True),
-                                               (16, 2, "f16", False), (10, 2, "f16", True)])
-def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host):
+@pytest.mark.parametrize("Hq,Hkv,dtype,host,n_slots", [(4, 4, "f16", False, 0), (4, 2, "f16", False, 0), (8, 2, "bf16", False, 0),
+                                                       (4, 4, "f16", True, 0), (16, 2, "f16", False, 0), (10, 2, "f16", True, 0),
+                                                       (4, 4, "f16", True, 2), (8, 2, "f16", True, 3)])
+def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host, n_slots):
     """Last tier with int4 keys that have one (scale, zero) per channel and 128 tokens (values int4 per token):
     bulk load of whole groups, eviction of whole 128-token blocks, codes / scales / zeros bit-exact, outputs within
     tolerance with outlier channels on the keys; one query head per KV head on the vector kernel, two, four, five
-    and eight on the matrix-core kernel; HBM and pinned host."""
+    and eight on the matrix-core kernel; HBM and pinned host (read in place and through staging slots)."""
     tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=128, ring_blocks=3),
              dict(k_fmt="i4t", v_fmt="i4", capacity=10**9, block_tokens=128 if not host else 256, ring_blocks=30,
                   mem="host" if host else "device")]
-    p = Pair(2, Hq, Hkv, tiers, dtype)
+    p = Pair(2, Hq, Hkv, tiers, dtype, n_slots=n_slots)
     try:
         g = synth.rng(synth.SEED_BASE + 50 + Hq)
         for b, n in enumerate((128 * 9 + 255, 128 * 20 + 130)):       # tier 0 takes the newest 255 / 130... rest whole groups
