@@ -26,17 +26,11 @@ __global__ __launch_bounds__(64) void score_kernel(const SelectArgs a) {
   const int G = a.Hq / a.Hkv;
   float s = 0.0f;
   for (int h = 0; h < a.Hq; ++h) {
-    const uint4 *m8 = (const uint4 *)(mu + (h / G) * 128), *q8 = (const uint4 *)(q + h * 128);
-#pragma unroll 2
-    for (int c8 = 0; c8 < 16; ++c8) {   // eight channels per 128-bit load; the additions keep channel order
-      const uint4 qw = q8[c8], mw = m8[c8];
-      const uint32_t qu[4] = {qw.x, qw.y, qw.z, qw.w}, mv[4] = {mw.x, mw.y, mw.z, mw.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint16_t qb = (uint16_t)(qu[e / 2] >> (16 * (e % 2))), mb = (uint16_t)(mv[e / 2] >> (16 * (e % 2)));
-        const float qv = a.q_fmt == TTKV_F16 ? h2f(qb) : __uint_as_float((uint32_t)qb << 16);
-        s = __fmaf_rn(qv, h2f(mb), s);
-      }
+    const uint16_t *m = mu + (h / G) * 128;
+    for (int ch = 0; ch < 128; ++ch) {
+      const uint16_t qb = q[h * 128 + ch];
+      const float qv = a.q_fmt == TTKV_F16 ? h2f(qb) : __uint_as_float((uint32_t)qb << 16);
+      s = __fmaf_rn(qv, h2f(m[ch]), s);
     }
   }
   a.scores[(int64_t)b * a.max_blocks + i] = s;
