@@ -6,9 +6,9 @@
 // kernel; only the lane mapping differs.
 //
 // One 16-token tile, lane = (c = lane % 16, kg = lane / 16):
-//   K rows are loaded in the MFMA A layout: lane (c, kg) holds channels [32 kg, 32 kg + 32)
-//   of token c (16 B int4, 32 B int8, 64 B fp16/bf16), spliced into packed 16-bit pairs as
-//   in the vector kernel.  Eight steps of 16 channels each give
+//   K rows are loaded in the MFMA A layout: lane (c, kg) holds 32 channels of token c, the 16-byte
+//   pieces kg, kg + 4, ... of the row (one piece for int4, two for int8, four for fp16 / bf16), spliced
+//   into packed 16-bit pairs as in the vector kernel.  Four 32-deep steps give
 //       S[token][column] = sum_d K[token][d] * Q[d][column]
 //   where a column is (quantization group, query head): the q operand is zero outside the
 //   column's group, so every column is a per-group dot product.  The splice offsets leave
@@ -17,23 +17,29 @@
 //   group) reach that layout by one more product: meta words as A operand against a 0/1
 //   selector of the column's group, which is exact.  The groups of one head are then summed
 //   by DPP row rotations, which also leaves every column with its head's score.
-//   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg).
+//   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg); its scale
+//   is applied inside the exponent.
 //   V rows are loaded like K rows and dequantized in packed fp16 while the lane still owns
 //   one token and one group: (o + n) * s - o * s in one fused multiply-add (o a power of two),
-//   i.e. code x scale rounded once, to nearest even.  A product with the identity matrix brings the tile
-//   from [token][channel] to [channel][token]: the fp32 result (exact) has lane (c, kg)
+//   i.e. code x scale rounded once, to nearest even.  A product with the identity matrix brings
+//   the tile from [token][channel] to [channel][token]: the fp32 result (exact) has lane (c, kg)
 //   holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
 //       O[channel][column] += sum_token V^T[channel][token] * P[token][column].
 //   Two 16-token tiles feed one 32-deep product.  The int4 zero points, and the 128 that the
 //   int8 splice leaves on every code, ride along as a 4-channel V (the meta words transposed
-//   the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32.  P is rounded to fp16 once and that
-//   rounded value is used for the row sum as well, so the normalisation is consistent.
+//   the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32.  P is rounded to
+//   fp16 once and that rounded value is used for the row sum as well, so the normalisation is
+//   consistent.
+//   Keys grouped over 128 tokens per channel have no channel groups (one column per head); the token
+//   group's scales fold into the q operand, carried as fp16 rounded product + exact remainder
+//   (two products per step), rebuilt for every 64 tokens in flight.
 //
 // Column budget: (group, head) columns come 16 to a pass of the score product; one pass serves int4 keys
 // (2 groups) with 4 or 8 heads per KV head and int8 keys (4 groups) with 4, two passes (a second q operand and
 // selector, summed before the softmax) int8 keys with 8 heads and int4 keys with 16.  Head counts are powers of
-// two where groups are summed by rotations; fp16 / bf16 take any count from 4 to 16.  The rest, and fewer than
-// 4 heads (where the vector kernel is faster), stay on the vector kernel.
+// two where groups are summed by rotations; fp16 / bf16 and keys grouped over tokens take any count up to 16.
+// The rest stays on the vector kernel, as do fewer than 4 heads per KV head (2 with keys grouped over tokens),
+// where the vector kernel is as fast or faster.
 #include "ttkv_attn_dev.h"
 
 #include <type_traits>
