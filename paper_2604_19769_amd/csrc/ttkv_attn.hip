@@ -2,8 +2,10 @@
 // the fast tier, Decompress + Attn per slow-tier block) and the log-sum-exp merge
 // of the partials (the "+" of Alg. 1, normalised once at the end).
 //
-// Work item = (tier, sequence, chunk of tokens, KV head[, query-head group]); one
+// Work item = (tier, sequence, chunk of tokens, KV head[, pair of query heads]); one
 // workgroup of four wave64 per item, each wave streaming 1/4 of the chunk's tiles.
+// This is the kernel for one or two query heads per KV head; launches with four or
+// more go to the matrix-core kernel where its tile takes the formats.
 //
 // Lane mapping: a K or V row of one token-head is ROWB bytes = LPT lanes x 16 B, so
 // one 128-bit load per lane brings TPL = 64/LPT whole rows per wave, fully
@@ -19,7 +21,10 @@
 //   sum_t p_t v_t = sum_t (p_t s_t)(c_t + o) - o * sum_t p_t s_t + sum_t p_t z_t
 // Accumulation is fp32 throughout.  Query values are held as fp16 for the fp16 and
 // quantized tiers (bf16 queries are converted; |q| must stay below 65504) and as
-// bf16 pairs for the bf16 tier.
+// bf16 pairs for the bf16 tier.  Keys grouped over 128 tokens per channel fold the
+// token group's scales into the queries per tile (see process).
+//
+// K/V bytes are read once per launch: the tile loads carry the non-temporal hint.
 //
 // The host tier needs no separate path: pinned host memory is read by the same
 // loads (PCIe reads in flight while other waves compute), or from a staging slot
