@@ -115,14 +115,15 @@ struct Fetch {
 // kernel (int4: 5.1 TB/s against 4.4-4.7 with two rounds; the other formats are indifferent).
 int default_items(const ttkv_cache *c) {
   const int G = c->n_q_heads / c->n_kv_heads;
-  bool t128 = false;
+  bool special = false;   // K 8-bit / V 4-bit or keys grouped over tokens: matrix-core kernel already from two heads
   for (int t = 0; t < c->n_tiers; ++t) {
-    if (!attn_mfma_fits(c->tier[t].k_fmt, c->tier[t].v_fmt, G)) return 2560;
-    t128 |= c->tier[t].k_fmt == TTKV_I4_ASYM_T128;
+    const ttkv_tier &T = c->tier[t];
+    if (!attn_mfma_fits(T.k_fmt, T.v_fmt, G)) return 2560;
+    special |= T.k_fmt == TTKV_I4_ASYM_T128 || (T.k_fmt == TTKV_I8_SYM_G32 && T.v_fmt == TTKV_I4_ASYM_G64);
   }
-  if (!attn_mfma_pays(G, t128)) return 2560;
+  if (!attn_mfma_pays(G, special)) return 2560;
   for (int t = 0; t < c->n_tiers; ++t)
-    if (G == 16 && c->tier[t].k_fmt == TTKV_I4_ASYM_G64) return 512;   // that case runs 2 workgroups per CU
+    if (G > 8 && c->tier[t].k_fmt == TTKV_I4_ASYM_G64) return 512;   // that case runs 2 workgroups per CU
   return 768;
 }
 

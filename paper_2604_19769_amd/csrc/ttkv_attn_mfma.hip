@@ -34,12 +34,12 @@
 //   group's scales fold into the q operand, carried as fp16 rounded product + exact remainder
 //   (two products per step), rebuilt for every 64 tokens in flight.
 //
-// Column budget: (group, head) columns come 16 to a pass of the score product; one pass serves int4 keys
-// (2 groups) with 4 or 8 heads per KV head and int8 keys (4 groups) with 4, two passes (a second q operand and
-// selector, summed before the softmax) int8 keys with 8 heads and int4 keys with 16.  Head counts are powers of
-// two where groups are summed by rotations; fp16 / bf16 and keys grouped over tokens take any count up to 16.
-// The rest stays on the vector kernel, as do fewer than 4 heads per KV head (2 with keys grouped over tokens),
-// where the vector kernel is as fast or faster.
+// Column budget: (group, head) columns come 16 to a pass of the score product, heads padded to 4, 8 or 16 where
+// the keys have channel groups (idle columns cost nothing).  One pass serves int4 keys (2 groups) with up to 8
+// heads per KV head and int8 keys (4 groups) with up to 4; two passes (a second q operand and selector, summed
+// before the softmax) int8 keys with up to 8 heads and int4 keys with up to 16.  fp16 / bf16 and keys grouped
+// over tokens take any count up to 16.  Launches outside this budget, and those where the vector kernel is as
+// fast or faster (two heads per KV head of one format), stay on the vector kernel.
 #include "ttkv_attn_dev.h"
 
 #include <type_traits>
@@ -111,13 +111,15 @@ constexpr float k_offset(int i) {
   return is_i4<F>() ? (i < 2 ? 1024.0f : 64.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
 }
 
-// GT: query heads per KV head as a compile-time constant (quantized K: the group sum below
-// depends on it), or 0 to take it from the arguments (fp16 / bf16, any count up to 16).
+// GT: query heads per KV head, padded to 4, 8 or 16, as a compile-time constant (quantized K: the column layout
+// and the group sum below depend on it; columns of heads beyond the real count stay zero), or 0 to take the real
+// count from the arguments (fp16 / bf16 / keys grouped over tokens: any count up to 16).
 template <int KF, int VF, int GT>
 __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
                                              int chunk, int seq, int hkv, float (*s_acc)[16][128],
                                              float (*s_m)[16], float (*s_l)[16]) {
-  const int G = GT ? GT : a.Hq / a.Hkv;
+  const int Gr = a.Hq / a.Hkv;             // real heads per KV head
+  const int G = GT ? GT : Gr;              // heads per group block of columns
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
@@ -145,7 +147,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 #pragma unroll
   for (int pp = 0; pp < NP; ++pp) {
     gam[pp] = KQ ? min((16 * pp + n) / G, NGK - 1) : 0;
-    col_on[pp] = 16 * pp + n < NGK * G;
+    col_on[pp] = 16 * pp + n < NGK * G && g < Gr;
   }
 
   // ---- q operand: 16 packed registers (step s: 2s, 2s+1), offset sum and plain sum of the column.  Element j
@@ -153,7 +155,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   uint32_t qB[NP][16];
   float off[NP], qs[NP];
   {
-    const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * G + g) * 128);
+    const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * Gr + min(g, Gr - 1)) * 128);
     uint32_t qw[16];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {     // 8 channels per 16-byte load
@@ -464,7 +466,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     z[0] = -128.0f * ((kg >> 1) ? accz[1] : accz[0]);
     z[1] = -128.0f * ((kg >> 1) ? accz[3] : accz[2]);
   }
-  if (n < G) {
+  if (n < Gr) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
@@ -548,53 +550,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
 
 // Can one 16-column tile hold every (group, head) column of these formats, and does the
 // single pass pay off (from four query heads per KV head on, measured)?
-// Does the (group, head) column budget take these formats (one pass: groups x heads <= 16, two passes: <= 32;
-// head counts that the rotation sums handle)?
+// Does the (group, head) column budget take these formats?  Head counts are padded to 4, 8 or 16 (idle columns
+// cost nothing); one pass holds groups x heads <= 16 columns, two passes <= 32.
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
   if (G < 2 || G > 16) return false;
   if (k_fmt == TTKV_I4_ASYM_T128) return true;    // no channel groups: one column per head
-  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt && (G == 4 || G == 8 || G == 16);
-  if (k_fmt == TTKV_I8_SYM_G32) return G == 4 || G == 8;
+  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt;            // 2 groups x 16 heads at most
+  if (k_fmt == TTKV_I8_SYM_G32) return G <= 8;                     // 4 groups x 8 heads at most
   return true;
 }
 
-// Does the single pass over the bytes pay off?  From four query heads per KV head on (measured: with two the
-// vector kernel's head pair is as fast or faster); with keys grouped over tokens already from two (the vector
-// kernel's pair needs 238 registers there: 3.5 against 4.4 TB/s).
-bool attn_mfma_pays(int G, bool has_t128) { return G >= (has_t128 ? 2 : 4); }
+// Does the single pass over the bytes pay off?  From three query heads per KV head on (measured: with two, the
+// vector kernel's head pair is as fast or faster: fp16 6.3 against 5.4 TB/s, int8 and int4 about equal).  With
+// two heads only for K 8-bit / V 4-bit (4.3 against 5.0 TB/s) and keys grouped over tokens (3.5 against 4.4),
+// whose head pair is short of registers on the vector kernel.
+bool attn_mfma_pays(int G, bool has_mixed_or_t128) { return G >= (has_mixed_or_t128 ? 2 : 3); }
 
 namespace {
+int padded_heads(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
 bool needs_two_passes(int k_fmt, int G) {
-  return (k_fmt == TTKV_I8_SYM_G32 && G == 8) || (k_fmt == TTKV_I4_ASYM_G64 && G == 16);
+  return (k_fmt == TTKV_I8_SYM_G32 && padded_heads(G) == 8) || (k_fmt == TTKV_I4_ASYM_G64 && padded_heads(G) == 16);
 }
+bool quantized_per_token(int k_fmt) { return k_fmt == TTKV_I8_SYM_G32 || k_fmt == TTKV_I4_ASYM_G64; }
 }  // namespace
 
 bool attn_mfma_eligible(const FusedArgs &a) {
   const int G = a.Hq / a.Hkv;
-  bool wide = false, t128 = false;
+  bool wide = false, t128 = false, mixed = false;
   for (int j = 0; j < a.n_entries; ++j) {
     const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
     if (!attn_mfma_fits(tv.k_fmt, tv.v_fmt, G)) return false;
     wide |= needs_two_passes(tv.k_fmt, G);
     t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
+    mixed |= tv.k_fmt == TTKV_I8_SYM_G32 && tv.v_fmt == TTKV_I4_ASYM_G64;
   }
-  return attn_mfma_pays(G, t128) && !(wide && t128);   // wide with T128 has no instantiation: vector kernel
+  return attn_mfma_pays(G, t128 || mixed) && !(wide && t128);   // wide with T128 has no instantiation: vector kernel
 }
 
 hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  bool wide = false, t128 = false;
+  bool wide = false, t128 = false, quant = false;
   for (int j = 0; j < a.n_entries; ++j) {
     const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
     wide |= needs_two_passes(tv.k_fmt, G);
     t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
+    quant |= quantized_per_token(tv.k_fmt);
   }
+  const int GP = quant ? padded_heads(G) : 4;   // only the per-token quantized key cases depend on the padded count
   const dim3 grid((uint32_t)a.n_items * a.Hkv);
-  if (t128 && G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, true>), grid, dim3(256), 0, s, a);
+  if (t128 && GP == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, true>), grid, dim3(256), 0, s, a);
   else if (t128) hipLaunchKernelGGL((attn_mfma_kernel<4, false, true>), grid, dim3(256), 0, s, a);
-  else if (G == 16 && wide) hipLaunchKernelGGL((attn_mfma_kernel<16, true, false>), grid, dim3(256), 0, s, a);
-  else if (G == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true, false>), grid, dim3(256), 0, s, a);
-  else if (G == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, false>), grid, dim3(256), 0, s, a);
+  else if (GP == 16) hipLaunchKernelGGL((attn_mfma_kernel<16, true, false>), grid, dim3(256), 0, s, a);
+  else if (GP == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true, false>), grid, dim3(256), 0, s, a);
+  else if (GP == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, false>), grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL((attn_mfma_kernel<4, false, false>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }

@@ -158,7 +158,7 @@ bool attn_supported(int k_fmt, int v_fmt, int G);
 int attn_group_width(int Gtot);
 // Grouped-query kernel on the matrix cores: all query heads of a KV head in one pass over its bytes.
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G);
-bool attn_mfma_pays(int G, bool has_t128);
+bool attn_mfma_pays(int G, bool has_mixed_or_t128);
 bool attn_mfma_eligible(const FusedArgs &a);
 hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s);
 
