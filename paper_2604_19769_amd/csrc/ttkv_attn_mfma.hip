@@ -38,10 +38,12 @@
 // the keys have channel groups (idle columns cost nothing).  One pass serves int4 keys (2 groups) with up to 8
 // heads per KV head and int8 keys (4 groups) with up to 4; two passes (a second q operand and selector, summed
 // before the softmax) int8 keys with up to 8 heads and int4 keys with up to 16.  fp16 / bf16 and keys grouped
-// over tokens take any count up to 16.  Launches outside this budget, and those where the vector kernel is as
-// fast or faster (two heads per KV head of one format), stay on the vector kernel.
+// over tokens take any count up to 16.  More heads per KV head are cut into blocks of 16 (8 if a tier has int8
+// keys), one workgroup and one pass over the bytes per block.  Launches where the vector kernel is as fast or
+// faster (two heads per KV head of one format) stay on the vector kernel.
 #include "ttkv_attn_dev.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace ttkv {
@@ -116,9 +118,10 @@ constexpr float k_offset(int i) {
 // count from the arguments (fp16 / bf16 / keys grouped over tokens: any count up to 16).
 template <int KF, int VF, int GT>
 __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
-                                             int chunk, int seq, int hkv, float (*s_acc)[16][128],
+                                             int chunk, int seq, int hq0, int Gr, int hkv, float (*s_acc)[16][128],
                                              float (*s_m)[16], float (*s_l)[16]) {
-  const int Gr = a.Hq / a.Hkv;             // real heads per KV head
+  // hq0, Gr: first query head and number of heads of this workgroup's block of heads (all heads of the KV head,
+  // or a block of up to 8 / 16 of them)
   const int G = GT ? GT : Gr;              // heads per group block of columns
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
@@ -155,7 +158,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   uint32_t qB[NP][16];
   float off[NP], qs[NP];
   {
-    const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hkv * Gr + min(g, Gr - 1)) * 128);
+    const uint4 *qrow = (const uint4 *)((const uint16_t *)a.q + ((int64_t)seq * a.Hq + hq0 + min(g, Gr - 1)) * 128);
     uint32_t qw[16];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {     // 8 channels per 16-byte load
@@ -488,9 +491,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   __shared__ float s_acc[4][16][128];   // [wave][head][channel]
   __shared__ float s_m[4][16], s_l[4][16];
 
-  const int G = a.Hq / a.Hkv;
-  const int item = blockIdx.x / a.Hkv;
-  const int hkv = blockIdx.x % a.Hkv;
+  // Linear workgroup id -> (item, KV head, block of heads).  More heads per KV head than one tile takes are cut
+  // into blocks of mfma_heads; the blocks of one (item, KV head) read the same bytes and get ids 8 apart, so that
+  // they run on the same XCD at the same time and the later readers are served from its L2.
+  const int Gtot = a.Hq / a.Hkv;
+  const uint32_t n_hb = (Gtot + a.mfma_heads - 1) / a.mfma_heads;
+  const uint32_t id = blockIdx.x;
+  const uint32_t base = ((id >> 3) / n_hb) * 8 + (id & 7);
+  if (base >= (uint32_t)a.n_items * a.Hkv) return;
+  const int item = base / a.Hkv;
+  const int hkv = base % a.Hkv;
+  const int hb0 = ((id >> 3) % n_hb) * a.mfma_heads;          // first head of the block within the KV head's heads
+  const int hq0 = hkv * Gtot + hb0;
+  const int G = min(a.mfma_heads, Gtot - hb0);                // heads in this block
 
   int lo = 0, hi = a.n_entries - 1;
   while (lo < hi) {
@@ -505,7 +518,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   const int chunk = item - en.item_start;
 
   const int combo = tv.k_fmt * 8 + tv.v_fmt;
-#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hkv, s_acc, s_m, s_l)
+#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hq0, G, hkv, s_acc, s_m, s_l)
   switch (combo) {
     case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
     case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;
@@ -537,7 +550,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
       o = fmaf(s_acc[w][g][dch], wgt, o);
       ll = fmaf(s_l[w][g], wgt, ll);
     }
-    const int64_t prow = ((int64_t)seq * a.Hq + hkv * G + g) * a.part_stride + part;
+    const int64_t prow = ((int64_t)seq * a.Hq + hq0 + g) * a.part_stride + part;
     a.pacc[prow * 128 + dch] = o;
     if (dch == 0) {
       a.pm[prow] = M * kLn2;  // natural-log units outside the kernel
@@ -550,13 +563,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
 
 // Can one 16-column tile hold every (group, head) column of these formats, and does the
 // single pass pay off (from four query heads per KV head on, measured)?
-// Does the (group, head) column budget take these formats?  Head counts are padded to 4, 8 or 16 (idle columns
-// cost nothing); one pass holds groups x heads <= 16 columns, two passes <= 32.
+// Heads one workgroup serves in a single pass over the bytes: 16 columns per pass of the score product, two
+// passes at most, groups x heads columns (heads padded to 4, 8 or 16 where the keys have channel groups; idle
+// columns cost nothing).  More heads per KV head are cut into blocks of this many.
+int mfma_block_heads(int k_fmt) { return k_fmt == TTKV_I8_SYM_G32 ? 8 : 16; }
+
+// Do the kernel's cases take these formats?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
-  if (G < 2 || G > 16) return false;
-  if (k_fmt == TTKV_I4_ASYM_T128) return true;    // no channel groups: one column per head
-  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt;            // 2 groups x 16 heads at most
-  if (k_fmt == TTKV_I8_SYM_G32) return G <= 8;                     // 4 groups x 8 heads at most
+  if (G < 2) return false;
+  if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt;
   return true;
 }
 
@@ -568,41 +583,54 @@ bool attn_mfma_pays(int G, bool has_mixed_or_t128) { return G >= (has_mixed_or_t
 
 namespace {
 int padded_heads(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
-bool needs_two_passes(int k_fmt, int G) {
-  return (k_fmt == TTKV_I8_SYM_G32 && padded_heads(G) == 8) || (k_fmt == TTKV_I4_ASYM_G64 && padded_heads(G) == 16);
-}
 bool quantized_per_token(int k_fmt) { return k_fmt == TTKV_I8_SYM_G32 || k_fmt == TTKV_I4_ASYM_G64; }
+
+// What one launch needs: heads per block (the smallest any of its tiers takes), the padded count the
+// quantized-key cases are compiled for, two-pass cases, keys grouped over tokens.
+struct MfmaShape {
+  int heads, padded;
+  bool wide, t128, mixed, ok;
+};
+MfmaShape mfma_shape(const FusedArgs &a) {
+  const int G = a.Hq / a.Hkv;
+  MfmaShape m{16, 4, false, false, false, true};
+  bool quant = false;
+  for (int j = 0; j < a.n_entries; ++j) {
+    const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
+    m.ok &= attn_mfma_fits(tv.k_fmt, tv.v_fmt, G);
+    m.heads = std::min(m.heads, mfma_block_heads(tv.k_fmt));
+    m.t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
+    m.mixed |= tv.k_fmt == TTKV_I8_SYM_G32 && tv.v_fmt == TTKV_I4_ASYM_G64;
+    quant |= quantized_per_token(tv.k_fmt);
+  }
+  m.heads = std::min(m.heads, G);
+  if (quant) m.padded = padded_heads(m.heads);
+  for (int j = 0; j < a.n_entries; ++j) {
+    const int kf = a.tv[(a.e[j].tier_seq >> 16) & 0xff].k_fmt;
+    m.wide |= (kf == TTKV_I8_SYM_G32 && m.padded == 8) || (kf == TTKV_I4_ASYM_G64 && m.padded == 16);
+  }
+  return m;
+}
 }  // namespace
 
 bool attn_mfma_eligible(const FusedArgs &a) {
-  const int G = a.Hq / a.Hkv;
-  bool wide = false, t128 = false, mixed = false;
-  for (int j = 0; j < a.n_entries; ++j) {
-    const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
-    if (!attn_mfma_fits(tv.k_fmt, tv.v_fmt, G)) return false;
-    wide |= needs_two_passes(tv.k_fmt, G);
-    t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
-    mixed |= tv.k_fmt == TTKV_I8_SYM_G32 && tv.v_fmt == TTKV_I4_ASYM_G64;
-  }
-  return attn_mfma_pays(G, t128 || mixed) && !(wide && t128);   // wide with T128 has no instantiation: vector kernel
+  const MfmaShape m = mfma_shape(a);
+  // two-pass cases together with keys grouped over tokens have no instantiation: vector kernel
+  return m.ok && attn_mfma_pays(a.Hq / a.Hkv, m.t128 || m.mixed) && !(m.wide && m.t128);
 }
 
-hipError_t launch_attn_mfma(const FusedArgs &a, hipStream_t s) {
+hipError_t launch_attn_mfma(const FusedArgs &a0, hipStream_t s) {
+  const MfmaShape m = mfma_shape(a0);
+  FusedArgs a = a0;
+  a.mfma_heads = m.heads;
   const int G = a.Hq / a.Hkv;
-  bool wide = false, t128 = false, quant = false;
-  for (int j = 0; j < a.n_entries; ++j) {
-    const TierView &tv = a.tv[(a.e[j].tier_seq >> 16) & 0xff];
-    wide |= needs_two_passes(tv.k_fmt, G);
-    t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
-    quant |= quantized_per_token(tv.k_fmt);
-  }
-  const int GP = quant ? padded_heads(G) : 4;   // only the per-token quantized key cases depend on the padded count
-  const dim3 grid((uint32_t)a.n_items * a.Hkv);
-  if (t128 && GP == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, true>), grid, dim3(256), 0, s, a);
-  else if (t128) hipLaunchKernelGGL((attn_mfma_kernel<4, false, true>), grid, dim3(256), 0, s, a);
-  else if (GP == 16) hipLaunchKernelGGL((attn_mfma_kernel<16, true, false>), grid, dim3(256), 0, s, a);
-  else if (GP == 8 && wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true, false>), grid, dim3(256), 0, s, a);
-  else if (GP == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, false>), grid, dim3(256), 0, s, a);
+  const uint32_t n_hb = (G + m.heads - 1) / m.heads;
+  const dim3 grid(((uint32_t)a.n_items * a.Hkv + 7) / 8 * 8 * n_hb);
+  if (m.t128 && m.padded == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, true>), grid, dim3(256), 0, s, a);
+  else if (m.t128) hipLaunchKernelGGL((attn_mfma_kernel<4, false, true>), grid, dim3(256), 0, s, a);
+  else if (m.padded == 16) hipLaunchKernelGGL((attn_mfma_kernel<16, true, false>), grid, dim3(256), 0, s, a);
+  else if (m.padded == 8 && m.wide) hipLaunchKernelGGL((attn_mfma_kernel<8, true, false>), grid, dim3(256), 0, s, a);
+  else if (m.padded == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, false, false>), grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL((attn_mfma_kernel<4, false, false>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }

@@ -152,6 +152,7 @@ struct FusedArgs {
   int32_t part_stride;
   int32_t Hq, Hkv;
   float scale;
+  int32_t mfma_heads;   // set by the matrix-core launcher: query heads one workgroup serves
 };
 hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels, int *n_mfma);
 bool attn_supported(int k_fmt, int v_fmt, int G);
