@@ -95,3 +95,16 @@ def test_many_query_heads_per_kv_head(Hq, Hkv, dtype, fmts):
     tiers = tiers3(dtype, host=False) if fmts is None else tiers3(dtype, fmts=fmts, host=False)
     st = run_config(2, Hq, Hkv, tiers, dtype, None, 3, synth.SEED_BASE + 44 + Hq, lens=[333, 2100], want_stats=True)
     assert st["mfma_launches"] == 3
+
+
+@pytest.mark.parametrize("Hq,Hkv,n_slots", [(4, 4, 0), (8, 2, 2)])
+def test_four_tiers_the_maximum(Hq, Hkv, n_slots):
+    """TTKV_MAX_TIERS tiers: fp16 -> int8 -> K 8-bit / V 4-bit in HBM -> int4 in pinned host memory; a token that
+    reaches the last tier has passed through every format above it, and every boundary evicts during the run."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=128, block_tokens=64, ring_blocks=3),
+             dict(k_fmt="i8", v_fmt="i8", capacity=256, block_tokens=64, ring_blocks=6),
+             dict(k_fmt="i8", v_fmt="i4", capacity=384, block_tokens=128, ring_blocks=5),
+             dict(k_fmt="i4", v_fmt="i4", capacity=10**9, block_tokens=256, ring_blocks=12, mem="host")]
+    st = run_config(2, Hq, Hkv, tiers, "f16", None, 200, synth.SEED_BASE + 70 + Hq, lens=[90, 1900], check_state_every=100,
+                    n_slots=n_slots, want_stats=True, oracle_max_tokens=[600, 1200, 1600, 3200])
+    assert st["demotions"] > 8
