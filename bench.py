@@ -334,6 +334,28 @@ def measure_hbm_read_peak(h):
     return n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def measure_hbm_read_same_size(h, n):
+    """The load-only kernel over n bytes, one HIP event pair per launch (median of 15): the time a kernel that
+    only streams the attention launch's bytes needs, measured the way the attention launch is."""
+    import torch
+    from paper_2604_19769_amd import binding as B
+    n = n // 4096 * 4096
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        B.ttkv_stream_read(h, buf.data_ptr(), n, sink.data_ptr(), stream)
+    ts = []
+    for _ in range(15):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.ttkv_stream_read(h, buf.data_ptr(), n, sink.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e-3)
+    return sorted(ts)[len(ts) // 2]
+
+
 def decode_only_seconds(cache, q, reps):
     """Attention alone (no append, no eviction), mean over reps, bracketed by full synchronisation."""
     for i in range(2):
@@ -655,6 +677,9 @@ def main():
     hbm_read = measure_hbm_read_peak(cache.h)
     roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
     roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
+    same = measure_hbm_read_same_size(cache.h, int(k_bytes))
+    roofline["load_only_same_bytes_us"] = round(same * 1e6, 2)
+    roofline["frac_of_load_only_same_bytes"] = round(same / (kms * 1e-3), 4)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_mha32k(kv, steps_in, shape, keep[:min(len(keep), 24)])   # the warm-up steps: ~0.1 s of oracle each
