@@ -167,7 +167,10 @@ ttkv_status ttkv_quantize_append(ttkv_handle h, ttkv_cache *c, int32_t tier, int
 
 /* The same for a host tier: quantizes into `workspace` [device]
  * (ttkv_append_host_workspace_bytes) and copies the touched rows of the touched
- * records to the pinned pool on `stream`. */
+ * records to the pinned pool on `stream`.  workspace NULL (ws_bytes ignored): no
+ * staging and no copies, the conversion kernels store into the pinned records
+ * themselves, so the transfer over PCIe runs while they compute (the bulk path
+ * for tiering a whole prompt, Sec. 3 "prefilling and decoding"). */
 ttkv_status ttkv_quantize_append_host(ttkv_handle h, ttkv_cache *c, int32_t tier, int32_t seq, const void *k_src,
                                       const void *v_src, int32_t src_fmt, int64_t n_tokens, int32_t through_tiers,
                                       void *workspace, size_t ws_bytes, void *stream);

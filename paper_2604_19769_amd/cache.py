@@ -32,6 +32,7 @@ class TieredCache:
         self.cfg = list(tiers)
         self.device = torch.device(device)
         self.n_slots = n_slots
+        self.host_append_direct = True    # bulk appends to a host tier are stored by the kernels; False: staging record + copies
         self.h = B.ttkv_create()
         self.c = B.ttkv_cache()
         c = self.c
@@ -109,7 +110,10 @@ class TieredCache:
         fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16, torch.float32: B.F32}[k.dtype]
         assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape and k.dtype == v.dtype
         n = k.shape[-2]
-        if self.cfg[tier].mem == "host":
+        if self.cfg[tier].mem == "host" and self.host_append_direct:
+            # no staging: the conversion kernels store into the pinned records
+            B.ttkv_quantize_append_host(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), None, 0, self._compute())
+        elif self.cfg[tier].mem == "host":
             need = B.ttkv_append_host_workspace_bytes(self.c, tier, seq, n)
             ws = torch.empty(need, dtype=torch.uint8, device=self.device)
             B.ttkv_quantize_append_host(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), ws, need, self._compute())

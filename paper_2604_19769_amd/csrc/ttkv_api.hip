@@ -345,8 +345,10 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
   a.n_tokens = (int32_t)n_tokens;
   fill_via(a, c, tier, through != 0);
 
+  // host tier without a workspace: the kernels store into the pinned records themselves (PCIe writes)
+  const bool direct = host_variant && workspace == nullptr;
   int max_touched = 0;
-  if (!host_variant) {
+  if (!host_variant || direct) {
     a.dst = make_view(T, L);
     for (int b = b0; b < b1; ++b) {
       const int j = b - b0;
@@ -374,7 +376,8 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
   TTKV_HIP(h, launch_convert(a, stream, &nk));
   TTKV_HIP(h, run_summary(a, c, tier, stream, &nk));
   h->stats.kernels += nk;
-  if (host_variant) {
+  if (direct) h->stats.d2h_bytes += (uint64_t)a.n_seq * (uint64_t)n_tokens * (L.kc + L.km + L.vc + L.vm) * c->n_kv_heads;
+  if (host_variant && !direct) {
     for (int b = b0; b < b1; ++b) {
       const int j = b - b0;
       const int64_t o0 = T.start[b] + T.len[b];

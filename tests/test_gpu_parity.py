@@ -77,8 +77,9 @@ def test_quantize_append_bit_exact(dtype, fmt):
 
 
 def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
-               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None):
-    p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots, oracle_max_tokens=oracle_max_tokens)
+               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None, host_append_direct=False):
+    p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots, oracle_max_tokens=oracle_max_tokens,
+             host_append_direct=host_append_direct)
     worst = 0.0
     try:
         g = synth.rng(seed)
@@ -176,6 +177,20 @@ def test_three_tiers_with_host_streaming_and_eviction_cascade(n_slots):
     2, 3: block copies into staging slots, event-chained with the attention kernels."""
     run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150 if n_slots != 3 else 20, synth.SEED_BASE + 4,
                check_state_every=50, n_slots=n_slots)
+
+
+@pytest.mark.parametrize("variant", ["plain", "paged", "summary"])
+def test_host_tier_bulk_load_written_by_the_kernels(variant):
+    """The initial state of the host tier stored by the conversion kernels straight into the pinned records
+    (no staging workspace, no copies): same codes, scales, zeros, summaries and outputs."""
+    if variant == "plain":
+        run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 3, synth.SEED_BASE + 4, host_append_direct=True)
+    elif variant == "paged":
+        run_config(4, 8, 2, tiers3("f16", paged=True, rings=(6, 8, 12)), "f16", None, 3, synth.SEED_BASE + 5,
+                   lens=[300, 1500, 2900, 2047], host_append_direct=True)
+    else:
+        tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
+        run_config(2, 8, 2, tiers, "bf16", 3500, 3, synth.SEED_BASE + 6, select_k=6, host_append_direct=True)
 
 
 def test_host_tier_no_overlap_gives_the_same_result():
@@ -281,7 +296,7 @@ def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host, n_slots):
     tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=128, ring_blocks=3),
              dict(k_fmt="i4t", v_fmt="i4", capacity=10**9, block_tokens=128 if not host else 256, ring_blocks=30,
                   mem="host" if host else "device")]
-    p = Pair(2, Hq, Hkv, tiers, dtype, n_slots=n_slots)
+    p = Pair(2, Hq, Hkv, tiers, dtype, n_slots=n_slots, host_append_direct=host and n_slots == 3)   # one case: bulk load stored by the kernels
     try:
         g = synth.rng(synth.SEED_BASE + 50 + Hq)
         for b, n in enumerate((128 * 9 + 255, 128 * 20 + 130)):       # tier 0 takes the newest 255 / 130... rest whole groups
