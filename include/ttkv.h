@@ -187,7 +187,7 @@ size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32
 ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int32_t max_blocks, void *workspace,
                              size_t ws_bytes, void *compute, void *copy);
 
-/* One decode step of streaming attention (Alg. 1 lines 1-10, Sec. 4.3) for every
+/* One decode step of streaming attention (Alg. 1, Sec. 4.3) for every
  * sequence: partial (max, sum-exp, weighted V) over each part of every tier,
  * merged by log-sum-exp.
  *   q    [device] [batch][n_q_heads][128], q_fmt F16 or BF16 (a BF16 tier needs BF16
@@ -210,7 +210,22 @@ ttkv_status ttkv_decode_attn(ttkv_handle h, const ttkv_cache *c, const void *q, 
                              float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
                              void *workspace, size_t ws_bytes, int32_t n_slots, void *compute, void *copy);
 
-/* Log-sum-exp merge of n_parts partials per row (the "+" of Alg. 1 line 10):
+/* The "append" and "attend" lines of Alg. 1 for one decode step in one call: the step's new token
+ * (k_new, v_new [device] [batch][n_kv_heads][128], new_fmt F16 or BF16) is appended to tier 0 of every
+ * sequence and attended together with everything cached; len[] of tier 0 grows by one.  Same result and
+ * same arguments otherwise as ttkv_quantize_append(tier 0, seq -1, n_tokens 1) followed by
+ * ttkv_decode_attn.  When tier 0 is an fp16/bf16 device tier (new_fmt must be its format, else
+ * UNSUPPORTED) the step takes one launch fewer: the attention kernels run over the tokens already
+ * cached, and the merge kernel adds the new token's own term (score q.k_new, weight 1, value v_new)
+ * and stores its row.  Any other first tier: the two calls, one after the other.  CAPACITY if tier
+ * 0's ring has no room; nothing is enqueued and no length changes when a status other than OK or
+ * HIP is returned.  Eviction (ttkv_tier_demote) stays the caller's next call. */
+ttkv_status ttkv_decode_step(ttkv_handle h, ttkv_cache *c, const void *q, int32_t q_fmt, const void *k_new,
+                             const void *v_new, int32_t new_fmt, float *out, float *lse, const int32_t *sel_blocks,
+                             const int32_t *sel_count, int32_t sel_stride, void *workspace, size_t ws_bytes,
+                             int32_t n_slots, void *compute, void *copy);
+
+/* Log-sum-exp merge of n_parts partials per row (the "+" of Alg. 1):
  *   m, l [device] [rows][part_stride] fp32;  acc [device] [rows][part_stride][128] fp32;
  *   n_parts_row [device] [rows] int32 parts to merge per row, or NULL = n_parts for all.
  *   out [device] [rows][128] fp32 = sum_p acc_p e^(m_p-m*) / sum_p l_p e^(m_p-m*);
@@ -220,7 +235,7 @@ ttkv_status ttkv_merge_partials(ttkv_handle h, const float *m, const float *l, c
                                 int32_t part_stride, const int32_t *n_parts_row, int32_t rows, float *out,
                                 float *lse, void *stream);
 
-/* Block identification (Alg. 1 lines 2-6): phi(q, B_j) = sum over query heads of
+/* Block identification (Alg. 1, the identification step): phi(q, B_j) = sum over query heads of
  * q_h . mean-key_j for every live block of the LAST tier (needs k_summary), then
  * the k best per sequence, ties to the lower block id.  sel_blocks [pinned]
  * [batch][sel_stride] block ids ascending, sel_count [pinned] [batch];

@@ -233,7 +233,7 @@ class OracleCache:
                 for blk, _, _ in self.live_blocks(t, b)}
 
     def attend(self, q, selected=None):
-        """Alg. 1 lines 1-10 for every sequence.  q [B][Hq][d] fp32.  selected:
+        """Alg. 1 (one decode step) for every sequence.  q [B][Hq][d] fp32.  selected:
         None (every slow block) or per sequence the block ids of the last tier to
         attend.  Returns (out [B][Hq][d], lse [B][Hq]) fp64."""
         out = np.empty((self.B, self.Hq, self.d), np.float64)

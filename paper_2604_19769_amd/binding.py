@@ -46,6 +46,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
+    "ttkv_decode_step",
     "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing", "ttkv_set_split",
     "ttkv_stream_read",
 ]
@@ -92,6 +93,7 @@ def lib():
         L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
         L.ttkv_tier_demote.argtypes = [p, cp, i32, i32, p, sz, p, p]
         L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
+        L.ttkv_decode_step.argtypes = [p, cp, p, i32, p, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
         L.ttkv_time_attn.argtypes = [p, i32]
@@ -201,6 +203,13 @@ def ttkv_decode_attn(h, cache, q, q_fmt, out, lse, sel_blocks, sel_count, sel_st
     _check(lib().ttkv_decode_attn(h, C.byref(cache), _p(q), q_fmt, _p(out), _p(lse), _p(sel_blocks), _p(sel_count),
                                   sel_stride, _p(workspace), ws_bytes, n_slots, _p(compute), _p(copy)),
            "ttkv_decode_attn")
+
+
+def ttkv_decode_step(h, cache, q, q_fmt, k_new, v_new, new_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace,
+                     ws_bytes, n_slots, compute, copy):
+    _check(lib().ttkv_decode_step(h, C.byref(cache), _p(q), q_fmt, _p(k_new), _p(v_new), new_fmt, _p(out), _p(lse),
+                                  _p(sel_blocks), _p(sel_count), sel_stride, _p(workspace), ws_bytes, n_slots,
+                                  _p(compute), _p(copy)), "ttkv_decode_step")
 
 
 def ttkv_merge_partials(h, m, l, acc, n_parts, part_stride, n_parts_row, rows, out, lse, stream):

@@ -32,6 +32,7 @@ class TieredCache:
         self.cfg = list(tiers)
         self.device = torch.device(device)
         self.n_slots = n_slots
+        self.one_call_step = True         # step(): append + attend through ttkv_decode_step; False: the two calls
         self.host_append_direct = True    # bulk appends to a host tier are stored by the kernels; False: staging record + copies
         self.h = B.ttkv_create()
         self.c = B.ttkv_cache()
@@ -139,8 +140,9 @@ class TieredCache:
             self.ws_parts, self.ws_slots = parts, self.n_slots
         return self.ws
 
-    def decode(self, q, selected=None, overlap=True):
-        """q [B][Hq][128] f16/bf16 on the device.  selected: None or (sel_blocks, sel_count) pinned int32 tensors."""
+    def decode(self, q, selected=None, overlap=True, new=None):
+        """q [B][Hq][128] f16/bf16 on the device.  selected: None or (sel_blocks, sel_count) pinned int32 tensors.
+        new: None, or (k_new, v_new) [B][Hkv][1][128] of the step's token, appended to tier 0 by the same call."""
         q_fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[q.dtype]
         assert q.is_contiguous() and tuple(q.shape) == (self.B, self.Hq, 128)
         sb = sc = None
@@ -148,12 +150,24 @@ class TieredCache:
         if selected is not None:
             sb, sc = selected
             stride = sb.shape[1]
+        if new is not None:
+            self.len[0] += 1            # size the workspace for the lengths the attention may see
         parts = B.ttkv_count_parts(self.h, self.c, sb, sc, stride, self.n_slots)
+        if new is not None:
+            self.len[0] -= 1
         if parts < 0:
             raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
         ws = self._workspace(max(parts, 1))
-        B.ttkv_decode_attn(self.h, self.c, q, q_fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(), self.n_slots,
-                           self._compute(), self._copy(overlap))
+        if new is not None:
+            k_new, v_new = new
+            fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[k_new.dtype]
+            assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == v_new.dtype
+            assert tuple(k_new.shape) == tuple(v_new.shape) == (self.B, self.Hkv, 1, 128)
+            B.ttkv_decode_step(self.h, self.c, q, q_fmt, k_new, v_new, fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(),
+                               self.n_slots, self._compute(), self._copy(overlap))
+        else:
+            B.ttkv_decode_attn(self.h, self.c, q, q_fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(), self.n_slots,
+                               self._compute(), self._copy(overlap))
         return self.out, self.lse
 
     def select(self, q, k):
@@ -168,10 +182,14 @@ class TieredCache:
         return self.sel_blocks, self.sel_count
 
     def step(self, q, k_new, v_new, select_k=None, overlap=True):
-        """One decode step (Alg. 1): append -> [identify blocks] -> attend -> evict."""
-        self.append(0, k_new, v_new)
-        sel = self.select(q, select_k) if select_k is not None else None
-        out, lse = self.decode(q, sel, overlap)
+        """One decode step (Alg. 1): append -> [identify blocks] -> attend -> evict.  k_new, v_new [B][Hkv][1][128]."""
+        if not self.one_call_step:
+            self.append(0, k_new, v_new)
+            sel = self.select(q, select_k) if select_k is not None else None
+            out, lse = self.decode(q, sel, overlap)
+        else:
+            sel = self.select(q, select_k) if select_k is not None else None
+            out, lse = self.decode(q, sel, overlap, new=(k_new, v_new))
         self.demote(overlap)
         return out, lse
 

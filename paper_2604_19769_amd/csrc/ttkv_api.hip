@@ -646,11 +646,13 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   return TTKV_OK;
 }
 
-ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
-                             const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
-                             size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h) return TTKV_ERR_INVALID_ARG;
+// Attention over the cached tokens and the merge.  k_new non-null: the step's new token as well, which the merge
+// kernel adds and stores at the tail of tier 0 (an fp device tier of format new_fmt with room for it: the caller
+// has checked); len[] of tier 0 then grows by one.
+static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
+                               const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
+                               size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_, const void *k_new,
+                               const void *v_new, int32_t new_fmt, bool check_only = false) {
   ttkv_status st = validate_cache(c);
   if (st != TTKV_OK) return st;
   if (!q || !out || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
@@ -677,6 +679,7 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   const int64_t stride = (int64_t)((ws_bytes - mis - slots_bytes) / (rows * 130 * sizeof(float)));
   if (stride < std::max(1, P.max_parts)) return TTKV_ERR_WORKSPACE;
   const int32_t part_stride = (int32_t)std::min<int64_t>(stride, 1 << 20);
+  if (check_only) return TTKV_OK;   // nothing enqueued so far
   if (!P.fetch.empty() && copy != compute && (st = ensure_events(h)) != TTKV_OK) return st;
   uint8_t *ws = (uint8_t *)workspace + mis;
   float *pm = (float *)(ws + slots_bytes);
@@ -785,10 +788,62 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   for (int b = 0; b < c->batch; ++b) m.cnt[b] = P.parts[b];
   m.out = out;
   m.lse = lse;
+  if (k_new) {
+    const ttkv_tier &T0 = c->tier[0];
+    m.q = q; m.k_new = k_new; m.v_new = v_new;
+    m.q_fmt = q_fmt; m.new_fmt = new_fmt;
+    m.Hq = c->n_q_heads; m.Hkv = c->n_kv_heads;
+    m.scale = c->softmax_scale;
+    m.dst = make_view(T0, make_layout(T0, c->n_kv_heads));
+    for (int b = 0; b < c->batch; ++b) m.new_tok[b] = (int32_t)((T0.start[b] + T0.len[b]) % ring_tokens(T0));
+  }
   TTKV_HIP(h, launch_merge(m, compute));
+  if (k_new)
+    for (int b = 0; b < c->batch; ++b) c->tier[0].len[b] += 1;
   h->stats.mfma_launches += nm;
   h->stats.kernels += nk + 1;
   return TTKV_OK;
+}
+
+ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
+                             const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
+                             size_t ws_bytes, int32_t n_slots, void *compute, void *copy) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute,
+                     copy, nullptr, nullptr, 0);
+}
+
+ttkv_status ttkv_decode_step(ttkv_handle hh, ttkv_cache *c, const void *q, int32_t q_fmt, const void *k_new,
+                             const void *v_new, int32_t new_fmt, float *out, float *lse, const int32_t *sel_blocks,
+                             const int32_t *sel_count, int32_t sel_stride, void *workspace, size_t ws_bytes,
+                             int32_t n_slots, void *compute, void *copy) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (!k_new || !v_new || (new_fmt != TTKV_F16 && new_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
+  ttkv_tier &T0 = c->tier[0];
+  for (int b = 0; b < c->batch; ++b)
+    if (T0.len[b] + 1 > ring_tokens(T0)) return TTKV_ERR_CAPACITY;
+  const bool in_merge = T0.mem == TTKV_MEM_DEVICE && is_fp(T0.k_fmt) && T0.k_fmt == T0.v_fmt && !T0.k_sum;
+  if (in_merge) {
+    if (T0.k_fmt != new_fmt) return TTKV_ERR_UNSUPPORTED;   // an fp tier takes only its own format
+    return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute,
+                       copy, k_new, v_new, new_fmt);
+  }
+  // any other first tier: the two calls.  What the second one checks before it enqueues is checked first, on the
+  // lengths it will see, so that a refusal leaves the cache as it was.
+  for (int b = 0; b < c->batch; ++b) T0.len[b] += 1;
+  st = decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute, copy,
+                   nullptr, nullptr, 0, true);
+  for (int b = 0; b < c->batch; ++b) T0.len[b] -= 1;
+  if (st != TTKV_OK) return st;
+  st = append_impl(h, c, 0, -1, k_new, v_new, new_fmt, 1, 0, nullptr, 0, (hipStream_t)compute,
+                   T0.mem == TTKV_MEM_HOST_PINNED);
+  if (st != TTKV_OK) return st;
+  return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute,
+                     copy, nullptr, nullptr, 0);
 }
 
 ttkv_status ttkv_merge_partials(ttkv_handle hh, const float *m, const float *l, const float *acc, int32_t n_parts,

@@ -440,14 +440,37 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
 // One workgroup of 256 threads per row: thread = channel, the parts split over the two halves of
 // the workgroup.  Each half scans its parts' maxima itself (the same few addresses for every
 // thread: broadcast loads), so the only exchange is the final merge of the two halves.
+// With a new token (Alg. 1 appends it before attending) the row's own term is formed here from q, k_new and
+// v_new, and the first query head of each KV head stores the token's row at the tail of tier 0: the attention
+// kernels then run over the tokens already cached and a step needs no launch of its own for the append.
 __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
-  __shared__ float s_o[128], s_l2, s_M2;
+  __shared__ float s_o[128], s_l2, s_M2, s_dot[4];
   const int row = blockIdx.x, dch = threadIdx.x & 127, half = threadIdx.x >> 7;
   int n = a.n_parts;
   if (a.n_parts_row)
     n = a.n_parts_row[row];
   else if (a.rows_per_seq > 0)
     n = a.cnt[row / a.rows_per_seq];
+  float v_new = 0.0f;
+  if (a.k_new) {   // launch-uniform
+    const int seq = row / a.Hq, hq = row - seq * a.Hq, G = a.Hq / a.Hkv, hkv = hq / G;
+    const int64_t src = ((int64_t)seq * a.Hkv + hkv) * 128 + dch;
+    const uint16_t kb = ((const uint16_t *)a.k_new)[src], vb = ((const uint16_t *)a.v_new)[src];
+    const uint16_t qb = ((const uint16_t *)a.q)[(int64_t)row * 128 + dch];
+    const float kf = a.new_fmt == TTKV_F16 ? h2f(kb) : __uint_as_float((uint32_t)kb << 16);
+    const float qf = a.q_fmt == TTKV_F16 ? h2f(qb) : __uint_as_float((uint32_t)qb << 16);
+    v_new = a.new_fmt == TTKV_F16 ? h2f(vb) : __uint_as_float((uint32_t)vb << 16);
+    const float part = wave_sum(qf * kf);   // both halves form the same two wave sums
+    if ((threadIdx.x & 63) == 0) s_dot[threadIdx.x >> 6] = part;
+    if (hq == hkv * G) {   // half 0 stores the key row, half 1 the value row
+      const int tok = a.new_tok[seq];
+      const int rb = tok / a.dst.bt, r = tok - rb * a.dst.bt;
+      const int64_t rec = a.dst.table ? (int64_t)a.dst.table[(int64_t)seq * a.dst.ring_blocks + rb]
+                                      : (int64_t)seq * a.dst.ring_blocks + rb;
+      uint8_t *head = a.dst.base + rec * a.dst.rec_bytes + (int64_t)hkv * a.dst.head_bytes;
+      ((uint16_t *)(head + (half ? a.dst.v_off : 0) + r * 256))[dch] = half ? vb : kb;
+    }
+  }
   const float *pm = a.m + (int64_t)row * a.part_stride;
   const float *pl = a.l + (int64_t)row * a.part_stride;
   const float *pa = a.acc + (int64_t)row * a.part_stride * 128;
@@ -471,10 +494,12 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
   }
   __syncthreads();
   if (!half) {
-    const float M2 = s_M2, Mt = fmaxf(M, M2);
+    const float Mn = a.k_new ? (s_dot[0] + s_dot[1]) * a.scale : -INFINITY;   // the new token: (m, l, acc) = (score, 1, v)
+    const float M2 = s_M2, Mt = fmaxf(fmaxf(M, M2), Mn);
     const float w1 = M == -INFINITY ? 0.0f : __expf(M - Mt), w2 = M2 == -INFINITY ? 0.0f : __expf(M2 - Mt);
-    o = o * w1 + s_o[dch] * w2;
-    l = l * w1 + s_l2 * w2;
+    const float wn = Mn == -INFINITY ? 0.0f : __expf(Mn - Mt);
+    o = o * w1 + s_o[dch] * w2 + v_new * wn;
+    l = l * w1 + s_l2 * w2 + wn;
     a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
     if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? Mt + __logf(l) : -INFINITY;
   }

@@ -170,6 +170,13 @@ struct MergeArgs {
   int32_t rows_per_seq;         // > 0: use cnt[row / rows_per_seq]
   int32_t cnt[TTKV_MAX_BATCH];
   float *out, *lse;
+  // The step's new token (k_new nullable; then rows = batch x Hq): its term (score q.k_new, weight 1, value
+  // v_new) joins the merge, and its row is stored at the tail of tier 0, whose fp format it has.
+  const void *q, *k_new, *v_new;   // q [batch][Hq][128]; k_new, v_new [batch][Hkv][128]
+  int32_t q_fmt, new_fmt, Hq, Hkv;
+  float scale;
+  TierView dst;                       // tier 0
+  int32_t new_tok[TTKV_MAX_BATCH];    // ring token index where the sequence's row lands
 };
 hipError_t launch_merge(const MergeArgs &a, hipStream_t s);
 

@@ -93,6 +93,21 @@ def test_invalid_arguments_are_status_codes():
     assert L.ttkv_quantize_append(h, C.byref(c), 3, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
     assert L.ttkv_quantize_append(h, C.byref(c), 0, 2, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG
     assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 0, 0, None) == B.OK     # nothing to do
+    # one-call step: NULL token, a format the fp tier does not have, a full ring; no length changes on refusal
+    tail = (dummy, None, None, None, 0, dummy, 1 << 20, 0, None, None)     # out, lse, selection, workspace, slots, streams
+    assert L.ttkv_decode_step(h, C.byref(c), dummy, B.F16, None, dummy, B.F16, *tail) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_step(h, C.byref(c), dummy, B.F16, dummy, dummy, B.I8_SYM_G32, *tail) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_step(h, C.byref(c), dummy, B.F16, dummy, dummy, B.BF16, *tail) == B.ERR_UNSUPPORTED
+    assert L.ttkv_decode_step(None, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, *tail) == B.ERR_INVALID_ARG
+    lens = c._keep[2]                       # tier 0's len[]
+    lens[:] = 8 * 128
+    assert L.ttkv_decode_step(h, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, *tail) == B.ERR_CAPACITY
+    lens[:] = 5
+    assert L.ttkv_decode_step(h, C.byref(c), None, B.F16, dummy, dummy, B.F16, *tail) == B.ERR_INVALID_ARG      # no query
+    assert L.ttkv_decode_step(h, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, dummy, None, None, None, 0, dummy, 64, 0,
+                              None, None) == B.ERR_WORKSPACE
+    assert lens.tolist() == [5, 5]
+    lens[:] = 0
     # keys grouped over tokens: a key format of the last tier only, whole groups of 128 tokens
     c.tier[2].k_fmt = B.I4_ASYM_T128
     assert L.ttkv_quantize_append_host is not None

@@ -77,9 +77,9 @@ def test_quantize_append_bit_exact(dtype, fmt):
 
 
 def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
-               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None, host_append_direct=False):
+               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None, host_append_direct=False, one_call_step=True):
     p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots, oracle_max_tokens=oracle_max_tokens,
-             host_append_direct=host_append_direct)
+             host_append_direct=host_append_direct, one_call_step=one_call_step)
     worst = 0.0
     try:
         g = synth.rng(seed)
@@ -177,6 +177,23 @@ def test_three_tiers_with_host_streaming_and_eviction_cascade(n_slots):
     2, 3: block copies into staging slots, event-chained with the attention kernels."""
     run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150 if n_slots != 3 else 20, synth.SEED_BASE + 4,
                check_state_every=50, n_slots=n_slots)
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype,paged", [(4, 4, "f16", False), (8, 2, "bf16", False), (8, 2, "f16", True)])
+def test_step_as_two_calls(Hq, Hkv, dtype, paged):
+    """Append (ttkv_quantize_append on tier 0) and attention (ttkv_decode_attn) as separate calls; every other test
+    steps through ttkv_decode_step, where the merge kernel adds the new token and stores its row."""
+    run_config(2, Hq, Hkv, tiers3(dtype, paged=paged, rings=(6, 8, 16)), dtype, 2900, 70, synth.SEED_BASE + 60 + Hq,
+               check_state_every=35, one_call_step=False)
+
+
+@pytest.mark.parametrize("first", [("i8", "i8"), ("i8", "i4")])
+def test_step_with_a_quantized_first_tier(first):
+    """No fp tier at all (the ablation's "no fast tier" taken to the end): ttkv_decode_step falls back to
+    quantize-append + attention, same state and outputs."""
+    tiers = [dict(k_fmt=first[0], v_fmt=first[1], capacity=256, block_tokens=64, ring_blocks=6),
+             dict(k_fmt="i4", v_fmt="i4", capacity=10**9, block_tokens=128, ring_blocks=30)]
+    run_config(2, 8, 2, tiers, "f16", 1500, 70, synth.SEED_BASE + 62, check_state_every=35)
 
 
 @pytest.mark.parametrize("variant", ["plain", "paged", "summary"])
