@@ -437,20 +437,31 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
   }
 }
 
-// One workgroup of 256 threads per row: thread = channel, the parts split over the two halves of
-// the workgroup.  Each half scans its parts' maxima itself (the same few addresses for every
-// thread: broadcast loads), so the only exchange is the final merge of the two halves.
+// One workgroup of 256 threads per row: thread = channel, the parts split over the two halves of the workgroup.
+// The kernel is a chain of memory latencies, so each part's (m, l) is loaded once, by thread p of its half; the
+// half's maximum and the weights e^(m_p - M) go through LDS, and the acc loads (independent of them) are issued
+// eight at a time, the first eight before anything else.
 // With a new token (Alg. 1 appends it before attending) the row's own term is formed here from q, k_new and
 // v_new, and the first query head of each KV head stores the token's row at the tail of tier 0: the attention
 // kernels then run over the tokens already cached and a step needs no launch of its own for the append.
 __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
-  __shared__ float s_o[128], s_l2, s_M2, s_dot[4];
-  const int row = blockIdx.x, dch = threadIdx.x & 127, half = threadIdx.x >> 7;
+  __shared__ float s_o[128], s_w[2][128], s_hm[4], s_hl[4], s_dot[4];
+  const int row = blockIdx.x, dch = threadIdx.x & 127, half = threadIdx.x >> 7, wave = threadIdx.x >> 6;
   int n = a.n_parts;
   if (a.n_parts_row)
     n = a.n_parts_row[row];
   else if (a.rows_per_seq > 0)
     n = a.cnt[row / a.rows_per_seq];
+  const float *pm = a.m + (int64_t)row * a.part_stride;
+  const float *pl = a.l + (int64_t)row * a.part_stride;
+  const float *pa = a.acc + (int64_t)row * a.part_stride * 128 + dch;
+  const int p0 = half ? (n + 1) / 2 : 0, p1 = half ? n : (n + 1) / 2;
+  const int nb = ((n + 1) / 2 + 127) / 128;   // batches of 128 parts: the same count in both halves (barriers inside)
+  constexpr int U = 8;
+  float av[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) av[u] = p0 + u < p1 ? pa[(int64_t)(p0 + u) * 128] : 0.0f;
+
   float v_new = 0.0f;
   if (a.k_new) {   // launch-uniform
     const int seq = row / a.Hq, hq = row - seq * a.Hq, G = a.Hq / a.Hkv, hkv = hq / G;
@@ -461,7 +472,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
     const float qf = a.q_fmt == TTKV_F16 ? h2f(qb) : __uint_as_float((uint32_t)qb << 16);
     v_new = a.new_fmt == TTKV_F16 ? h2f(vb) : __uint_as_float((uint32_t)vb << 16);
     const float part = wave_sum(qf * kf);   // both halves form the same two wave sums
-    if ((threadIdx.x & 63) == 0) s_dot[threadIdx.x >> 6] = part;
+    if ((threadIdx.x & 63) == 0) s_dot[wave] = part;
     if (hq == hkv * G) {   // half 0 stores the key row, half 1 the value row
       const int tok = a.new_tok[seq];
       const int rb = tok / a.dst.bt, r = tok - rb * a.dst.bt;
@@ -471,35 +482,56 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
       ((uint16_t *)(head + (half ? a.dst.v_off : 0) + r * 256))[dch] = half ? vb : kb;
     }
   }
-  const float *pm = a.m + (int64_t)row * a.part_stride;
-  const float *pl = a.l + (int64_t)row * a.part_stride;
-  const float *pa = a.acc + (int64_t)row * a.part_stride * 128;
-  const int p0 = half ? (n + 1) / 2 : 0, p1 = half ? n : (n + 1) / 2;
-  float M = -INFINITY;
-  for (int p = p0; p < p1; ++p) M = fmaxf(M, pm[p]);
-  float o = 0.0f, l = 0.0f;
-#pragma unroll 4
-  for (int p = p0; p < p1; ++p) {
-    const float mp = pm[p];
-    const float w = mp == -INFINITY ? 0.0f : __expf(mp - M);
-    o = fmaf(pa[(int64_t)p * 128 + dch], w, o);
-    l = fmaf(pl[p], w, l);
-  }
-  if (half) {
-    s_o[dch] = o;
-    if (dch == 0) {
-      s_l2 = l;
-      s_M2 = M;
+
+  // the half's maximum
+  float mp0 = -INFINITY, pl0 = 0.0f, M = -INFINITY;   // mp0, pl0: (m, l) of this thread's part in the first batch
+  for (int b = 0; b < nb; ++b) {
+    const int p = p0 + b * 128 + dch;
+    const float mp = p < p1 ? pm[p] : -INFINITY;
+    if (b == 0) {
+      mp0 = mp;
+      pl0 = p < p1 ? pl[p] : 0.0f;
     }
+    M = fmaxf(M, mp);
   }
+  M = wave_max(M);
+  if ((threadIdx.x & 63) == 0) s_hm[wave] = M;
+  __syncthreads();
+  M = fmaxf(s_hm[2 * half], s_hm[2 * half + 1]);
+
+  float o = 0.0f, l = 0.0f;
+  for (int b = 0; b < nb; ++b) {
+    const int pb = p0 + b * 128, p = pb + dch;
+    float w = 0.0f;
+    if (p < p1) {
+      const float mp = b == 0 ? mp0 : pm[p];
+      w = mp == -INFINITY ? 0.0f : __expf(mp - M);
+      l = fmaf(b == 0 ? pl0 : pl[p], w, l);
+    }
+    if (b) __syncthreads();   // the weights of the batch before have been used
+    s_w[half][dch] = w;
+    __syncthreads();
+    const int cnt = min(128, p1 - pb);   // <= 0 when the other half has one batch more
+    int u = 0;
+    if (b == 0) {
+#pragma unroll
+      for (; u < U; ++u)
+        if (u < cnt) o = fmaf(av[u], s_w[half][u], o);
+    }
+#pragma unroll 8
+    for (; u < cnt; ++u) o = fmaf(pa[(int64_t)(pb + u) * 128], s_w[half][u], o);
+  }
+  l = wave_sum(l);
+  if ((threadIdx.x & 63) == 0) s_hl[wave] = l;
+  if (half) s_o[dch] = o;
   __syncthreads();
   if (!half) {
     const float Mn = a.k_new ? (s_dot[0] + s_dot[1]) * a.scale : -INFINITY;   // the new token: (m, l, acc) = (score, 1, v)
-    const float M2 = s_M2, Mt = fmaxf(fmaxf(M, M2), Mn);
+    const float M2 = fmaxf(s_hm[2], s_hm[3]), Mt = fmaxf(fmaxf(M, M2), Mn);
     const float w1 = M == -INFINITY ? 0.0f : __expf(M - Mt), w2 = M2 == -INFINITY ? 0.0f : __expf(M2 - Mt);
     const float wn = Mn == -INFINITY ? 0.0f : __expf(Mn - Mt);
     o = o * w1 + s_o[dch] * w2 + v_new * wn;
-    l = l * w1 + s_l2 * w2 + wn;
+    l = (s_hl[0] + s_hl[1]) * w1 + (s_hl[2] + s_hl[3]) * w2 + wn;
     a.out[(int64_t)row * 128 + dch] = l > 0.0f ? o / l : 0.0f;
     if (a.lse && dch == 0) a.lse[row] = l > 0.0f ? Mt + __logf(l) : -INFINITY;
   }

@@ -251,21 +251,23 @@ def test_summaries_match_the_oracle_bit_for_bit():
         p.close()
 
 
-def test_merge_partials_standalone():
-    """ttkv_merge_partials against the oracle's merge: random partials, empty parts, ragged part counts."""
+@pytest.mark.parametrize("rows,P,stride", [(37, 19, 24), (9, 700, 704), (5, 257, 257), (4, 1, 1)])
+def test_merge_partials_standalone(rows, P, stride):
+    """ttkv_merge_partials against the oracle's merge: random partials, empty parts, ragged part counts; one part,
+    and more parts than one pass of the workgroup takes (several batches, halves with different batch counts)."""
     g = synth.rng(synth.SEED_BASE + 8)
-    rows, P, stride = 37, 19, 24
     m = (g.standard_normal((rows, stride)) * 5).astype(np.float32)
     l = (g.random((rows, stride)) * 50 + 0.1).astype(np.float32)
     acc = (g.standard_normal((rows, stride, 128)) * 30).astype(np.float32)
-    m[3, 4] = -np.inf
-    l[3, 4] = 0
-    acc[3, 4] = 0
-    m[5, :] = -np.inf
-    l[5, :] = 0
-    acc[5] = 0
+    m[3, min(4, P - 1)] = -np.inf
+    l[3, min(4, P - 1)] = 0
+    acc[3, min(4, P - 1)] = 0
+    m[2, :] = -np.inf
+    l[2, :] = 0
+    acc[2] = 0
     cnt = g.integers(1, P + 1, rows).astype(np.int32)
-    cnt[7] = 0
+    cnt[1] = 0
+    cnt[0] = P
     h = B.ttkv_create()
     try:
         for counts in (None, cnt):
