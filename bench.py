@@ -76,6 +76,21 @@ def timed_steps(cache, q, kn, vn, first, count, overlap=True, keep=None, sample_
     return sync_time() - t0
 
 
+def step_latencies(cache, q, kn, vn, first, count):
+    """Per-step times in seconds of steps [first, first+count): one HIP event recorded on the stream after every
+    step, no host synchronisation in between.  Each event leaves a few microseconds of idle stream, so the median
+    reads higher than the back-to-back mean of timed_steps; the spread (p95) is what this is for."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(count + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i, s in enumerate(range(first, first + count)):
+        cache.step(q[s], kn[s], vn[s])
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return sorted(ev[i].elapsed_time(ev[i + 1]) * 1e-3 for i in range(count))
+
+
 # ------------------------------------------------------------------ workload: MHA 32K, int4 in HBM
 
 def build_mha32k(steps_total, N=32768, slow_k="i4"):
@@ -669,7 +684,8 @@ def main():
         print(json.dumps(line))
         return
 
-    cache, kv, steps_in, shape = build_mha32k(W + K)
+    L = 64                                                   # further steps timed one by one (median, p95)
+    cache, kv, steps_in, shape = build_mha32k(W + K + L)
     q, kn, vn = steps_in
     keep = []
     timed_steps(cache, q, kn, vn, 0, W, keep=keep)
@@ -691,6 +707,7 @@ def main():
     hbm_read = measure_hbm_read_peak(cache.h)
     roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
     roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
+    lat = step_latencies(cache, q, kn, vn, W + K, L)
     same = measure_hbm_read_same_size(cache.h, int(k_bytes))
     roofline["load_only_same_bytes_us"] = round(same * 1e6, 2)
     roofline["frac_of_load_only_same_bytes"] = round(same / (kms * 1e-3), 4)
@@ -710,7 +727,9 @@ def main():
         "config": {"workload": "mha32k: batch 4, 32 heads MHA, head_dim 128, 32768 tokens, recent 2048 fp16 + 30720 int4 "
                                "(group 64, asymmetric) in HBM, append + attend + evict per step",
                    "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-                   "fp16_equivalent_GBs": round(shape["B"] * shape["Hkv"] * shape["N"] * 512 / (secs / K) / 1e9, 1)},
+                   "fp16_equivalent_GBs": round(shape["B"] * shape["Hkv"] * shape["N"] * 512 / (secs / K) / 1e9, 1),
+                   "step_us_p50_p95_of_64_event_timed": [round(lat[len(lat) // 2] * 1e6, 1),
+                                                         round(lat[int(0.95 * len(lat))] * 1e6, 1)]},
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
         "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
         "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),
