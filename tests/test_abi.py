@@ -191,3 +191,17 @@ def test_sizes_of_the_layout_formula():
         fp = "bf16" if kf == "bf16" else "f16"
         ora = OracleCache(1, hkv, hkv, 128, [TierSpec(fp, fp, 128, 128), TierSpec(kf, vf, 10**9, bt)], [128, 128])
         assert ora.record_bytes(1) * (tokens // bt) == nbytes, name
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/ttkv.h is the boundary: it must compile as C99 on its own (no C++ or HIP types in the signatures)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "ttkv.h"\nint main(void) { ttkv_cache c; ttkv_stats s; (void)c; (void)s; return 0; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(src), "-o",
+                    str(tmp_path / "hdr.o")], check=True)
+
