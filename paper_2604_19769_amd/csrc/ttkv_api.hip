@@ -66,6 +66,7 @@ TierView make_view(const ttkv_tier &T, const Layout &L) {
   v.ring_blocks = (int32_t)T.ring_blocks;
   v.k_fmt = T.k_fmt;
   v.v_fmt = T.v_fmt;
+  v.in_host = T.mem == TTKV_MEM_HOST_PINNED;
   return v;
 }
 
@@ -75,6 +76,7 @@ TierView make_slot_view(const ttkv_tier &T, const Layout &L, void *slot, int nre
   v.base = (uint8_t *)slot;
   v.table = nullptr;
   v.ring_blocks = nrec;
+  v.in_host = 0;
   return v;
 }
 

@@ -113,12 +113,57 @@ constexpr float k_offset(int i) {
   return is_i4<F>() ? (i < 2 ? 1024.0f : 64.0f) : (F == TTKV_I8_SYM_G32 ? 1152.0f : 0.0f);
 }
 
+// ---- tiles of quantized rows prefetched through LDS
+// The rows of a batch of tiles are copied global -> LDS asynchronously (no registers in between), the K half and
+// the V half separately, while the batch before is being computed; the copy instructions read whole rows (whole
+// 128-byte lines, so they carry the streaming hint), and the lanes then read their 16-byte pieces from LDS in the
+// operand layout.  Inside LDS row r keeps its pieces in the order p ^ swz(r), which makes the 16 rows that the
+// lanes of one piece read at a time fall into 16 different bank groups; the copy realises the order by choosing
+// which piece each lane fetches.
+constexpr int kTileRowsLds = 8 * 1024, kTileLds = kTileRowsLds + 4 * 256;   // per wave: K rows, V rows, 4 planes of meta words
+typedef const __attribute__((address_space(1))) void *gas_ptr;
+typedef __attribute__((address_space(3))) void *las_ptr;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// lane L's 16 (4) bytes land at dst + 16 L (4 L); dst is wave-uniform; OFF is added to both addresses.
+template <int OFF = 0>
+__device__ __forceinline__ void dma16(const uint8_t *src, char *dst) {
+  __builtin_amdgcn_global_load_lds((gas_ptr)src, (las_ptr)dst, 16, OFF, 2);   // 2: non-temporal
+}
+__device__ __forceinline__ void dma4(const uint8_t *src, char *dst) {
+  __builtin_amdgcn_global_load_lds((gas_ptr)src, (las_ptr)dst, 4, 0, 2);
+}
+// At most N of the wave's vector-memory loads are still outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// LDS reads of a landed half and the wait for them as one block (no use of a result can be scheduled in between;
+// the reads are opaque to the compiler, which would otherwise wait for every copy in flight before an LDS read).
+// A batch is 32 tokens = two tiles.  Rows: int8 w[0..3] = tile 0 piece x = 0, 1 (a0, a1), tile 1 likewise, 2 KiB
+// further; int4 w[0..1] = the lane's one piece of tile 0, 1 (a0, 1 KiB further).  Meta: tile tt's two words from
+// m0 + 64 tt and m0 + 256 + 64 tt.
+__device__ __forceinline__ void lds_half_i4x2(uint32_t a0, uint32_t m0, u32x4 *w, uint32_t *m) {
+  asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %6 offset:1024\n\t"
+               "ds_read_b32 %2, %7\n\tds_read_b32 %3, %7 offset:256\n\tds_read_b32 %4, %7 offset:64\n\t"
+               "ds_read_b32 %5, %7 offset:320\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(w[0]), "=&v"(w[1]), "=&v"(m[0]), "=&v"(m[1]), "=&v"(m[2]), "=&v"(m[3])
+               : "v"(a0), "v"(m0) : "memory");
+}
+__device__ __forceinline__ void lds_half_i8(uint32_t a0, uint32_t a1, uint32_t m0, u32x4 *w, uint32_t *m) {
+  asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %8 offset:2048\n\t"
+               "ds_read_b128 %3, %9 offset:2048\n\t"
+               "ds_read_b32 %4, %10\n\tds_read_b32 %5, %10 offset:256\n\tds_read_b32 %6, %10 offset:64\n\t"
+               "ds_read_b32 %7, %10 offset:320\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(m[0]), "=&v"(m[1]), "=&v"(m[2]), "=&v"(m[3])
+               : "v"(a0), "v"(a1), "v"(m0) : "memory");
+}
+
 // GT: query heads per KV head, padded to 4, 8 or 16, as a compile-time constant (quantized K: the column layout
 // and the group sum below depend on it; columns of heads beyond the real count stay zero), or 0 to take the real
 // count from the arguments (fp16 / bf16 / keys grouped over tokens: any count up to 16).
 template <int KF, int VF, int GT>
 __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
-                                             int chunk, int seq, int hq0, int Gr, int hkv, float (*s_acc)[16][128],
+                                             int chunk, int seq, int hq0, int Gr, int hkv, char *s_buf,
                                              float (*s_m)[16], float (*s_l)[16]) {
   // hq0, Gr: first query head and number of heads of this workgroup's block of heads (all heads of the KV head,
   // or a block of up to 8 / 16 of them)
@@ -132,10 +177,16 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
   constexpr bool KT = KF == TTKV_I4_ASYM_T128;   // keys grouped over 128 tokens per channel: the scales fold into q
   constexpr bool KBF = KF == TTKV_BF16, VBF = VF == TTKV_BF16;
+  // int8 keys (with int8 or int4 values): rows prefetched through LDS.  Measured per format against the register
+  // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; int4 keys, whose unpack arithmetic already fills the
+  // issue slots, gain nothing (4.9-5.0 either way) and stay on the register loads, as do fp16 / bf16 (a batch of
+  // their rows is 16 KiB per wave: LDS for only two workgroups per CU).
+  constexpr bool PF = KF == TTKV_I8_SYM_G32 && VQ;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, kg = lane >> 4;
+  char *const wbuf = s_buf + wave * kTileLds;   // the wave's LDS: a batch of tiles in flight, at the end its result
   const int c0 = chunk * chunk_tokens;
   const int c1 = min(en.len, c0 + chunk_tokens);
   const int ring_tokens = tv.ring_blocks * tv.bt;
@@ -260,14 +311,22 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   // Plain loads here, not the non-temporal ones of the vector kernel: the load instructions of a tile share
   // cache lines (each reads 64 of a line's 128 bytes), and lines fetched with the streaming hint do not
   // survive until the next instruction.
-  auto load_tiles = [&](TileRegs &t, int i0, int nv, auto full_tag) {
-    constexpr bool FULL = decltype(full_tag)::value;
-    int tok0 = en.first_tok + i0;
+  // Head section and row inside it of the chunk's token i.  The block table does not change during the launch and
+  // the index is wave-uniform: it is read through the constant address space (a scalar load).
+  auto locate = [&](int i, int &row0) -> const uint8_t * {
+    int tok0 = en.first_tok + i;
     if (tok0 >= ring_tokens) tok0 -= ring_tokens;
     const int rb = tok0 / tv.bt;
-    const int row0 = tok0 - rb * tv.bt;
-    const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
-    const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
+    row0 = tok0 - rb * tv.bt;
+    typedef const __attribute__((address_space(4))) int32_t *const_i32;
+    const int64_t rec = tv.table ? (int64_t)((const_i32)(uintptr_t)tv.table)[(int64_t)seq * tv.ring_blocks + rb]
+                                 : (int64_t)en.rec_base + rb;
+    return tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
+  };
+  auto load_tiles = [&](TileRegs &t, int i0, int nv, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    int row0;
+    const uint8_t *head = locate(i0, row0);
     const uint8_t *kb = head + row0 * FK::ROWB, *kmb = head + tv.k_meta_off + row0 * 8;
     const uint8_t *vb = head + tv.v_off + row0 * FV::ROWB, *vmb = head + tv.v_meta_off + row0 * 8;
     if constexpr (KT) {   // the 64 tokens in flight lie inside one aligned group of 128: its 128 meta rows x 4 B
@@ -289,7 +348,100 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
   };
 
-  auto compute_tiles = [&](const TileRegs &t, int nv, auto full_tag) {
+  // ---- PF: the same rows as asynchronous copies into the wave's LDS and reads from there.
+  // LDS of the wave: K rows at 0, V rows at 4 KiB (row r at r ROWB, its piece p at 16 (p ^ swz(r))), then four
+  // planes of 64 meta words: K words 0 and 1 of the batch's tokens, V words 0 and 1.
+  constexpr int PK = FK::ROWB / 16, PV = FV::ROWB / 16;              // pieces per row
+  constexpr int NDK = TT * FK::ROWB / 1024, NDV = TT * FV::ROWB / 1024;   // copy instructions of 1 KiB per half
+  constexpr int N_K = NDK + 2, N_V = NDV + 2;                          // with the two meta planes
+  static_assert(!PF || (NT == 2 && PK == 8 && NDK == 4 && (NDV == 4 || NDV == 2)), "the batch the LDS readers cover");
+  auto swz = [](int pieces, int r) { return pieces == 4 ? (r >> 2) & 3 : (r >> 1) & 7; };
+  // per-lane byte offset of copy instruction j inside a full batch, minus j KiB (even and odd j differ for 8 pieces)
+  uint32_t dko[2], dvo[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int rk = j * (64 / PK) + lane / PK, rv = j * (64 / PV) + lane / PV;
+    dko[j] = rk * FK::ROWB + ((lane % PK) ^ swz(PK, rk)) * 16 - j * 1024;
+    dvo[j] = rv * FV::ROWB + ((lane % PV) ^ swz(PV, rv)) * 16 - j * 1024;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(las_ptr)wbuf;
+  // where lane (n, kg) finds its piece kg (and kg + 4) of row n of tile 0
+  auto piece_addr = [&](int pieces, int rowb, int x) -> uint32_t {
+    return n * rowb + (((kg + 4 * x) ^ swz(pieces, n)) * 16);
+  };
+  const uint32_t lka0 = lds0 + piece_addr(PK, FK::ROWB, 0), lka1 = lds0 + piece_addr(PK, FK::ROWB, PK == 8 ? 1 : 0);
+  const uint32_t lva0 = lds0 + 4096 + piece_addr(PV, FV::ROWB, 0), lva1 = lds0 + 4096 + piece_addr(PV, FV::ROWB, PV == 8 ? 1 : 0);
+  const uint32_t lkm = lds0 + kTileRowsLds + n * 4, lvm = lkm + 512;
+  const uint8_t *nx_head = nullptr;   // batch whose K half was issued last
+  int nx_row0 = 0, nx_nv = 0;
+  auto issue_k = [&](int i0) {
+    nx_head = locate(i0, nx_row0);
+    nx_nv = min(TT, c1 - i0);
+    const uint8_t *kb = nx_head + nx_row0 * FK::ROWB, *kmb = nx_head + tv.k_meta_off + nx_row0 * 8;
+    if (nx_nv == TT) {
+      dma16<0>(kb + dko[0], wbuf); dma16<1024>(kb + dko[1], wbuf);
+      dma16<2048>(kb + dko[0], wbuf); dma16<3072>(kb + dko[1], wbuf);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NDK; ++j) {
+        const int r = j * (64 / PK) + lane / PK;   // LDS row; rows past the end repeat the last live row
+        dma16(kb + min(r, nx_nv - 1) * FK::ROWB + ((lane % PK) ^ swz(PK, r)) * 16, wbuf + j * 1024);
+      }
+    }
+    const uint32_t mo = min(lane, nx_nv - 1) * 8;   // one lane per token (TT = 32: the upper lanes repeat the last row)
+    dma4(kmb + mo, wbuf + kTileRowsLds);
+    dma4(kmb + mo + 4, wbuf + kTileRowsLds + 256);
+  };
+  auto issue_v = [&]() {
+    const uint8_t *vb = nx_head + tv.v_off + nx_row0 * FV::ROWB, *vmb = nx_head + tv.v_meta_off + nx_row0 * 8;
+    if (nx_nv == TT) {
+      dma16<0>(vb + dvo[0], wbuf + 4096); dma16<1024>(vb + dvo[1], wbuf + 4096);
+      if constexpr (NDV == 4) {
+        dma16<2048>(vb + dvo[0], wbuf + 4096); dma16<3072>(vb + dvo[1], wbuf + 4096);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NDV; ++j) {
+        const int r = j * (64 / PV) + lane / PV;
+        dma16(vb + min(r, nx_nv - 1) * FV::ROWB + ((lane % PV) ^ swz(PV, r)) * 16, wbuf + 4096 + j * 1024);
+      }
+    }
+    const uint32_t mo = min(lane, nx_nv - 1) * 8;
+    dma4(vmb + mo, wbuf + kTileRowsLds + 512);
+    dma4(vmb + mo + 4, wbuf + kTileRowsLds + 768);
+  };
+  auto fetch_k = [&](TileRegs &t) {
+    u32x4 w[4];
+    uint32_t mw[8];
+    lds_half_i8(lka0, lka1, lkm, w, mw);
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+#pragma unroll
+      for (int x = 0; x < NLK; ++x) {
+        const u32x4 v = w[tt * NLK + x];
+        t.kw[tt][x] = uint4{v.x, v.y, v.z, v.w};
+      }
+      t.kmeta[tt] = uint2{mw[2 * tt], mw[2 * tt + 1]};
+    }
+  };
+  auto fetch_v = [&](TileRegs &t) {
+    u32x4 w[4];
+    uint32_t mw[8];
+    if constexpr (PV == 8) lds_half_i8(lva0, lva1, lvm, w, mw);
+    else lds_half_i4x2(lva0, lvm, w, mw);
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) {
+#pragma unroll
+      for (int x = 0; x < NLV; ++x) {
+        const u32x4 v = w[tt * NLV + x];
+        t.vw[tt][x] = uint4{v.x, v.y, v.z, v.w};
+      }
+      t.vmeta[tt] = uint2{mw[2 * tt], mw[2 * tt + 1]};
+    }
+  };
+
+  // before_v runs between the softmax and the first use of the batch's V half.
+  auto compute_tiles = [&](TileRegs &t, int nv, auto full_tag, auto before_v) {
     constexpr bool FULL = decltype(full_tag)::value;
     // ---- KT: q . k = sum_d (q_d s_d) (c_d - 8) + sum_d q_d (z_d + 8 s_d) with s, z of the token group.  q_d s_d
     // is carried as two fp16 operands (rounded product and exact remainder), both multiplied with the codes;
@@ -387,6 +539,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 
     // ---- weighted V, two 16-token tiles per 32-deep product
+    before_v();
 #pragma unroll
     for (int tp = 0; tp < NT; tp += 2) {
       uint32_t pB[4];          // softmax weights of the pair, rounded to fp16: the B operand
@@ -446,17 +599,50 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
   };
 
-  {
+  auto register_loop = [&]() {
     TileRegs ra;
     int i0 = c0 + wave * TT;
     for (; i0 + TT <= c1; i0 += 4 * TT) {
       load_tiles(ra, i0, TT, std::true_type{});
-      compute_tiles(ra, TT, std::true_type{});
+      compute_tiles(ra, TT, std::true_type{}, []() {});
     }
     if (i0 < c1) {
       load_tiles(ra, i0, c1 - i0, std::false_type{});
-      compute_tiles(ra, c1 - i0, std::false_type{});
+      compute_tiles(ra, c1 - i0, std::false_type{}, []() {});
     }
+  };
+  // Records in pinned host memory keep the register loads: over PCIe the copies through LDS are 3-4 % slower
+  // (measured), and the streaming hint has nothing to gain there.
+  if constexpr (PF) {
+    if (!tv.in_host) {
+      // While batch i is computed the copies of batch i + 1 are in flight: its K half is issued once batch i's K
+      // rows are in registers, its V half once batch i's V rows are.  Loads complete in order, so "at most as
+      // many outstanding as were issued after it" means a half has landed.
+      TileRegs ra;
+      int i0 = c0 + wave * TT;
+      if (i0 < c1) {
+        issue_k(i0);
+        issue_v();
+      }
+      auto step = [&](int nv, auto full_tag) {
+        const bool more = i0 + 4 * TT < c1;   // wave-uniform
+        wait_vmcnt<N_V>();
+        fetch_k(ra);
+        if (more) issue_k(i0 + 4 * TT);
+        compute_tiles(ra, nv, full_tag, [&]() {
+          if (more) wait_vmcnt<N_K>();
+          else wait_vmcnt<0>();
+          fetch_v(ra);
+          if (more) issue_v();
+        });
+      };
+      for (; i0 + TT <= c1; i0 += 4 * TT) step(TT, std::true_type{});
+      if (i0 < c1) step(c1 - i0, std::false_type{});
+    } else {
+      register_loop();
+    }
+  } else {
+    register_loop();
   }
 
   // ---- the wave's result: column n < G of lane (n, kg) holds, in acc[s][i], the row channel of slice element
@@ -469,11 +655,12 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     z[0] = -128.0f * ((kg >> 1) ? accz[1] : accz[0]);
     z[1] = -128.0f * ((kg >> 1) ? accz[3] : accz[2]);
   }
+  float (*w_acc)[128] = (float (*)[128])wbuf;   // [head][channel]; the wave's last batch has been consumed
   if (n < Gr) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s_acc[wave][n][slice_channel<VF>(kg, chan<VF>(s, i))] = acc[s][i] + z[s / 4];
+      for (int i = 0; i < 4; ++i) w_acc[n][slice_channel<VF>(kg, chan<VF>(s, i))] = acc[s][i] + z[s / 4];
     if (kg == 0) {
       s_m[wave][n] = m * cs;   // log2 domain
       s_l[wave][n] = l;
@@ -488,7 +675,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 // T128: the launch has a tier whose keys are grouped over 128 tokens per channel (its own instantiations as well).
 template <int GQ, bool WIDE, bool T128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 2 : 3, GQ == 16 ? 2 : 3))) void attn_mfma_kernel(const FusedArgs a) {
-  __shared__ float s_acc[4][16][128];   // [wave][head][channel]
+  static_assert(kTileLds >= 16 * 128 * 4, "the wave's result fits its tile buffer");
+  __shared__ __attribute__((aligned(128))) char s_buf[4 * kTileLds];   // per wave: batch in flight, then [head][channel] floats
   __shared__ float s_m[4][16], s_l[4][16];
 
   // Linear workgroup id -> (item, KV head, block of heads).  More heads per KV head than one tile takes are cut
@@ -518,7 +706,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   const int chunk = item - en.item_start;
 
   const int combo = tv.k_fmt * 8 + tv.v_fmt;
-#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hq0, G, hkv, s_acc, s_m, s_l)
+#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hq0, G, hkv, s_buf, s_m, s_l)
   switch (combo) {
     case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
     case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;
@@ -547,7 +735,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float wgt = s_m[w][g] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(s_m[w][g] - M);
-      o = fmaf(s_acc[w][g][dch], wgt, o);
+      o = fmaf(((const float *)(s_buf + w * kTileLds))[g * 128 + dch], wgt, o);
       ll = fmaf(s_l[w][g], wgt, ll);
     }
     const int64_t prow = ((int64_t)seq * a.Hq + hq0 + g) * a.part_stride + part;

@@ -55,6 +55,7 @@ struct TierView {
   int32_t head_bytes, k_meta_off, v_off, v_meta_off;
   int32_t bt, ring_blocks;
   int32_t k_fmt, v_fmt;
+  int32_t in_host;        // the records are pinned host memory, read over PCIe
 };
 
 // Per-launch sequence table, passed by value in the kernel arguments so that no
