@@ -410,7 +410,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     dma4(vmb + mo, wbuf + kTileRowsLds + 512);
     dma4(vmb + mo + 4, wbuf + kTileRowsLds + 768);
   };
-  auto fetch_k = [&](TileRegs &t) {
+  auto fetch_k = [&](auto &t) {   // generic: compiled only where it is called, i.e. for the formats of PF
     u32x4 w[4];
     uint32_t mw[8];
     lds_half_i8(lka0, lka1, lkm, w, mw);
@@ -424,7 +424,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       t.kmeta[tt] = uint2{mw[2 * tt], mw[2 * tt + 1]};
     }
   };
-  auto fetch_v = [&](TileRegs &t) {
+  auto fetch_v = [&](auto &t) {
     u32x4 w[4];
     uint32_t mw[8];
     if constexpr (PV == 8) lds_half_i8(lva0, lva1, lvm, w, mw);
