@@ -149,6 +149,14 @@ __device__ __forceinline__ void lds_half_i4x2(uint32_t a0, uint32_t m0, u32x4 *w
                : "=&v"(w[0]), "=&v"(w[1]), "=&v"(m[0]), "=&v"(m[1]), "=&v"(m[2]), "=&v"(m[3])
                : "v"(a0), "v"(m0) : "memory");
 }
+// fp16 / bf16: w[4 tt + x] = piece x of the lane of tile tt, from ax (tile 1: 4 KiB further); no meta words.
+__device__ __forceinline__ void lds_half_fp(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, u32x4 *w) {
+  asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
+               "ds_read_b128 %4, %8 offset:4096\n\tds_read_b128 %5, %9 offset:4096\n\t"
+               "ds_read_b128 %6, %10 offset:4096\n\tds_read_b128 %7, %11 offset:4096\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(w[4]), "=&v"(w[5]), "=&v"(w[6]), "=&v"(w[7])
+               : "v"(a0), "v"(a1), "v"(a2), "v"(a3) : "memory");
+}
 __device__ __forceinline__ void lds_half_i8(uint32_t a0, uint32_t a1, uint32_t m0, u32x4 *w, uint32_t *m) {
   asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %8 offset:2048\n\t"
                "ds_read_b128 %3, %9 offset:2048\n\t"
@@ -179,8 +187,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   constexpr bool KBF = KF == TTKV_BF16, VBF = VF == TTKV_BF16;
   // int8 keys (with int8 or int4 values): rows prefetched through LDS.  Measured per format against the register
   // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; int4 keys, whose unpack arithmetic already fills the
-  // issue slots, gain nothing (4.9-5.0 either way) and stay on the register loads, as do fp16 / bf16 (a batch of
-  // their rows is 16 KiB per wave: LDS for only two workgroups per CU).
+  // issue slots, gain nothing (4.9-5.0 either way) and stay on the register loads; fp16 / bf16 rows take the
+  // one-region variant further down.
   constexpr bool PF = KF == TTKV_I8_SYM_G32 && VQ;
 
   const int lane = threadIdx.x & 63;
@@ -599,6 +607,67 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
   };
 
+  // ---- fp16 / bf16 rows through LDS: a half (K or V rows of a batch of 32 tokens) is 8 KiB, so the wave's LDS
+  // takes one half at a time: K of batch i is read out, V of batch i is copied in while the scores are computed,
+  // read out, K of batch i + 1 copied in while the weighted values are computed.  Row r keeps its 16 pieces in the
+  // order p ^ (r & 15).
+  constexpr bool PF2 = (KF == TTKV_F16 || KF == TTKV_BF16) && KF == VF;
+  const uint8_t *cur_head = nullptr;
+  int cur_row0 = 0, cur_nv = 0;
+  auto issue_fp = [&](const uint8_t *rows, int nv) {   // rows: the half's first row
+    if (nv == 32) {
+      const uint32_t r0 = lane >> 4, s0 = (lane & 15) ^ r0;   // copy j: row 4 j + r0, piece s0 ^ 4 (j & 3)
+      const uint8_t *a0 = rows + r0 * 256 + s0 * 16, *a1 = rows + r0 * 256 + (s0 ^ 4) * 16;
+      const uint8_t *a2 = rows + r0 * 256 + (s0 ^ 8) * 16, *a3 = rows + r0 * 256 + (s0 ^ 12) * 16;
+      dma16<0>(a0, wbuf); dma16<1024>(a1, wbuf); dma16<2048>(a2, wbuf); dma16<3072>(a3, wbuf);
+      dma16<0>(a0 + 4096, wbuf + 4096); dma16<1024>(a1 + 4096, wbuf + 4096);
+      dma16<2048>(a2 + 4096, wbuf + 4096); dma16<3072>(a3 + 4096, wbuf + 4096);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = 4 * j + (lane >> 4);   // LDS row; rows past the end repeat the last live row
+        dma16(rows + min(r, nv - 1) * 256 + (((lane & 15) ^ (r & 15)) * 16), wbuf + j * 1024);
+      }
+    }
+  };
+  auto fetch_fp = [&](auto *dst) {   // dst: kw or vw of the tile registers
+    const uint32_t base = (uint32_t)(uintptr_t)(las_ptr)wbuf + n * 256 + ((kg ^ (n & 3)) * 16);
+    const uint32_t hi = n >> 2;   // piece kg + 4 x sits at slot (kg ^ (n & 3)) + 4 (x ^ hi)
+    u32x4 w[8];
+    lds_half_fp(base + ((0 ^ hi) << 6), base + ((1 ^ hi) << 6), base + ((2 ^ hi) << 6), base + ((3 ^ hi) << 6), w);
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const u32x4 v = w[4 * tt + x];
+        dst[tt][x] = uint4{v.x, v.y, v.z, v.w};
+      }
+  };
+  auto fp_loop = [&](auto &ra) {   // generic: compiled only for the formats of PF2
+    int i0 = c0 + wave * TT;
+    if (i0 < c1) {
+      cur_head = locate(i0, cur_row0);
+      cur_nv = min(TT, c1 - i0);
+      issue_fp(cur_head + cur_row0 * 256, cur_nv);
+    }
+    auto step = [&](int nv, auto full_tag) {
+      wait_vmcnt<0>();
+      fetch_fp(ra.kw);
+      issue_fp(cur_head + tv.v_off + cur_row0 * 256, cur_nv);
+      compute_tiles(ra, nv, full_tag, [&]() {
+        wait_vmcnt<0>();
+        fetch_fp(ra.vw);
+        if (i0 + 4 * TT < c1) {   // wave-uniform
+          cur_head = locate(i0 + 4 * TT, cur_row0);
+          cur_nv = min(TT, c1 - i0 - 4 * TT);
+          issue_fp(cur_head + cur_row0 * 256, cur_nv);
+        }
+      });
+    };
+    for (; i0 + TT <= c1; i0 += 4 * TT) step(TT, std::true_type{});
+    if (i0 < c1) step(c1 - i0, std::false_type{});
+  };
+
   auto register_loop = [&]() {
     TileRegs ra;
     int i0 = c0 + wave * TT;
@@ -641,6 +710,14 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     } else {
       register_loop();
     }
+  } else if constexpr (PF2) {
+    static_assert(!PF2 || (TT == 32 && NT == 2 && NLK == 4 && NLV == 4), "the batch the LDS readers cover");
+    if (!tv.in_host) {
+      TileRegs ra;
+      fp_loop(ra);
+    } else {
+      register_loop();
+    }
   } else {
     register_loop();
   }
@@ -676,7 +753,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 template <int GQ, bool WIDE, bool T128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 2 : 3, GQ == 16 ? 2 : 3))) void attn_mfma_kernel(const FusedArgs a) {
   static_assert(kTileLds >= 16 * 128 * 4, "the wave's result fits its tile buffer");
-  __shared__ __attribute__((aligned(128))) char s_buf[4 * kTileLds];   // per wave: batch in flight, then [head][channel] floats
+  __shared__ __attribute__((aligned(256))) char s_buf[4 * kTileLds];   // per wave: batch in flight, then [head][channel] floats
   __shared__ float s_m[4][16], s_l[4][16];
 
   // Linear workgroup id -> (item, KV head, block of heads).  More heads per KV head than one tile takes are cut
