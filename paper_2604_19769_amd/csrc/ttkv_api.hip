@@ -117,7 +117,7 @@ struct Fetch {
 // kernel (int4: 5.1 TB/s against 4.4-4.7 with two rounds; the other formats are indifferent).
 int default_items(const ttkv_cache *c) {
   const int G = c->n_q_heads / c->n_kv_heads;
-  bool special = false;   // K 8-bit / V 4-bit or keys grouped over tokens: matrix-core kernel already from two heads
+  bool special = false;   // K 8-bit / V 4-bit or keys grouped over tokens
   for (int t = 0; t < c->n_tiers; ++t) {
     const ttkv_tier &T = c->tier[t];
     if (!attn_mfma_fits(T.k_fmt, T.v_fmt, G)) return 2560;

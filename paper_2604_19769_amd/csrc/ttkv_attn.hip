@@ -4,8 +4,8 @@
 //
 // Work item = (tier, sequence, chunk of tokens, KV head[, pair of query heads]); one
 // workgroup of four wave64 per item, each wave streaming 1/4 of the chunk's tiles.
-// This is the kernel for one or two query heads per KV head; launches with four or
-// more go to the matrix-core kernel where its tile takes the formats.
+// This is the kernel for one query head per KV head; launches with two or more go to
+// the matrix-core kernel where its cases take the formats, else here in head pairs.
 //
 // Lane mapping: a K or V row of one token-head is ROWB bytes = LPT lanes x 16 B, so
 // one 128-bit load per lane brings TPL = 64/LPT whole rows per wave, fully

@@ -840,11 +840,13 @@ bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
   return true;
 }
 
-// Does the single pass over the bytes pay off?  From three query heads per KV head on (measured: with two, the
-// vector kernel's head pair is as fast or faster: fp16 6.3 against 5.4 TB/s, int8 and int4 about equal).  With
-// two heads only for K 8-bit / V 4-bit (4.3 against 5.0 TB/s) and keys grouped over tokens (3.5 against 4.4),
-// whose head pair is short of registers on the vector kernel.
-bool attn_mfma_pays(int G, bool has_mixed_or_t128) { return G >= (has_mixed_or_t128 ? 2 : 3); }
+// Does the single pass over the bytes pay off?  From two query heads per KV head on (measured against the vector
+// kernel's head pair at two heads: fp16 6.4 against 6.2 TB/s, int8 6.2 against 5.3, int4 5.2 against 4.5, K 8-bit /
+// V 4-bit 6.0 against 4.3, keys grouped over tokens 4.4 against 3.5).
+bool attn_mfma_pays(int G, bool has_mixed_or_t128) {
+  (void)has_mixed_or_t128;
+  return G >= 2;
+}
 
 namespace {
 int padded_heads(int G) { return G <= 4 ? 4 : (G <= 8 ? 8 : 16); }
