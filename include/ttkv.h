@@ -181,9 +181,11 @@ size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32
  * (src block_tokens tokens; values as stored or decompressed) to the tail of
  * tier src_tier+1 in that tier's formats, repeating while still due, at most
  * max_blocks times per sequence (<= 0: no limit).  Host destination: quantized
- * into `workspace` [device] on `compute`, then copied device->pinned on `copy`
- * after an event.  Updates start[], len[] of both tiers and the destination's
- * key summaries.  CAPACITY if a destination ring would overflow. */
+ * into `workspace` [device] (ttkv_demote_workspace_bytes) on `compute`, then
+ * copied device->pinned on `copy` after an event; workspace NULL: the kernels
+ * store into the pinned records themselves, on `compute`, no copies.  Updates
+ * start[], len[] of both tiers and the destination's key summaries.  CAPACITY
+ * if a destination ring would overflow. */
 ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int32_t max_blocks, void *workspace,
                              size_t ws_bytes, void *compute, void *copy);
 

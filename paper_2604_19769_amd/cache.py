@@ -33,6 +33,7 @@ class TieredCache:
         self.device = torch.device(device)
         self.n_slots = n_slots
         self.one_call_step = True         # step(): append + attend through ttkv_decode_step; False: the two calls
+        self.host_demote_direct = False   # True: evictions into a host tier are stored by the kernels (no staging, no copies)
         self.host_append_direct = True    # bulk appends to a host tier are stored by the kernels; False: staging record + copies
         self.h = B.ttkv_create()
         self.c = B.ttkv_cache()
@@ -125,7 +126,7 @@ class TieredCache:
     def demote(self, overlap=True):
         """Cascade eviction through all tiers (Alg. 1, last lines)."""
         for t in range(len(self.cfg) - 1):
-            need = B.ttkv_demote_workspace_bytes(self.c, t)
+            need = 0 if self.host_demote_direct else B.ttkv_demote_workspace_bytes(self.c, t)
             if need and (self.demote_ws is None or self.demote_ws.numel() < need):
                 self.demote_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
             B.ttkv_tier_demote(self.h, self.c, t, 0, self.demote_ws if need else None, need, self._compute(),

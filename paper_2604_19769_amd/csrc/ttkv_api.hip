@@ -562,7 +562,10 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   if (D.k_fmt == TTKV_I4_ASYM_T128 && S.block_tokens % 128) return TTKV_ERR_UNSUPPORTED;   // whole token groups arrive
   hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
   const Layout LS = make_layout(S, c->n_kv_heads), LD = make_layout(D, c->n_kv_heads);
-  const bool to_host = D.mem == TTKV_MEM_HOST_PINNED;
+  // host destination with a workspace: staging records + copies; without one the kernels store into the pinned
+  // records themselves (ordered on `compute` like a device destination)
+  const bool to_host = D.mem == TTKV_MEM_HOST_PINNED && workspace != nullptr;
+  const bool host_direct = D.mem == TTKV_MEM_HOST_PINNED && workspace == nullptr;
 
   // how many blocks each sequence moves; check every ring before touching anything
   int nmove[TTKV_MAX_BATCH], rounds = 0;
@@ -580,7 +583,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   }
   if (rounds == 0) return TTKV_OK;
   const int touched = LS.bt / LD.bt + 2;
-  if (to_host && (!workspace || ws_bytes < (size_t)c->batch * touched * LD.rec_bytes)) return TTKV_ERR_WORKSPACE;
+  if (to_host && ws_bytes < (size_t)c->batch * touched * LD.rec_bytes) return TTKV_ERR_WORKSPACE;
   if (to_host && (st = ensure_events(h)) != TTKV_OK) return st;
 
   for (int round = 0; round < rounds; ++round) {
@@ -628,6 +631,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
           if (st != TTKV_OK) return st;
         }
       }
+      if (host_direct) h->stats.d2h_bytes += (uint64_t)LS.bt * (LD.kc + LD.km + LD.vc + LD.vm) * c->n_kv_heads;
       S.start[b] += LS.bt;
       S.len[b] -= LS.bt;
       D.len[b] += LS.bt;

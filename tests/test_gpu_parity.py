@@ -77,9 +77,10 @@ def test_quantize_append_bit_exact(dtype, fmt):
 
 
 def run_config(B_, Hq, Hkv, tiers, dtype, N, steps, seed, select_k=None, overlap=True, check_state_every=None, n_slots=0,
-               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None, host_append_direct=False, one_call_step=True):
+               lens=None, peaked=False, want_stats=False, oracle_max_tokens=None, host_append_direct=False, one_call_step=True,
+               host_demote_direct=False):
     p = Pair(B_, Hq, Hkv, tiers, dtype, n_slots=n_slots, oracle_max_tokens=oracle_max_tokens,
-             host_append_direct=host_append_direct, one_call_step=one_call_step)
+             host_append_direct=host_append_direct, one_call_step=one_call_step, host_demote_direct=host_demote_direct)
     worst = 0.0
     try:
         g = synth.rng(seed)
@@ -208,6 +209,18 @@ def test_host_tier_bulk_load_written_by_the_kernels(variant):
     else:
         tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
         run_config(2, 8, 2, tiers, "bf16", 3500, 3, synth.SEED_BASE + 6, select_k=6, host_append_direct=True)
+
+
+@pytest.mark.parametrize("n_slots,paged", [(0, False), (2, False), (0, True)])
+def test_evictions_into_the_host_tier_written_by_the_kernels(n_slots, paged):
+    """ttkv_tier_demote without a workspace: the conversion kernels store the evicted blocks into the pinned records
+    (no staging record, no copies, no events); the records are then read in place or copied to staging slots."""
+    if paged:
+        run_config(4, 8, 2, tiers3("f16", paged=True, rings=(6, 8, 12)), "f16", None, 70, synth.SEED_BASE + 5,
+                   lens=[300, 1500, 2900, 2047], check_state_every=35, n_slots=n_slots, host_demote_direct=True)
+    else:
+        run_config(2, 8, 2, tiers3("f16"), "f16", 2900, 150, synth.SEED_BASE + 4, check_state_every=50, n_slots=n_slots,
+                   host_demote_direct=True)
 
 
 def test_host_tier_no_overlap_gives_the_same_result():

@@ -22,13 +22,15 @@ def dev(x, dtype, device="cuda:0"):
 class Pair:
     """tiers: list of dicts(k_fmt, v_fmt, capacity, block_tokens, ring_blocks, mem, paged_seed, summary)."""
 
-    def __init__(self, B, Hq, Hkv, tiers, dtype, oracle_max_tokens=None, n_slots=0, host_append_direct=False, one_call_step=True):
+    def __init__(self, B, Hq, Hkv, tiers, dtype, oracle_max_tokens=None, n_slots=0, host_append_direct=False, one_call_step=True,
+                 host_demote_direct=False):
         self.B, self.Hq, self.Hkv, self.dtype = B, Hq, Hkv, dtype
         self.tiers = tiers
         self.gpu = TieredCache(B, Hq, Hkv, [TierConfig(t["k_fmt"], t["v_fmt"], t["capacity"], t["block_tokens"],
                                                         t["ring_blocks"], t.get("mem", "device"), t.get("paged_seed"),
                                                         t.get("summary", False)) for t in tiers], n_slots=n_slots)
         self.gpu.host_append_direct = host_append_direct   # bulk loads of a host tier written by the kernels
+        self.gpu.host_demote_direct = host_demote_direct   # evictions into a host tier stored by the kernels
         self.gpu.one_call_step = one_call_step             # append + attend in one call (ttkv_decode_step) or in two
         if oracle_max_tokens is None:
             oracle_max_tokens = [t["ring_blocks"] * t["block_tokens"] * 4 for t in tiers]
