@@ -90,7 +90,8 @@ typedef struct ttkv_tier {
   int64_t pool_blocks;       /* records in `data` */
   void *data;                /* [device] or [pinned] per `mem`: pool_blocks records */
   const int32_t *block_table;     /* [host] [batch][ring_blocks] record index per ring block, or NULL = b*ring_blocks + r */
-  const int32_t *block_table_dev; /* [device] copy of block_table; required iff block_table != NULL and mem == DEVICE */
+  const int32_t *block_table_dev; /* [device] copy of block_table; required when block_table != NULL and kernels address the
+                                     pool: a device tier, a host tier read in place (n_slots 0) or written without a workspace */
   float *k_sum;              /* [device] fp32 [pool_blocks][n_kv_heads][128] running key sums, or NULL (no summaries) */
   void *k_summary;           /* [device] fp16 [pool_blocks][n_kv_heads][128] mean keys; required iff k_sum != NULL */
   int64_t *start;            /* [host] [batch] lifetime ordinal of the oldest live token (library updates) */

@@ -349,6 +349,7 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
 
   // host tier without a workspace: the kernels store into the pinned records themselves (PCIe writes)
   const bool direct = host_variant && workspace == nullptr;
+  if (direct && T.block_table && !T.block_table_dev) return TTKV_ERR_INVALID_ARG;   // the kernels look the records up
   int max_touched = 0;
   if (!host_variant || direct) {
     a.dst = make_view(T, L);
@@ -566,6 +567,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   // records themselves (ordered on `compute` like a device destination)
   const bool to_host = D.mem == TTKV_MEM_HOST_PINNED && workspace != nullptr;
   const bool host_direct = D.mem == TTKV_MEM_HOST_PINNED && workspace == nullptr;
+  if (host_direct && D.block_table && !D.block_table_dev) return TTKV_ERR_INVALID_ARG;   // the kernels look the records up
 
   // how many blocks each sequence moves; check every ring before touching anything
   int nmove[TTKV_MAX_BATCH], rounds = 0;

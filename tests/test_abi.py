@@ -108,6 +108,11 @@ def test_invalid_arguments_are_status_codes():
                               None, None) == B.ERR_WORKSPACE
     assert lens.tolist() == [5, 5]
     lens[:] = 0
+    # a paged host tier written by the kernels needs the device copy of its block table
+    tbl = np.arange(16, dtype=np.int32)
+    c.tier[2].mem, c.tier[2].block_table = B.MEM_HOST_PINNED, tbl.ctypes.data
+    assert L.ttkv_quantize_append_host(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 4, 0, None, 0, None) == B.ERR_INVALID_ARG
+    c.tier[2].mem, c.tier[2].block_table = B.MEM_DEVICE, None
     # keys grouped over tokens: a key format of the last tier only, whole groups of 128 tokens
     c.tier[2].k_fmt = B.I4_ASYM_T128
     assert L.ttkv_quantize_append_host is not None
