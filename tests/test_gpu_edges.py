@@ -108,3 +108,42 @@ def test_four_tiers_the_maximum(Hq, Hkv, n_slots):
     st = run_config(2, Hq, Hkv, tiers, "f16", None, 200, synth.SEED_BASE + 70 + Hq, lens=[90, 1900], check_state_every=100,
                     n_slots=n_slots, want_stats=True, oracle_max_tokens=[600, 1200, 1600, 3200])
     assert st["demotions"] > 8
+
+
+def random_layout(seed):
+    """A seeded random but valid cache: 1-4 tiers, formats that never widen from one tier to the next (values never
+    wider than keys), block sizes, capacities, rings sized for the lengths, host / paged / staged variants."""
+    g = synth.rng(synth.SEED_BASE + 900 + seed)
+    dtype = ("f16", "bf16")[int(g.integers(2))]
+    Hkv = int(g.choice([1, 2, 4]))
+    G = int(g.choice([1, 1, 2, 3, 4, 6, 8]))
+    B_ = int(g.integers(1, 4))
+    n_tiers = int(g.integers(1, 5))
+    order = [(dtype, dtype), ("i8", "i8"), ("i8", "i4"), ("i4", "i4")]
+    level = 0
+    tiers = []
+    lens = [int(g.integers(1, 2600)) for _ in range(B_)]
+    for t in range(n_tiers):
+        if t > 0:
+            level = int(g.integers(max(level, 0 if t < n_tiers - 1 else 0), len(order)))
+        bt = int(g.choice([64, 128, 256]))
+        last = t == n_tiers - 1
+        cap = 10**9 if last else bt * int(g.integers(1, 5))
+        prev_bt = tiers[-1]["block_tokens"] if tiers else 0            # a tier takes whole blocks of the tier above
+        ring = (max(lens) + 64 + prev_bt) // bt + 3 if last else (cap + prev_bt) // bt + 2
+        host = last and t > 0 and bool(g.integers(2))
+        tiers.append(dict(k_fmt=order[level][0], v_fmt=order[level][1], capacity=cap, block_tokens=bt, ring_blocks=ring,
+                          mem="host" if host else "device", paged_seed=int(g.integers(1, 99)) if g.integers(3) == 0 else None))
+    n_slots = int(g.choice([0, 0, 2, 3])) if tiers[-1].get("mem") == "host" else 0
+    return B_, Hkv * G, Hkv, tiers, dtype, lens, n_slots
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_randomized_layouts(seed):
+    """Forty seeded random caches, loaded in bulk and stepped across evictions, against the oracle: state bit for
+    bit, outputs within tolerance, locate and traffic counters equal."""
+    B_, Hq, Hkv, tiers, dtype, lens, n_slots = random_layout(seed)
+    run_config(B_, Hq, Hkv, tiers, dtype, None, 12, synth.SEED_BASE + 950 + seed, lens=lens, n_slots=n_slots,
+               check_state_every=6, host_append_direct=bool(seed & 1), host_demote_direct=bool(seed & 2),
+               one_call_step=bool(seed % 3))
+
