@@ -228,6 +228,24 @@ ttkv_status ttkv_decode_step(ttkv_handle h, ttkv_cache *c, const void *q, int32_
                              const int32_t *sel_count, int32_t sel_stride, void *workspace, size_t ws_bytes,
                              int32_t n_slots, void *compute, void *copy);
 
+/* "Identify", "TopK" and the attention of Alg. 1 in one call with no host round trip: the blocks of the LAST
+ * tier are scored against its mean keys and the k best per sequence chosen as by ttkv_select_blocks, the ids
+ * stay on the device, and the attention kernels look them up themselves (the host only needs their number,
+ * min(k, live blocks)); every other tier is attended whole.  The last tier is read in place (no staging
+ * slots).  k_new, v_new as in ttkv_decode_step or both NULL (attend only); with a token, tier 0 must be an
+ * fp16/bf16 device tier of format new_fmt (UNSUPPORTED otherwise).
+ *   sel_scratch [device] as for ttkv_select_blocks; it holds the ids until the call's kernels have run.
+ *   sel_blocks_out [pinned] [batch][sel_stride], sel_count_out [pinned] [batch], or both NULL: copies of the
+ *   chosen ids and counts for the caller's information, enqueued behind the attention; valid once `stream`
+ *   has drained.
+ * Same results as ttkv_select_blocks + ttkv_decode_step with its lists.  Enqueues on `stream` only and does
+ * not block. */
+ttkv_status ttkv_decode_step_topk(ttkv_handle h, ttkv_cache *c, const void *q, int32_t q_fmt, const void *k_new,
+                                  const void *v_new, int32_t new_fmt, float *out, float *lse, int32_t k,
+                                  int32_t *sel_blocks_out, int32_t *sel_count_out, int32_t sel_stride,
+                                  void *sel_scratch, size_t sel_scratch_bytes, void *workspace, size_t ws_bytes,
+                                  void *stream);
+
 /* Log-sum-exp merge of n_parts partials per row (the "+" of Alg. 1):
  *   m, l [device] [rows][part_stride] fp32;  acc [device] [rows][part_stride][128] fp32;
  *   n_parts_row [device] [rows] int32 parts to merge per row, or NULL = n_parts for all.

@@ -46,7 +46,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
-    "ttkv_decode_step",
+    "ttkv_decode_step", "ttkv_decode_step_topk",
     "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing", "ttkv_set_split",
     "ttkv_stream_read",
 ]
@@ -94,6 +94,7 @@ def lib():
         L.ttkv_tier_demote.argtypes = [p, cp, i32, i32, p, sz, p, p]
         L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
         L.ttkv_decode_step.argtypes = [p, cp, p, i32, p, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
+        L.ttkv_decode_step_topk.argtypes = [p, cp, p, i32, p, p, i32, p, p, i32, p, p, i32, p, sz, p, sz, p]
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
         L.ttkv_time_attn.argtypes = [p, i32]
@@ -210,6 +211,13 @@ def ttkv_decode_step(h, cache, q, q_fmt, k_new, v_new, new_fmt, out, lse, sel_bl
     _check(lib().ttkv_decode_step(h, C.byref(cache), _p(q), q_fmt, _p(k_new), _p(v_new), new_fmt, _p(out), _p(lse),
                                   _p(sel_blocks), _p(sel_count), sel_stride, _p(workspace), ws_bytes, n_slots,
                                   _p(compute), _p(copy)), "ttkv_decode_step")
+
+
+def ttkv_decode_step_topk(h, cache, q, q_fmt, k_new, v_new, new_fmt, out, lse, k, sel_blocks_out, sel_count_out, sel_stride,
+                          sel_scratch, sel_scratch_bytes, workspace, ws_bytes, stream):
+    _check(lib().ttkv_decode_step_topk(h, C.byref(cache), _p(q), q_fmt, _p(k_new), _p(v_new), new_fmt, _p(out), _p(lse), k,
+                                       _p(sel_blocks_out), _p(sel_count_out), sel_stride, _p(sel_scratch), sel_scratch_bytes,
+                                       _p(workspace), ws_bytes, _p(stream)), "ttkv_decode_step_topk")
 
 
 def ttkv_merge_partials(h, m, l, acc, n_parts, part_stride, n_parts_row, rows, out, lse, stream):

@@ -32,6 +32,7 @@ class TieredCache:
         self.cfg = list(tiers)
         self.device = torch.device(device)
         self.n_slots = n_slots
+        self.device_topk = True           # step() with select_k: the chosen ids stay on the device (ttkv_decode_step_topk)
         self.one_call_step = True         # step(): append + attend through ttkv_decode_step; False: the two calls
         self.host_demote_direct = False   # True: evictions into a host tier are stored by the kernels (no staging, no copies)
         self.host_append_direct = True    # bulk appends to a host tier are stored by the kernels; False: staging record + copies
@@ -173,17 +174,46 @@ class TieredCache:
 
     def select(self, q, k):
         q_fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[q.dtype]
+        stride = self._select_buffers(k)
+        B.ttkv_select_blocks(self.h, self.c, q, q_fmt, k, self.sel_blocks, self.sel_count, stride, self.sel_scratch,
+                             self.sel_scratch.numel(), self._compute())
+        return self.sel_blocks, self.sel_count
+
+    def _select_buffers(self, k):
         stride = max(1, k)
         if self.sel_blocks is None or self.sel_blocks.shape[1] != stride:
             self.sel_blocks = torch.zeros(self.B, stride, dtype=torch.int32, pin_memory=True)
             self.sel_count = torch.zeros(self.B, dtype=torch.int32, pin_memory=True)
             self.sel_scratch = torch.empty(self.B * (1024 * 4 + (stride + 1) * 4) + 512, dtype=torch.uint8, device=self.device)
-        B.ttkv_select_blocks(self.h, self.c, q, q_fmt, k, self.sel_blocks, self.sel_count, stride, self.sel_scratch,
-                             self.sel_scratch.numel(), self._compute())
-        return self.sel_blocks, self.sel_count
+        return stride
+
+    def step_topk(self, q, k_new, v_new, k):
+        """append -> identify + top-k + attend with the chosen ids left on the device (no host round trip)."""
+        q_fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[q.dtype]
+        fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[k_new.dtype]
+        assert q.is_contiguous() and k_new.is_contiguous() and v_new.is_contiguous()
+        assert tuple(k_new.shape) == tuple(v_new.shape) == (self.B, self.Hkv, 1, 128)
+        stride = self._select_buffers(k)
+        # parts: every other tier as usual; the last one min(k, live blocks) blocks of fixed items -- an upper bound
+        # is what a dense pass over everything would use, at the lengths the attention will see
+        self.len[0] += 1
+        parts = B.ttkv_count_parts(self.h, self.c, None, None, 0, 0)
+        self.len[0] -= 1
+        last = self.cfg[-1]
+        per_block = max(1, last.block_tokens // (2048 if last.mem == "host" else 256))
+        parts += per_block * min(k, int(max((l + last.block_tokens - 1) // last.block_tokens for l in self.len[-1]))) + 1
+        ws = self._workspace(max(parts, 1))
+        B.ttkv_decode_step_topk(self.h, self.c, q, q_fmt, k_new, v_new, fmt, self.out, self.lse, k, self.sel_blocks,
+                                self.sel_count, stride, self.sel_scratch, self.sel_scratch.numel(), ws, ws.numel(),
+                                self._compute())
+        return self.out, self.lse
 
     def step(self, q, k_new, v_new, select_k=None, overlap=True):
         """One decode step (Alg. 1): append -> [identify blocks] -> attend -> evict.  k_new, v_new [B][Hkv][1][128]."""
+        if select_k is not None and self.device_topk and self.one_call_step and self.n_slots == 0:
+            out, lse = self.step_topk(q, k_new, v_new, select_k)
+            self.demote(overlap)
+            return out, lse
         if not self.one_call_step:
             self.append(0, k_new, v_new)
             sel = self.select(q, select_k) if select_k is not None else None

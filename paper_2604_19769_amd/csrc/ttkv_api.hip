@@ -101,7 +101,13 @@ struct Run {
   int tier, b;
   int32_t rec_base, first_tok, len;
   bool no_table;
+  bool selected;   // `len` blocks named by the device-side selection (rec_base: index of the first id, first_tok: newest block id)
   int part_base, n_chunks;
+};
+// Selection left on the device by the top-k kernel: ids [batch][stride], min(k, live blocks) of them per sequence.
+struct DevSel {
+  const int32_t *ids;
+  int32_t k, stride;
 };
 // One staged copy: consecutive pool records of a host tier brought into a slot.
 struct Fetch {
@@ -161,7 +167,7 @@ int pick_chunk(const ttkv_cache *c, int t, int target_items) {
 // staged: host tiers are copied block by block into staging slots (one kernel per
 // copy); otherwise the fused kernel reads them in place.
 void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, bool staged,
-                int target_items, Plan *P) {
+                int target_items, Plan *P, const DevSel *ds = nullptr) {
   P->status = TTKV_OK;
   P->slot_bytes = 0;
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
@@ -174,7 +180,29 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured);
     // staged slots and selected blocks of a device tier: 256-token items for parallelism
     P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : pick_chunk(c, t, target_items);
+    if (ds && t == last) P->chunk[t] = host ? 2048 : 256;
     const int chunk = P->chunk[t];
+    if (ds && t == last) {
+      // the kernel looks the block ids up itself: the host only knows how many there are
+      const int ipb = (L.bt + chunk - 1) / chunk;   // items per block
+      for (int b = 0; b < c->batch; ++b) {
+        const int64_t first_id = T.start[b] / L.bt;
+        const int64_t end_id = (T.start[b] + T.len[b] + L.bt - 1) / L.bt;  // exclusive
+        const int count = (int)std::min<int64_t>(std::min(ds->k, ds->stride), end_id - first_id);
+        if (T.len[b] == 0 || count <= 0) continue;
+        Run r{};
+        r.tier = t; r.b = b;
+        r.rec_base = (int32_t)((int64_t)b * ds->stride);
+        r.first_tok = (int32_t)(end_id - 1);
+        r.len = count;
+        r.selected = true;
+        r.part_base = P->parts[b];
+        r.n_chunks = count * ipb;
+        P->parts[b] += r.n_chunks;
+        P->runs.push_back(r);
+      }
+      continue;
+    }
     if (!sparse && !(host && staged)) {
       for (int b = 0; b < c->batch; ++b) {
         if (T.len[b] == 0) continue;
@@ -660,7 +688,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
 static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
                                const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
                                size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_, const void *k_new,
-                               const void *v_new, int32_t new_fmt, bool check_only = false) {
+                               const void *v_new, int32_t new_fmt, bool check_only = false, const DevSel *ds = nullptr) {
   ttkv_status st = validate_cache(c);
   if (st != TTKV_OK) return st;
   if (!q || !out || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
@@ -676,7 +704,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   const bool staged = n_slots > 0;
 
   Plan P;
-  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items ? h->target_items : default_items(c), &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items ? h->target_items : default_items(c), &P, ds);
   if (P.status != TTKV_OK) return P.status;
   if (!workspace) return TTKV_ERR_WORKSPACE;
   // workspace = [n_slots staging slots][m][l][acc]
@@ -715,6 +743,14 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
     a.tv[t] = make_view(T, make_layout(T, c->n_kv_heads));
     a.chunk[t] = P.chunk[t];
   }
+  if (ds) {
+    const ttkv_tier &T = c->tier[c->n_tiers - 1];
+    a.sel_ids = ds->ids;
+    for (int b = 0; b < c->batch; ++b) {
+      const int64_t live_end = T.start[b] + T.len[b];
+      a.sel_last_ntok[b] = T.len[b] ? (int32_t)(live_end - (live_end - 1) / T.block_tokens * T.block_tokens) : 0;
+    }
+  }
   const bool timed = h->time_on && h->time_n < h->time_max && !P.runs.empty();
   if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
   // launch order: runs of host tiers first, so that the PCIe stream starts with the first workgroups
@@ -731,7 +767,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
     for (size_t i = r0; i < r1; ++i) {
       const Run &r = *order[i];
       Entry &e = a.e[i - r0];
-      e.tier_seq = (r.no_table ? (1 << 24) : 0) | (r.tier << 16) | r.b;
+      e.tier_seq = (r.no_table ? (1 << 24) : 0) | (r.selected ? (1 << 25) : 0) | (r.tier << 16) | r.b;
       e.rec_base = r.rec_base;
       e.first_tok = r.first_tok;
       e.len = r.len;
@@ -782,7 +818,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   for (const Run &r : P.runs) {
     const ttkv_tier &T = c->tier[r.tier];
     if (T.mem != TTKV_MEM_HOST_PINNED) continue;
-    const int nrec = (r.len + T.block_tokens - 1) / T.block_tokens;
+    const int nrec = r.selected ? r.len : (r.len + T.block_tokens - 1) / T.block_tokens;
     h->stats.h2d_bytes += (uint64_t)nrec * make_layout(T, c->n_kv_heads).rec_bytes;
     h->stats.blocks_fetched += nrec;
   }
@@ -873,18 +909,13 @@ ttkv_status ttkv_merge_partials(ttkv_handle hh, const float *m, const float *l, 
   return TTKV_OK;
 }
 
-ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k,
-                               int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
-                               size_t scratch_bytes, void *stream_) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
-  if (st != TTKV_OK) return st;
-  if (!q || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16) || k < 0 || !sel_blocks || !sel_count || sel_stride < 1)
-    return TTKV_ERR_INVALID_ARG;
+// Scores and top-k of the last tier's live blocks, enqueued on `stream`; the result stays on the device:
+// counts at sel_out[0 .. batch), ids of sequence b at sel_out[batch + b * sel_stride ...].
+static ttkv_status enqueue_select(Handle *h, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k, int32_t sel_stride,
+                                  void *scratch, size_t scratch_bytes, hipStream_t stream, int32_t **sel_out) {
+  if (!q || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16) || k < 0 || sel_stride < 1) return TTKV_ERR_INVALID_ARG;
   const ttkv_tier &T = c->tier[c->n_tiers - 1];
   if (!T.k_summary) return TTKV_ERR_UNSUPPORTED;
-  hipStream_t stream = (hipStream_t)stream_;
   SelectArgs a{};
   a.q = q;
   a.q_fmt = q_fmt;
@@ -913,11 +944,72 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
   a.sel_out = (int32_t *)((uint8_t *)scratch + align256((size_t)c->batch * a.max_blocks * sizeof(float)));
   TTKV_HIP(h, launch_select(a, stream));
   h->stats.kernels += 2;
+  *sel_out = a.sel_out;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k,
+                               int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
+                               size_t scratch_bytes, void *stream_) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if (!sel_blocks || !sel_count) return TTKV_ERR_INVALID_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t *sel_out = nullptr;
+  st = enqueue_select(h, c, q, q_fmt, k, sel_stride, scratch, scratch_bytes, stream, &sel_out);
+  if (st != TTKV_OK) return st;
   // sel_out = [batch counts][batch][sel_stride ids]
-  TTKV_HIP(h, hipMemcpyAsync(sel_count, a.sel_out, (size_t)c->batch * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-  TTKV_HIP(h, hipMemcpyAsync(sel_blocks, a.sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
+  TTKV_HIP(h, hipMemcpyAsync(sel_count, sel_out, (size_t)c->batch * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  TTKV_HIP(h, hipMemcpyAsync(sel_blocks, sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
                              hipMemcpyDeviceToHost, stream));
   TTKV_HIP(h, hipStreamSynchronize(stream));
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_decode_step_topk(ttkv_handle hh, ttkv_cache *c, const void *q, int32_t q_fmt, const void *k_new,
+                                  const void *v_new, int32_t new_fmt, float *out, float *lse, int32_t k,
+                                  int32_t *sel_blocks_out, int32_t *sel_count_out, int32_t sel_stride, void *sel_scratch,
+                                  size_t sel_scratch_bytes, void *workspace, size_t ws_bytes, void *stream_) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  ttkv_status st = validate_cache(c);
+  if (st != TTKV_OK) return st;
+  if ((k_new == nullptr) != (v_new == nullptr) || (sel_blocks_out == nullptr) != (sel_count_out == nullptr))
+    return TTKV_ERR_INVALID_ARG;
+  if (k < 0 || sel_stride < 1) return TTKV_ERR_INVALID_ARG;
+  const ttkv_tier &TL = c->tier[c->n_tiers - 1];
+  if (!TL.k_summary) return TTKV_ERR_UNSUPPORTED;
+  if (TL.block_table && !TL.block_table_dev) return TTKV_ERR_INVALID_ARG;   // the kernels look the records up
+  ttkv_tier &T0 = c->tier[0];
+  if (k_new) {
+    if (new_fmt != TTKV_F16 && new_fmt != TTKV_BF16) return TTKV_ERR_INVALID_ARG;
+    // the new token goes through the merge kernel: an fp device tier of its format (ttkv_decode_step's other
+    // first tiers would need their own append call first)
+    if (!(T0.mem == TTKV_MEM_DEVICE && is_fp(T0.k_fmt) && T0.k_fmt == T0.v_fmt && !T0.k_sum) || T0.k_fmt != new_fmt)
+      return TTKV_ERR_UNSUPPORTED;
+    for (int b = 0; b < c->batch; ++b)
+      if (T0.len[b] + 1 > ring_tokens(T0)) return TTKV_ERR_CAPACITY;
+  }
+  hipStream_t stream = (hipStream_t)stream_;
+  // everything the attention call checks before it enqueues, first: nothing is enqueued on a refusal
+  DevSel probe{nullptr, k, sel_stride};
+  st = decode_impl(h, c, q, q_fmt, out, lse, nullptr, nullptr, 0, workspace, ws_bytes, 0, stream_, stream_, k_new, v_new, new_fmt,
+                   true, &probe);
+  if (st != TTKV_OK) return st;
+  int32_t *sel_out = nullptr;
+  st = enqueue_select(h, c, q, q_fmt, k, sel_stride, sel_scratch, sel_scratch_bytes, stream, &sel_out);
+  if (st != TTKV_OK) return st;
+  const DevSel ds{sel_out + c->batch, k, sel_stride};
+  st = decode_impl(h, c, q, q_fmt, out, lse, nullptr, nullptr, 0, workspace, ws_bytes, 0, stream_, stream_, k_new, v_new,
+                   new_fmt, false, &ds);
+  if (st != TTKV_OK) return st;
+  if (sel_blocks_out) {   // for the caller's information, behind the attention; valid once `stream` has drained
+    TTKV_HIP(h, hipMemcpyAsync(sel_count_out, sel_out, (size_t)c->batch * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    TTKV_HIP(h, hipMemcpyAsync(sel_blocks_out, sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
+                               hipMemcpyDeviceToHost, stream));
+  }
   return TTKV_OK;
 }
 

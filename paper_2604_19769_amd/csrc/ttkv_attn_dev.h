@@ -111,6 +111,21 @@ __device__ __forceinline__ float group_sum(float v) {
   if constexpr (LPT >= 16) v += dpp<0x140>(v);  // row_mirror: lane i <- lane 15-i = the other half's sum
   return v;
 }
+// A run whose blocks are named by the device-side selection: item `chunk` of the run is sub-chunk chunk % ipb of
+// the run's (chunk / ipb)-th selected block.  The entry is rewritten into a run over that one block, so that
+// everything after it sees an ordinary run.  Only the tier's newest block can be partly filled.
+__device__ __forceinline__ void resolve_selected(const FusedArgs &a, const TierView &tv, Entry &en, int seq, int chunk_tokens,
+                                                 int &chunk) {
+  if (!(en.tier_seq & (1 << 25))) return;
+  const int ipb = (tv.bt + chunk_tokens - 1) / chunk_tokens;
+  const int blk = chunk / ipb;
+  chunk -= blk * ipb;
+  const int32_t id = a.sel_ids[en.rec_base + blk];
+  en.len = id == en.first_tok ? a.sel_last_ntok[seq] : tv.bt;
+  en.first_tok = (id % tv.ring_blocks) * tv.bt;
+  en.rec_base = seq * tv.ring_blocks;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp<0xB1>(v));
   v = fmaxf(v, dpp<0x4E>(v));

@@ -775,12 +775,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
     const int mid = (lo + hi + 1) >> 1;
     if (a.e[mid].item_start <= item) lo = mid; else hi = mid - 1;
   }
-  const Entry en = a.e[lo];
+  Entry en = a.e[lo];
   const int tier = (en.tier_seq >> 16) & 0xff, seq = en.tier_seq & 0xffff;
   TierView tv = a.tv[tier];
-  if (en.tier_seq >> 24) tv.table = nullptr;   // the run names pool records directly
+  if (en.tier_seq & (1 << 24)) tv.table = nullptr;   // the run names pool records directly
   const int chunk_tokens = a.chunk[tier];
-  const int chunk = item - en.item_start;
+  const int part = en.part_base + item - en.item_start;   // this item's partial
+  int chunk = item - en.item_start;
+  resolve_selected(a, tv, en, seq, chunk_tokens, chunk);
 
   const int combo = tv.k_fmt * 8 + tv.v_fmt;
 #define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hq0, G, hkv, s_buf, s_m, s_l)
@@ -804,7 +806,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   __syncthreads();
 
   // ---- merge the four waves (each with its own running max) and write the item's partials
-  const int part = en.part_base + chunk;
   for (int idx = threadIdx.x; idx < G * 128; idx += 256) {
     const int g = idx >> 7, dch = idx & 127;
     const float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));

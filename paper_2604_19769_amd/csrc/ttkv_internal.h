@@ -136,6 +136,8 @@ hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels);
 #define TTKV_MAX_ENTRIES 120
 struct Entry {
   int32_t tier_seq;     // bit 24: ignore the block table (rec_base is a pool record); bits 16-23 tier; low 16 sequence
+                        // bit 25: the run is `len` blocks named by the device-side selection: rec_base = index of
+                        // its first id in FusedArgs::sel_ids, first_tok = id of the tier's newest live block
   int32_t rec_base;     // record of ring block 0 (no table) or of the run's first block
   int32_t first_tok;    // ring token index of the run's first token (multiple of 64)
   int32_t len;          // tokens
@@ -154,7 +156,10 @@ struct FusedArgs {
   int32_t Hq, Hkv;
   float scale;
   int32_t mfma_heads;   // set by the matrix-core launcher: query heads one workgroup serves
+  const int32_t *sel_ids;                    // device: block ids (Eq. 1) chosen by the top-k kernel, for runs with bit 25
+  int32_t sel_last_ntok[TTKV_MAX_BATCH];     // live tokens in the newest block of the selected tier, per sequence
 };
+static_assert(sizeof(FusedArgs) <= 4096, "kernel arguments are passed by value");
 hipError_t launch_attn(const FusedArgs &a, hipStream_t s, int *n_kernels, int *n_mfma);
 bool attn_supported(int k_fmt, int v_fmt, int G);
 int attn_group_width(int Gtot);

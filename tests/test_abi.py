@@ -108,6 +108,13 @@ def test_invalid_arguments_are_status_codes():
                               None, None) == B.ERR_WORKSPACE
     assert lens.tolist() == [5, 5]
     lens[:] = 0
+    # identify + top-k + attend in one call: no mean keys on the last tier, half a pair of output pointers
+    topk_tail = (dummy, None, 4, None, None, 4, dummy, 1 << 16, dummy, 1 << 20, None)
+    assert L.ttkv_decode_step_topk(h, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, *topk_tail) == B.ERR_UNSUPPORTED
+    assert L.ttkv_decode_step_topk(None, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, *topk_tail) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_step_topk(h, C.byref(c), dummy, B.F16, dummy, None, B.F16, *topk_tail) == B.ERR_INVALID_ARG
+    assert L.ttkv_decode_step_topk(h, C.byref(c), dummy, B.F16, dummy, dummy, B.F16, dummy, None, 4, dummy, None, 4, dummy,
+                                   1 << 16, dummy, 1 << 20, None) == B.ERR_INVALID_ARG
     # a paged host tier written by the kernels needs the device copy of its block table
     tbl = np.arange(16, dtype=np.int32)
     c.tier[2].mem, c.tier[2].block_table = B.MEM_HOST_PINNED, tbl.ctypes.data
