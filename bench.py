@@ -708,6 +708,20 @@ def main():
     roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
     roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
     lat = step_latencies(cache, q, kn, vn, W + K, L)
+    # the attention launch eight times back to back between one event pair, eight samples: the pair's own cost
+    # (dispatch of the markers, a few microseconds) spread over eight launches
+    B.ttkv_time_attn_repeat(cache.h, 8)
+    B.ttkv_time_attn(cache.h, 8)
+    for i in range(8):
+        cache.decode(q[i])
+    B.ttkv_time_attn(cache.h, 0)
+    B.ttkv_time_attn_repeat(cache.h, 1)
+    b2b = B.ttkv_read_attn_timing(cache.h)
+    b2b_ms = sum(b2b) / len(b2b)
+    b2b_bytes = algorithmic_bytes(cache)[0]
+    roofline["kernel_us_back_to_back"] = round(b2b_ms * 1e3, 2)
+    roofline["achieved_back_to_back"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9, 1)
+    roofline["frac_back_to_back"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     same = measure_hbm_read_same_size(cache.h, int(k_bytes))
     roofline["load_only_same_bytes_us"] = round(same * 1e6, 2)
     roofline["frac_of_load_only_same_bytes"] = round(same / (kms * 1e-3), 4)

@@ -276,6 +276,11 @@ ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q
  * finished, writes their durations in milliseconds (oldest first, at most
  * `capacity`), returns the count in *n_out and clears the samples. */
 ttkv_status ttkv_time_attn(ttkv_handle h, int32_t max_samples);
+/* Measurement aid: a timed call issues its attention launch(es) `repeat` times (1..64) back to back between
+ * the two events -- same arguments, the same partials written again -- and its sample is the duration
+ * divided by `repeat`, so that the event pair's own cost (a few microseconds per sample) is spread over
+ * several launches.  1 restores the single launch.  Calls that are not timed are unaffected. */
+ttkv_status ttkv_time_attn_repeat(ttkv_handle h, int32_t repeat);
 /* Measurement aid: enqueue a load-only kernel that streams `bytes` (rounded down to a
  * multiple of 64 KiB) of [device] memory at `src` with the attention kernels' access
  * pattern (128-bit loads, eight in flight per lane, four wave64 per workgroup).  Timed by

@@ -47,7 +47,7 @@ EXPORTS = [
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
     "ttkv_decode_step", "ttkv_decode_step_topk",
-    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_read_attn_timing", "ttkv_set_split",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_time_attn_repeat", "ttkv_read_attn_timing", "ttkv_set_split",
     "ttkv_stream_read",
 ]
 
@@ -98,6 +98,7 @@ def lib():
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
         L.ttkv_select_blocks.argtypes = [p, cp, p, i32, i32, p, p, i32, p, sz, p]
         L.ttkv_time_attn.argtypes = [p, i32]
+        L.ttkv_time_attn_repeat.argtypes = [p, i32]
         L.ttkv_stream_read.argtypes = [p, p, sz, p, p]
         L.ttkv_read_attn_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
         for name in EXPORTS:
@@ -232,6 +233,10 @@ def ttkv_select_blocks(h, cache, q, q_fmt, k, sel_blocks, sel_count, sel_stride,
 
 def ttkv_time_attn(h, max_samples):
     _check(lib().ttkv_time_attn(h, max_samples), "ttkv_time_attn")
+
+
+def ttkv_time_attn_repeat(h, repeat):
+    _check(lib().ttkv_time_attn_repeat(h, repeat), "ttkv_time_attn_repeat")
 
 
 def ttkv_read_attn_timing(h, capacity=4096):

@@ -84,6 +84,8 @@ struct Handle {
   int target_items;     // split-K granularity of the fused launch
   int time_max, time_n;
   hipEvent_t *time_ev;  // 2 * time_max events
+  int32_t *time_reps;   // launches between the events of each sample
+  int time_repeat;      // how often a timed call issues its attention launch(es)
 };
 
 #define TTKV_HIP(h, expr)                                   \
