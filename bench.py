@@ -706,7 +706,6 @@ def main():
                 "kernel_us": round(kms * 1e3, 2), "bytes_per_launch": int(k_bytes), "launches_timed": len(kernel_ms)}
     hbm_read = measure_hbm_read_peak(cache.h)
     roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
-    roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
     lat = step_latencies(cache, q, kn, vn, W + K, L)
     # the attention launch eight times back to back between one event pair, eight samples: the pair's own cost
     # (dispatch of the markers, a few microseconds) spread over eight launches
@@ -719,12 +718,19 @@ def main():
     b2b = B.ttkv_read_attn_timing(cache.h)
     b2b_ms = sum(b2b) / len(b2b)
     b2b_bytes = algorithmic_bytes(cache)[0]
-    roofline["kernel_us_back_to_back"] = round(b2b_ms * 1e3, 2)
-    roofline["achieved_back_to_back"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9, 1)
-    roofline["frac_back_to_back"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    # the headline figures of the object are the back-to-back ones (they agree with rocprofv3's duration of the
+    # kernel); the single pair inside the timed region, which also spans the dispatch of its two markers, stays beside
+    roofline["kernel_us_single_pair_in_timed_region"] = roofline["kernel_us"]
+    roofline["achieved_single_pair_in_timed_region"] = roofline["achieved"]
+    roofline["kernel_us"] = round(b2b_ms * 1e3, 2)
+    roofline["bytes_per_launch"] = int(b2b_bytes)
+    roofline["achieved"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9, 1)
+    roofline["frac"] = round(b2b_bytes / (b2b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    roofline["launches_timed"] = 8 * len(b2b)
+    roofline["frac_of_load_only_kernel"] = round(roofline["achieved"] / hbm_read, 4)
     same = measure_hbm_read_same_size(cache.h, int(k_bytes))
     roofline["load_only_same_bytes_us"] = round(same * 1e6, 2)
-    roofline["frac_of_load_only_same_bytes"] = round(same / (kms * 1e-3), 4)
+    roofline["frac_of_load_only_same_bytes"] = round(same / (kms * 1e-3), 4)   # both with a single event pair per launch
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_mha32k(kv, steps_in, shape, keep[:min(len(keep), 24)])   # the warm-up steps: ~0.1 s of oracle each
