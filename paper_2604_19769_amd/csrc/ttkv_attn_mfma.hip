@@ -680,8 +680,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       compute_tiles(ra, c1 - i0, std::false_type{}, []() {});
     }
   };
-  // Records in pinned host memory keep the register loads: over PCIe the copies through LDS are 3-4 % slower
-  // (measured), and the streaming hint has nothing to gain there.
+  // int8-key records in pinned host memory keep the register loads: over PCIe the copies through LDS are 3-4 %
+  // slower for them (measured), and the streaming hint has nothing to gain there.
   if constexpr (PF) {
     if (!tv.in_host) {
       // While batch i is computed the copies of batch i + 1 are in flight: its K half is issued once batch i's K
@@ -712,12 +712,10 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     }
   } else if constexpr (PF2) {
     static_assert(!PF2 || (TT == 32 && NT == 2 && NLK == 4 && NLV == 4), "the batch the LDS readers cover");
-    if (!tv.in_host) {
-      TileRegs ra;
-      fp_loop(ra);
-    } else {
-      register_loop();
-    }
+    // also for a tier in pinned host memory: the copies read whole 256-byte rows, where the register loads ask
+    // for 64 bytes of a row per instruction -- over PCIe 55.7 against 42.8 GB/s (measured)
+    TileRegs ra;
+    fp_loop(ra);
   } else {
     register_loop();
   }
