@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "ablation"])
+    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "ablation", "grid"])
     ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offload-steps", type=int, default=20)
@@ -567,6 +567,50 @@ def run_key_grouping(steps=12):
                         "int4 groupings; error = attention output vs the all-fp16 cache", "rows": rows}
 
 
+# ------------------------------------------------------------------ workload: formats x head groupings in HBM
+
+def run_grid():
+    """One HBM-resident tier of ~560 MB (plus a 256-token fp16 window for the quantized ones), batch 4, every stored
+    format against head groupings from multi-head to multi-query: attention launch issued four times back to back
+    between one event pair, median of six samples.  Effective TB/s of stored bytes; which kernel served it."""
+    import torch
+    from paper_2604_19769_amd import binding as B
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 9)
+    per = {("f16", "f16"): 512, ("i8", "i8"): 272, ("i8", "i4"): 208, ("i4", "i4"): 144}
+    rows = []
+    for Hq, Hkv in ((32, 32), (32, 16), (24, 8), (32, 8), (48, 8), (64, 8), (64, 4), (64, 2)):
+        row = {"q_heads": Hq, "kv_heads": Hkv}
+        for (kf, vf), bytes_per in per.items():
+            N = int(560e6 / (4 * Hkv * bytes_per)) // 256 * 256
+            tiers = [TierConfig(kf, vf, 10**9, 128, N // 128 + 2)] if kf == "f16" else \
+                    [TierConfig("f16", "f16", 256, 128, 3), TierConfig(kf, vf, 10**9, 128, N // 128 + 2)]
+            cache = TieredCache(4, Hq, Hkv, tiers)
+            K = device_normal(gen, (4, Hkv, N, 128), torch.float16)
+            V = device_normal(gen, (4, Hkv, N, 128), torch.float16)
+            cache.append(len(tiers) - 1, K, V, through_tiers=True)
+            del K, V
+            q = device_normal(gen, (4, 4, Hq, 128), torch.float16)
+            total, _ = algorithmic_bytes(cache)
+            for _ in range(3):
+                cache.decode(q[0])
+            B.ttkv_time_attn_repeat(cache.h, 4)
+            B.ttkv_time_attn(cache.h, 6)
+            for i in range(6):
+                cache.decode(q[i % 4])
+            B.ttkv_time_attn(cache.h, 0)
+            B.ttkv_time_attn_repeat(cache.h, 1)
+            ms = sorted(B.ttkv_read_attn_timing(cache.h))
+            row[f"K {kf} / V {vf}"] = {"TBs": round(total / ms[3] / 1e9, 2),
+                                      "kernel": "matrix-core" if cache.stats()["mfma_launches"] else "vector"}
+            cache.close()
+            del cache
+        rows.append(row)
+    return {"workload": "one HBM-resident tier of ~560 MB, batch 4; attention launch x4 back to back per sample", "rows": rows}
+
+
 # ------------------------------------------------------------------ workload: ablation variants (Sec. 5.4, Table 6)
 
 def run_ablation(steps, warmup):
@@ -664,6 +708,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload == "grid":
+        r = run_grid()
+        best = max(v["TBs"] for row in r["rows"] for k, v in row.items() if isinstance(v, dict))
+        line = {"metric": "decode-attn effective KV TB/s by stored format and head grouping (HBM-resident)", "value": best,
+                "unit": "TB/s", "n_gpus": 1, "steps": 24, "warmup": 3, "ms_per_step": None, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f16/int8/int4 -> f32", "data": "synthetic",
+                "config": {"workload": "grid: " + r["workload"]}, "grid": r}
+        print(json.dumps(line))
+        return
     if args.workload == "ablation":
         r = run_ablation(K, W)
         ttkv = [x for x in r["rows"] if x["variant"].startswith("TTKV")][0]
