@@ -261,20 +261,85 @@ def test_selection_properties():
     assert np.array_equal(dense, every)
     none, lse = c.attend(q, c.select(q, 0))               # k = 0 and empty tier 0: nothing attended
     assert np.all(none == 0) and np.all(lse == -np.inf)
-    # summary is the mean key of the block (fp16 of an fp32 mean)
-    mu = O.f16_bits_to_f32(c.summaries(0)[5])
-    ref = c_block_mean(c, 5)
-    assert np.max(np.abs(mu - ref)) <= np.abs(ref).max() * 2.0 ** -10 + 1e-6
     # ties go to the lower index
     assert O.topk(np.array([1, 5, 5, 0, 5], np.float32), 2).tolist() == [1, 2]
     assert O.topk(np.array([2, 2, 2], np.float32), 2).tolist() == [0, 1]
 
 
-def c_block_mean(c, blk):
-    # the host tier's quantizer saw the raw keys (tier index 1 is reached directly)
-    s = c.seq[1][0]
-    # decompressed values differ from the inputs by at most half a step; use the summary's own inputs instead:
-    return s.ksum[blk] / 64.0
+def token_order_mean_bits(K, lo, hi, block_tokens):
+    """fp16 bits of (fp32 sum of K[:, lo:hi] in token order) * (1 / block_tokens): the mean key as Alg. 1's
+    identification step reads it, written out with numpy (each `+` below is one IEEE fp32 addition per element)."""
+    s = np.zeros((K.shape[0], K.shape[2]), np.float32)
+    for t in range(lo, hi):
+        s = s + K[:, t]
+    return (s * np.float32(1.0 / block_tokens)).astype(np.float16).view(np.uint16)
+
+
+def test_summary_accumulate_token_range_and_head_stride():
+    """The accumulator adds exactly tokens [t0, t0 + n) of every head, in token order, to what it held."""
+    rng = np.random.default_rng(23)
+    x = rand(rng, 3, 50, 128)                                  # 3 KV heads, 50 tokens held (stride 50)
+    for t0, n in ((0, 50), (7, 1), (7, 0), (13, 29), (49, 1)):
+        acc = rng.standard_normal((3, 128)).astype(np.float32)
+        want = acc.copy()
+        for t in range(t0, t0 + n):
+            want = want + x[:, t]
+        O.summary_accumulate(acc, x, t0, n)
+        assert np.array_equal(acc, want), (t0, n)
+    # integer-valued keys: every partial sum is exact, so the result is the exact sum whatever the order
+    xi = rng.integers(-8, 9, (2, 40, 128)).astype(np.float32)
+    acc = np.zeros((2, 128), np.float32)
+    O.summary_accumulate(acc, xi, 5, 30)
+    assert np.array_equal(acc, xi[:, 5:35].sum(1))
+    # one token off at either end, or the other head's rows, is a different number
+    assert not np.array_equal(acc, xi[:, 4:34].sum(1)) and not np.array_equal(acc, xi[:, 5:36].sum(1))
+    assert not np.array_equal(acc[0], xi[1, 5:35].sum(0))
+
+
+@pytest.mark.parametrize("pieces", [[768], [40, 100, 300, 328], [64, 64, 1, 63, 200, 376], [1] * 70 + [698]])
+def test_block_summaries_are_token_order_means_of_the_keys(pieces):
+    """Mean keys of a tier fed by appends that straddle block boundaries, fill a block in several calls, or
+    stop inside a block: each equals the token-order fp32 mean of that block's keys, bit for bit, for both KV
+    heads; a partly filled newest block divides by B_blk as well."""
+    rng = np.random.default_rng(24)
+    bt, N = 64, sum(pieces) - 24                               # the last block holds 40 of 64 tokens
+    pieces = pieces[:-1] + [pieces[-1] - 24]
+    c = OracleCache(1, 8, 2, 128, [TierSpec("f16", "f16", 32, 16), TierSpec("i4", "i4", 10**9, bt, mem="host", summary=True)], 2048)
+    K, V = rand(rng, 2, N, 128), rand(rng, 2, N, 128)
+    o = 0
+    for n in pieces:
+        c.append(1, 0, K[:, o:o + n], V[:, o:o + n], o)
+        o += n
+    c.total[0] = N
+    mu = c.summaries(0)
+    assert sorted(mu) == list(range((N + bt - 1) // bt))
+    for j in mu:
+        want = token_order_mean_bits(K, j * bt, min(N, (j + 1) * bt), bt)
+        assert np.array_equal(mu[j], want), j
+        # and it is the mean key: within fp16 rounding + fp32 summation error of the fp64 mean
+        ref = K[:, j * bt:min(N, (j + 1) * bt)].astype(np.float64).sum(1) / bt
+        assert np.max(np.abs(O.f16_bits_to_f32(mu[j]) - ref)) <= np.abs(ref).max() * 2.0 ** -10 + 1e-5
+
+
+def test_block_summaries_after_eviction_are_means_of_what_the_quantizer_received():
+    """Blocks that reach the summarised tier by eviction (Alg. 1, evict & compress) out of an fp16 tier with a
+    smaller block: the mean is over the values that entered that tier's quantizer (the stored fp16 keys), in
+    token order, several evictions filling one block."""
+    rng = np.random.default_rng(25)
+    tiers = [TierSpec("f16", "f16", 64, 32), TierSpec("i4", "i4", 10**9, 128, mem="host", summary=True)]
+    c = OracleCache(1, 4, 2, 128, tiers, [2048, 2048])
+    ks = []
+    for _ in range(500):
+        q, k, v = rand(rng, 1, 4, 128), rand(rng, 1, 2, 128), rand(rng, 1, 2, 128)
+        ks.append(k[0])
+        c.step(q, k, v)
+    K = np.stack(ks, 1)                                         # [Hkv][500][128]
+    n1 = c.seq[1][0].count
+    assert n1 == 448 and c.seq[1][0].first == 0                 # 14 evictions of 32 tokens
+    mu = c.summaries(0)
+    assert sorted(mu) == [0, 1, 2, 3]
+    for j in mu:
+        assert np.array_equal(mu[j], token_order_mean_bits(K, j * 128, min(n1, (j + 1) * 128), 128)), j
 
 
 def test_block_score_is_the_plain_dot_product():
