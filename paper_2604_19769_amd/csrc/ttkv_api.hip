@@ -94,30 +94,6 @@ int copy_granule(int64_t rec_bytes) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(64, g));
 }
 
-// One run of consecutive tokens of one (tier, sequence) attended by the fused
-// kernel in place: a device tier, a host tier read over PCIe by the kernel itself,
-// or a run of selected blocks.
-struct Run {
-  int tier, b;
-  int32_t rec_base, first_tok, len;
-  bool no_table;
-  bool selected;   // `len` blocks named by the device-side selection (rec_base: index of the first id, first_tok: newest block id)
-  int part_base, n_chunks;
-};
-// Selection left on the device by the top-k kernel: ids [batch][stride], min(k, live blocks) of them per sequence.
-struct DevSel {
-  const int32_t *ids;
-  int32_t k, stride;
-};
-// One staged copy: consecutive pool records of a host tier brought into a slot.
-struct Fetch {
-  int tier, b;
-  int64_t rec;     // first pool record
-  int nrec;        // consecutive records in this copy
-  int ntok;        // live tokens covered
-  int part_base;
-  int chunk;
-};
 // Default split-K granularity, in workgroups resident at once on 256 CUs: 2.5 rounds of 4 per CU for the vector
 // kernel (flat between 1 and 3 rounds, measured), exactly one round of 3 per CU for the grouped-query matrix-core
 // kernel (int4: 5.1 TB/s against 4.4-4.7 with two rounds; the other formats are indifferent).
@@ -134,16 +110,6 @@ int default_items(const ttkv_cache *c) {
     if (G > 8 && c->tier[t].k_fmt == TTKV_I4_ASYM_G64) return 512;   // that case runs 2 workgroups per CU
   return 768;
 }
-
-struct Plan {
-  std::vector<Run> runs;
-  std::vector<Fetch> fetch;
-  int chunk[TTKV_MAX_TIERS];
-  int parts[TTKV_MAX_BATCH];
-  int max_parts;
-  size_t slot_bytes;
-  ttkv_status status;
-};
 
 // Tokens per work item of tier t so that every item of the fused launch streams
 // about the same number of bytes: total bytes of the in-place tiers / target_items.
@@ -170,6 +136,9 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
                 int target_items, Plan *P, const DevSel *ds = nullptr) {
   P->status = TTKV_OK;
   P->slot_bytes = 0;
+  P->max_parts = 0;
+  P->runs.clear();
+  P->fetch.clear();
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
   const int last = c->n_tiers - 1;
   for (int t = 0; t < c->n_tiers; ++t) {
@@ -449,6 +418,14 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   if (!out) return TTKV_ERR_INVALID_ARG;
   Handle *h = new (std::nothrow) Handle();
   if (!h) return TTKV_ERR_INVALID_ARG;
+  try {
+    h->plan.runs.reserve(TTKV_PLAN_RESERVE);
+    h->plan.fetch.reserve(TTKV_PLAN_RESERVE);
+    h->plan.order.reserve(TTKV_PLAN_RESERVE);
+  } catch (...) {
+    delete h;
+    return TTKV_ERR_INVALID_ARG;
+  }
   h->have_events = false;
   h->target_items = 0;
   h->time_on = false;
@@ -560,7 +537,7 @@ int32_t ttkv_count_parts(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel
                          int32_t sel_stride, int32_t n_slots) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
-  Plan P;
+  Plan &P = h->plan;
   build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items ? h->target_items : default_items(c), &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
 }
@@ -706,7 +683,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   hipStream_t compute = (hipStream_t)compute_, copy = (hipStream_t)copy_;
   const bool staged = n_slots > 0;
 
-  Plan P;
+  Plan &P = h->plan;
   build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items ? h->target_items : default_items(c), &P, ds);
   if (P.status != TTKV_OK) return P.status;
   if (!workspace) return TTKV_ERR_WORKSPACE;
@@ -758,8 +735,8 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
   // launch order: runs of host tiers first, so that the PCIe stream starts with the first workgroups
   // and the device-tier items fill the remaining slots while it runs
-  std::vector<const Run *> order;
-  order.reserve(P.runs.size());
+  std::vector<const Run *> &order = P.order;
+  order.clear();
   for (int pass = 0; pass < 2; ++pass)
     for (const Run &r : P.runs)
       if ((c->tier[r.tier].mem == TTKV_MEM_HOST_PINNED) == (pass == 0)) order.push_back(&r);

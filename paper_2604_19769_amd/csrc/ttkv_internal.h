@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <vector>
+
 #include "ttkv.h"
 
 namespace ttkv {
@@ -70,8 +72,48 @@ struct SeqTable {
   int32_t part_base[TTKV_MAX_BATCH];    // first partial index this launch writes for the entry
 };
 
+// ---------------------------------------------------------------- the split-K plan of one attention call
+// One run of consecutive tokens of one (tier, sequence) attended by the fused
+// kernel in place: a device tier, a host tier read over PCIe by the kernel itself,
+// or a run of selected blocks.
+struct Run {
+  int tier, b;
+  int32_t rec_base, first_tok, len;
+  bool no_table;
+  bool selected;   // `len` blocks named by the device-side selection (rec_base: index of the first id, first_tok: newest block id)
+  int part_base, n_chunks;
+};
+// Selection left on the device by the top-k kernel: ids [batch][stride], min(k, live blocks) of them per sequence.
+struct DevSel {
+  const int32_t *ids;
+  int32_t k, stride;
+};
+// One staged copy: consecutive pool records of a host tier brought into a slot.
+struct Fetch {
+  int tier, b;
+  int64_t rec;     // first pool record
+  int nrec;        // consecutive records in this copy
+  int ntok;        // live tokens covered
+  int part_base;
+  int chunk;
+};
+// Lives in the handle and is rebuilt by every call: the vectors keep their storage, so a call allocates host
+// memory only when its plan is larger than any before it (ttkv_create reserves TTKV_PLAN_RESERVE entries).
+#define TTKV_PLAN_RESERVE 4096
+struct Plan {
+  std::vector<Run> runs;
+  std::vector<Fetch> fetch;
+  std::vector<const Run *> order;   // launch order of `runs`
+  int chunk[TTKV_MAX_TIERS];
+  int parts[TTKV_MAX_BATCH];
+  int max_parts;
+  size_t slot_bytes;
+  ttkv_status status;
+};
+
 // ---------------------------------------------------------------- handle
 struct Handle {
+  Plan plan;
   int device;
   bool have_events;
   hipEvent_t ready[TTKV_MAX_SLOTS];

@@ -56,25 +56,51 @@ def compare_codes(cache, ora, b, heads, fmts):
                 assert np.array_equal(meta[:, :, 0::2], q["scale"][:, sl]) and np.array_equal(meta[:, :, 1::2], q["zero"][:, sl]), (t, name)
 
 
-def test_mha32k_full_size_sampled_heads():
-    """BASELINE config 2: batch 4, 32 heads, 32K tokens, 2K fp16 + 30K int4 in HBM, append + attend + evict."""
+def compare_codes_of(cache, ora, b, heads, fmts):
+    """compare_codes for an oracle that holds the whole batch and every head: view of sequence b, heads `heads`."""
+    class _View:
+        pass
+    v = _View()
+    v.seq = []
+    for t in range(len(fmts)):
+        s, w = ora.seq[t][b], _View()
+        w.count, w.first = s.count, s.first
+        w.khat, w.vhat = s.khat[heads], s.vhat[heads]
+        w.kq = None if s.kq is None else {k: a[heads] for k, a in s.kq.items()}
+        w.vq = None if s.vq is None else {k: a[heads] for k, a in s.vq.items()}
+        v.seq.append([w])
+    compare_codes(cache, v, b, heads, fmts)
+
+
+def test_mha32k_full_size_every_head():
+    """BASELINE config 2: batch 4, 32 heads, 32K tokens, 2K fp16 + 30K int4 in HBM, append + attend + evict.
+    The oracle holds the whole workload: every (sequence, head) row of every step is compared, element-wise and
+    relative to the largest output (on N(0,1) data at 32K tokens the outputs are ~5e-3, so the absolute term of
+    the element-wise tolerance alone would be most of the signal)."""
     steps = 3
     cache, (K, V), (q, kn, vn), shape = bench.build_mha32k(steps)
     try:
-        b, heads = 2, [5, 30]
+        B_, H = shape["B"], shape["Hq"]
         tiers = [TierSpec("f16", "f16", shape["R"], shape["bt"]), TierSpec("i4", "i4", 10**9, shape["bt"])]
-        ora = sample_oracle(tiers, 32, 32, heads, K[b], V[b], [shape["R"] + 256, shape["N"] + 256])
-        compare_codes(cache, ora, b, heads, [("f16", "f16"), ("i4", "i4")])
+        ora = OracleCache(B_, H, H, 128, tiers, [shape["R"] + 256, shape["N"] + 256])
+        for b in range(B_):
+            ora.load(b, K[b].float().cpu().numpy(), V[b].float().cpu().numpy())
+        code_checks = [(0, [0, 31]), (2, [5, 30])]                      # (sequence, heads) whose stored bytes are compared
+        for b, heads in code_checks:
+            compare_codes_of(cache, ora, b, heads, [("f16", "f16"), ("i4", "i4")])
         for s in range(steps):
             out, lse = cache.step(q[s], kn[s], vn[s])
             torch.cuda.synchronize()
-            ro, rl = ora.step(q[s, b][heads][None].float().cpu().numpy(), kn[s, b, heads, 0][None].float().cpu().numpy(),
-                              vn[s, b, heads, 0][None].float().cpu().numpy())
-            assert_close(out[b, heads].cpu().numpy(), ro[0], f"out step {s}")
-            assert_close(lse[b, heads].cpu().numpy(), rl[0], f"lse step {s}")
-        compare_codes(cache, ora, b, heads, [("f16", "f16"), ("i4", "i4")])
-        assert cache.stats()["demotions"] == 4 and int(cache.len[0][b]) == shape["R"] - shape["bt"] + steps - 1
-        # outputs of every row are finite and each lse exceeds that of the fp16 tier alone (more tokens, more mass)
+            ro, rl = ora.step(q[s].float().cpu().numpy(), kn[s, :, :, 0].float().cpu().numpy(), vn[s, :, :, 0].float().cpu().numpy())
+            g = out.cpu().numpy()
+            assert_close(g, ro, f"out step {s}")
+            assert_close(lse.cpu().numpy(), rl, f"lse step {s}")
+            for b in range(B_):                                        # per row: no head may hide behind another's scale
+                rel = np.max(np.abs(g[b] - ro[b]), axis=1) / np.max(np.abs(ro[b]), axis=1)
+                assert rel.max() < 2e-3, (s, b, int(rel.argmax()), float(rel.max()))
+        for b, heads in code_checks:
+            compare_codes_of(cache, ora, b, heads, [("f16", "f16"), ("i4", "i4")])
+        assert cache.stats()["demotions"] == 4 and int(cache.len[0][2]) == shape["R"] - shape["bt"] + steps - 1
         assert torch.isfinite(out).all() and torch.isfinite(lse).all()
     finally:
         cache.close()

@@ -10,8 +10,10 @@ from paper_2604_19769_amd.cache import TierConfig, TieredCache
 
 TORCH_DT = {"f16": torch.float16, "bf16": torch.bfloat16}
 
-# |gpu - oracle| <= ABS_TOL + REL_TOL * |oracle|, element-wise, on fp32-accumulated outputs
-ABS_TOL, REL_TOL = 2e-3, 1e-2
+# |gpu - oracle| <= ABS_TOL + REL_TOL * |oracle|, element-wise, on fp32-accumulated outputs; and, because on
+# N(0,1) data over thousands of tokens the outputs are only ~1e-2 and the absolute term alone would be most of
+# the signal, max|gpu - oracle| <= NORM_TOL * max|oracle| as well
+ABS_TOL, REL_TOL, NORM_TOL = 2e-3, 1e-2, 2e-3
 
 
 def dev(x, dtype, device="cuda:0"):
@@ -109,4 +111,7 @@ def assert_close(gpu, ora, what=""):
     err = np.abs(gpu[fin] - ora[fin])
     lim = ABS_TOL + REL_TOL * np.abs(ora[fin])
     assert np.all(err <= lim), f"{what}: max err {err.max():.3e} (max |ref| {np.abs(ora[fin]).max():.3e}, worst ratio {(err / lim).max():.3f})"
-    return float(err.max())
+    if err.size:
+        top = np.abs(ora[fin]).max()
+        assert err.max() <= NORM_TOL * top + 1e-6, f"{what}: max err {err.max():.3e} against max |ref| {top:.3e}: normalised {err.max() / max(top, 1e-30):.2e}"
+    return float(err.max()) if err.size else 0.0
