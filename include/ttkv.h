@@ -54,6 +54,7 @@ extern "C" {
 #define TTKV_MAX_BATCH 64
 #define TTKV_HEAD_DIM 128
 #define TTKV_MAX_SLOTS 16
+#define TTKV_NOALLOC_SCRATCH_BYTES (16u << 20) /* split partials of ttkv_decode_attn_noalloc, per GPU */
 
 typedef enum {
   TTKV_OK = 0,
@@ -212,6 +213,20 @@ ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int
 ttkv_status ttkv_decode_attn(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
                              float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
                              void *workspace, size_t ws_bytes, int32_t n_slots, void *compute, void *copy);
+
+/* ttkv_decode_attn for callers that cannot allocate or hand over device memory for the call: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results as ttkv_decode_attn with n_slots = 0 (host tiers read in place) and both streams = `stream`, but the
+ * split partials live in an array of TTKV_NOALLOC_SCRATCH_BYTES (16 MiB) that is part of the library's device
+ * code: each GPU the library runs on holds its own copy from the first call on it until the process ends.  The
+ * call allocates nothing on the device and calls no allocating routine.  WORKSPACE if the partials this cache
+ * needs right now, batch x n_q_heads x ttkv_count_parts(.., n_slots 0) x 520 bytes, exceed the array; nothing
+ * is enqueued then.  All calls on one GPU share that GPU's array: two calls whose kernels may overlap on one
+ * GPU (different streams, different threads) race; calls on one stream are ordered and safe.  Nothing in the
+ * array needs clearing between calls (every part the merge reads is written by the same call first). */
+ttkv_status ttkv_decode_attn_noalloc(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
+                                     float *lse, const int32_t *sel_blocks, const int32_t *sel_count,
+                                     int32_t sel_stride, void *stream);
 
 /* The "append" and "attend" lines of Alg. 1 for one decode step in one call: the step's new token
  * (k_new, v_new [device] [batch][n_kv_heads][128], new_fmt F16 or BF16) is appended to tier 0 of every

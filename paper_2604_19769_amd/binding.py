@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(HERE, "libttkv.so")
 TTKV_MAX_TIERS = 4
 TTKV_MAX_BATCH = 64
 TTKV_MAX_SLOTS = 16
+TTKV_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
 F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32, I4_ASYM_T128 = range(6)
@@ -46,7 +47,7 @@ EXPORTS = [
     "ttkv_create", "ttkv_destroy", "ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
-    "ttkv_decode_step", "ttkv_decode_step_topk",
+    "ttkv_decode_step", "ttkv_decode_step_topk", "ttkv_decode_attn_noalloc",
     "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_time_attn_repeat", "ttkv_read_attn_timing", "ttkv_set_split",
     "ttkv_stream_read",
 ]
@@ -93,6 +94,7 @@ def lib():
         L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
         L.ttkv_tier_demote.argtypes = [p, cp, i32, i32, p, sz, p, p]
         L.ttkv_decode_attn.argtypes = [p, cp, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
+        L.ttkv_decode_attn_noalloc.argtypes = [p, cp, p, i32, p, p, p, p, i32, p]
         L.ttkv_decode_step.argtypes = [p, cp, p, i32, p, p, i32, p, p, p, p, i32, p, sz, i32, p, p]
         L.ttkv_decode_step_topk.argtypes = [p, cp, p, i32, p, p, i32, p, p, i32, p, p, i32, p, sz, p, sz, p]
         L.ttkv_merge_partials.argtypes = [p, p, p, p, i32, i32, p, i32, p, p, p]
@@ -205,6 +207,11 @@ def ttkv_decode_attn(h, cache, q, q_fmt, out, lse, sel_blocks, sel_count, sel_st
     _check(lib().ttkv_decode_attn(h, C.byref(cache), _p(q), q_fmt, _p(out), _p(lse), _p(sel_blocks), _p(sel_count),
                                   sel_stride, _p(workspace), ws_bytes, n_slots, _p(compute), _p(copy)),
            "ttkv_decode_attn")
+
+
+def ttkv_decode_attn_noalloc(h, cache, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, stream):
+    _check(lib().ttkv_decode_attn_noalloc(h, C.byref(cache), _p(q), q_fmt, _p(out), _p(lse), _p(sel_blocks), _p(sel_count),
+                                          sel_stride, _p(stream)), "ttkv_decode_attn_noalloc")
 
 
 def ttkv_decode_step(h, cache, q, q_fmt, k_new, v_new, new_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace,

@@ -4,6 +4,7 @@
 #include "ttkv_internal.h"
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -841,6 +842,43 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   if (!h) return TTKV_ERR_INVALID_ARG;
   return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute,
                      copy, nullptr, nullptr, 0);
+}
+
+// Split partials of ttkv_decode_attn_noalloc: one array per GPU (every device that loads this code object holds
+// its own copy at its own address), held until the process ends.  The name is a host-side stand-in: host code
+// uses the address hipGetSymbolAddress returns for the current device, never the name.
+static __device__ __align__(256) unsigned char scratch[TTKV_NOALLOC_SCRATCH_BYTES];
+#define TTKV_MAX_DEVICES 64
+static void *g_scratch_ptr[TTKV_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's `scratch`, looked up once per device.
+static ttkv_status scratch_of_current_device(Handle *h, void **out) {
+  int dev = -1;
+  TTKV_HIP(h, hipGetDevice(&dev));
+  if (dev < 0 || dev >= TTKV_MAX_DEVICES) return TTKV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    TTKV_HIP(h, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return TTKV_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_decode_attn_noalloc(ttkv_handle hh, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out,
+                                     float *lse, const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride,
+                                     void *stream) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h) return TTKV_ERR_INVALID_ARG;
+  void *ws = nullptr;
+  ttkv_status st = scratch_of_current_device(h, &ws);   // a lookup; enqueues nothing
+  if (st != TTKV_OK) return st;
+  // the partials need no clearing: every part the merge reads is written by this call's attention launch first
+  return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, ws, TTKV_NOALLOC_SCRATCH_BYTES, 0, stream,
+                     stream, nullptr, nullptr, 0);
 }
 
 ttkv_status ttkv_decode_step(ttkv_handle hh, ttkv_cache *c, const void *q, int32_t q_fmt, const void *k_new,
