@@ -317,19 +317,27 @@ void o_summary_finish(const float *sum, int32_t n, int32_t block_tokens, uint16_
   for (int32_t i = 0; i < n; ++i) mu[i] = o_f32_to_f16(sum[i] * inv);
 }
 
-/* phi(q, B_j) = sum over query heads h (ascending) and channels i (ascending)
- * of q[h][i] * mu[h/G][i], accumulated left to right with fused multiply-add
- * in fp32 so that the value is one well-defined number. */
+/* phi(q, B_j) = sum over query heads h of (q_h . mu_{h/G}): each head's dot
+ * product is accumulated over the channels in ascending order with fused
+ * multiply-add in fp32, and the per-head dot products are then added in
+ * ascending head order in fp32, so that the value is one well-defined number
+ * (and every head's chain can run on its own lane). */
 float o_block_score(const float *q, const uint16_t *mu, int32_t Hq, int32_t Hkv, int32_t d) {
   const int32_t G = Hq / Hkv;
-  float s = 0.0f;
-  for (int32_t h = 0; h < Hq; ++h)
+  float phi = 0.0f;
+  for (int32_t h = 0; h < Hq; ++h) {
+    float s = 0.0f;
     for (int32_t i = 0; i < d; ++i) s = fmaf(q[h * d + i], o_f16_to_f32(mu[(h / G) * d + i]), s);
-  return s;
+    phi = phi + s;
+  }
+  return phi;
 }
 
 /* TopK: the k largest scores, ties to the lower block index; indices returned
- * ascending.  Returns the count written (min(k, n)). */
+ * ascending.  A NaN score (possible only with non-finite inputs, which are
+ * outside the method's contract) ranks as -infinity, so that the ranks stay a
+ * permutation and exactly min(k, n) blocks are chosen whatever the scores.
+ * Returns the count written (min(k, n)). */
 int32_t o_topk(const float *score, int32_t n, int32_t k, int32_t *sel) {
   if (k > n) k = n;
   if (k < 0) k = 0;
@@ -338,8 +346,14 @@ int32_t o_topk(const float *score, int32_t n, int32_t k, int32_t *sel) {
   memset(taken, 0, (size_t)n);
   for (int32_t r = 0; r < k; ++r) {
     int32_t best = -1;
-    for (int32_t j = 0; j < n; ++j)
-      if (!taken[j] && (best < 0 || score[j] > score[best])) best = j;
+    float best_s = 0.0f;
+    for (int32_t j = 0; j < n; ++j) {
+      const float sj = score[j] != score[j] ? -INFINITY : score[j];
+      if (!taken[j] && (best < 0 || sj > best_s)) {
+        best = j;
+        best_s = sj;
+      }
+    }
     taken[best] = 1;
   }
   int32_t c = 0;

@@ -351,6 +351,43 @@ def test_block_score_is_the_plain_dot_product():
     assert abs(got - ref) < 1e-4 * (1 + abs(ref))
 
 
+def test_block_score_order_free_cases_and_head_mapping():
+    """Integer-valued queries and mean keys: every product and partial sum is exact in fp32, so phi must be
+    the exact integer sum whatever the accumulation order; and query head h reads KV head h // G."""
+    rng = np.random.default_rng(26)
+    q = rng.integers(-4, 5, (8, 128)).astype(np.float32)
+    mu = rng.integers(-4, 5, (2, 128)).astype(np.float16)
+    want = sum(int(q[h].astype(np.int64) @ mu[h // 4].astype(np.int64)) for h in range(8))
+    assert O.block_score(q, mu.view(np.uint16), 2) == float(want)
+    wrong = sum(int(q[h].astype(np.int64) @ mu[h % 2].astype(np.int64)) for h in range(8))
+    assert wrong != want
+    # one head alone is the left-to-right fused chain over its channels (single rounding per step)
+    q1 = rand(rng, 1, 128)
+    m1 = rng.standard_normal((1, 128)).astype(np.float16)
+    s = 0.0
+    for i in range(128):       # exact product in fp64 (24 x 11 bits), one rounding of product + sum to fp32 = fmaf
+        s = float(np.float32(float(q1[0, i]) * float(m1[0, i]) + s))
+    assert O.block_score(q1, m1.view(np.uint16), 1) == s
+
+
+def test_topk_against_brute_force_including_nan_scores():
+    """The k chosen are exactly those with fewer than k blocks ahead of them (larger score, or equal score and
+    lower index); NaN counts as -inf; always min(k, n) ids, ascending."""
+    rng = np.random.default_rng(27)
+    for trial in range(200):
+        n = int(rng.integers(1, 40))
+        sc = rng.integers(-3, 4, n).astype(np.float32)           # many ties
+        if trial % 3 == 0:
+            sc[rng.integers(0, n, 2)] = np.nan
+        if trial % 5 == 0:
+            sc[rng.integers(0, n)] = -np.inf
+        k = int(rng.integers(0, n + 3))
+        key = np.where(np.isnan(sc), -np.inf, sc)
+        want = [j for j in range(n) if sum((key[i] > key[j]) or (key[i] == key[j] and i < j) for i in range(n)) < k]
+        got = O.topk(sc, k).tolist()
+        assert got == want and len(got) == min(k, n), (sc, k, got, want)
+
+
 def test_h2d_traffic_closed_form():
     # 128K offload shape: 96 records of 1024 tokens x 8 KV heads x 144 B = 1,179,648 B each
     c = OracleCache(1, 32, 8, 128, [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 128),
