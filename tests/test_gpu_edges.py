@@ -147,3 +147,32 @@ def test_randomized_layouts(seed):
                check_state_every=6, host_append_direct=bool(seed & 1), host_demote_direct=bool(seed & 2),
                one_call_step=bool(seed % 3))
 
+
+
+def test_selection_ids_with_non_finite_scores_and_more_than_64_heads():
+    """Block identification alone (ttkv_select_blocks): 72 query heads (two passes of 64 lanes) and queries that
+    hold +inf, so that scores are +-inf and NaN (inf x 0 where a block's mean key has a zero channel): the ids are
+    the oracle's (NaN ranks as -inf, ties to the lower id), and there are exactly min(k, live blocks) of them."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=128, block_tokens=64, ring_blocks=3),
+             dict(k_fmt="f16", v_fmt="f16", capacity=10**9, block_tokens=64, ring_blocks=40, summary=True)]
+    p = Pair(2, 72, 1, tiers, "f16")
+    try:
+        g = synth.rng(synth.SEED_BASE + 45)
+        for b, n in enumerate((127 + 64 * 20 + 10, 127 + 64 * 33)):
+            k, v = synth.kv((synth.SEED_BASE + 45) * 31 + b, 1, n, "f16")
+            k[:, 64 * 3:64 * 7, 5] = 0.0                     # blocks 3..6: channel 5 of the mean key is exactly zero
+            p.load(b, k, v)
+        for trial, kk in enumerate((5, 0, 21, 1000)):
+            q = synth.normal(g, (2, 72, 128), "f16")
+            if trial != 1:
+                q[:, 7, 5] = np.inf                          # head 7, channel 5
+            if trial == 2:
+                q[:, 70, 9] = -np.inf
+            want = p.ora.select(q, kk)
+            sb, sc = p.gpu.select(dev(q, "f16"), kk)
+            for b in range(2):
+                got = sb.numpy()[b, :int(sc.numpy()[b])]
+                assert np.array_equal(got, want[b]), (trial, b, got, want[b])
+                assert len(got) == min(kk, len(p.ora.live_blocks(1, b)))
+    finally:
+        p.close()
