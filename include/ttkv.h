@@ -137,7 +137,7 @@ ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *ti
 
 /* [device] workspace ttkv_decode_attn needs for this cache: split partials for
  * up to max_parts parts per (sequence, query head) plus n_slots staging slots, each
- * holding the largest run of adjacent host-tier records one copy moves (up to 8 MiB).  ttkv_tier_demote needs batch records of its
+ * holding the largest run of adjacent host-tier records one copy moves (up to 32 MiB or 64 records).  ttkv_tier_demote needs batch records of its
  * destination tier when that is a host tier (always covered when n_slots >= batch,
  * else use ttkv_demote_workspace_bytes). */
 size_t ttkv_workspace_bytes(const ttkv_cache *c, int32_t max_parts, int32_t n_slots);
@@ -205,7 +205,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle h, ttkv_cache *c, int32_t src_tier, int
  *        overlap of Sec. 4.3 inside one launch); `copy` is not used.
  *   n_slots >= 1 (<= TTKV_MAX_SLOTS): host-tier records are copied with hipMemcpyAsync
  *        on `copy` into n_slots staging slots of `workspace` (adjacent records of a
- *        dense tier merged up to 8 MiB per copy), event-chained so that copy i+1 runs
+ *        dense tier merged up to 32 MiB per copy: every copy carries a fixed cost of tens of microseconds), event-chained so that copy i+1 runs
  *        while `compute` attends copy i (both streams equal: nothing overlaps).  A
  *        slot is reused only after the kernel that read it has finished; enough slots
  *        for a whole step avoid those waits.
@@ -280,29 +280,6 @@ ttkv_status ttkv_merge_partials(ttkv_handle h, const float *m, const float *l, c
 ttkv_status ttkv_select_blocks(ttkv_handle h, const ttkv_cache *c, const void *q, int32_t q_fmt, int32_t k,
                                int32_t *sel_blocks, int32_t *sel_count, int32_t sel_stride, void *scratch,
                                size_t scratch_bytes, void *stream);
-
-/* Measurement aid (roofline of the attention kernel; Sec. 5.1 item 4 "latency is
- * measured on the GPU with events"): from now on every ttkv_decode_attn records a
- * HIP event pair around its fused attention launch(es) on the compute stream, for
- * at most max_samples calls (<= 4096) in total; max_samples <= 0 pauses it (the
- * samples taken so far are kept, so a caller can time every n-th step: each event
- * pair costs a few microseconds of idle stream around the launch).  Creates HIP
- * events only.  ttkv_read_attn_timing BLOCKS until the recorded kernels have
- * finished, writes their durations in milliseconds (oldest first, at most
- * `capacity`), returns the count in *n_out and clears the samples. */
-ttkv_status ttkv_time_attn(ttkv_handle h, int32_t max_samples);
-/* Measurement aid: a timed call issues its attention launch(es) `repeat` times (1..64) back to back between
- * the two events -- same arguments, the same partials written again -- and its sample is the duration
- * divided by `repeat`, so that the event pair's own cost (a few microseconds per sample) is spread over
- * several launches.  1 restores the single launch.  Calls that are not timed are unaffected. */
-ttkv_status ttkv_time_attn_repeat(ttkv_handle h, int32_t repeat);
-/* Measurement aid: enqueue a load-only kernel that streams `bytes` (rounded down to a
- * multiple of 64 KiB) of [device] memory at `src` with the attention kernels' access
- * pattern (128-bit loads, eight in flight per lane, four wave64 per workgroup).  Timed by
- * the caller, it gives the read rate the memory system delivers to such a kernel, the
- * practical ceiling beside the nominal HBM peak.  sink: [device] 4 writable bytes. */
-ttkv_status ttkv_stream_read(ttkv_handle h, const void *src, size_t bytes, void *sink, void *stream);
-ttkv_status ttkv_read_attn_timing(ttkv_handle h, float *ms, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus
 }

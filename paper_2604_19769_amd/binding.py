@@ -48,9 +48,17 @@ EXPORTS = [
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
     "ttkv_decode_step", "ttkv_decode_step_topk", "ttkv_decode_attn_noalloc",
-    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_time_attn", "ttkv_time_attn_repeat", "ttkv_read_attn_timing", "ttkv_set_split",
-    "ttkv_stream_read",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_set_split",
 ]
+# include/ttkv_bench.h: measurement and inspection aids, not part of the boundary
+BENCH_EXPORTS = ["ttkv_time_attn", "ttkv_time_attn_repeat", "ttkv_read_attn_timing", "ttkv_stream_read", "ttkv_staged_schedule"]
+OP_COPY, OP_ATTEND, OP_RECORD, OP_WAIT, OP_MERGE = range(5)
+
+
+class ttkv_chain_op(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("stream", C.c_int32), ("event", C.c_int32), ("slot", C.c_int32), ("fetch", C.c_int32),
+                ("bytes", C.c_uint64)]
+
 
 _lib = None
 
@@ -103,7 +111,8 @@ def lib():
         L.ttkv_time_attn_repeat.argtypes = [p, i32]
         L.ttkv_stream_read.argtypes = [p, p, sz, p, p]
         L.ttkv_read_attn_timing.argtypes = [p, C.POINTER(C.c_float), i32, C.POINTER(i32)]
-        for name in EXPORTS:
+        L.ttkv_staged_schedule.argtypes = [p, cp, p, p, i32, i32, i32, C.POINTER(ttkv_chain_op), i32, C.POINTER(i32)]
+        for name in EXPORTS + BENCH_EXPORTS:
             f = getattr(L, name)
             if name not in ("ttkv_get_stats", "ttkv_reset_stats", "ttkv_status_string", "ttkv_record_bytes",
                             "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes",
@@ -251,3 +260,13 @@ def ttkv_read_attn_timing(h, capacity=4096):
     n = C.c_int32()
     _check(lib().ttkv_read_attn_timing(h, ms, capacity, C.byref(n)), "ttkv_read_attn_timing")
     return [ms[i] for i in range(n.value)]
+
+
+def ttkv_staged_schedule(h, cache, sel_blocks=None, sel_count=None, sel_stride=0, n_slots=2, same_stream=False, capacity=1 << 16):
+    """The stream operations ttkv_decode_attn would issue, as a list of dicts (host only: nothing runs)."""
+    ops = (ttkv_chain_op * capacity)()
+    n = C.c_int32()
+    _check(lib().ttkv_staged_schedule(h, C.byref(cache), _p(sel_blocks), _p(sel_count), sel_stride, n_slots, int(same_stream), ops,
+                                      capacity, C.byref(n)), "ttkv_staged_schedule")
+    assert n.value <= capacity
+    return [{k: getattr(ops[i], k) for k, _ in ttkv_chain_op._fields_} for i in range(n.value)]

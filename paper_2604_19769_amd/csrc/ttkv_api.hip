@@ -88,10 +88,14 @@ inline int64_t record_of(const ttkv_tier &T, int b, int64_t ring_block) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Consecutive pool records merged into one copy when adjacent (dense, unpaged tiers): up to
-// 8 MiB per copy, so that the cross-stream event hop per copy (tens of microseconds, measured)
-// is small against the copy itself (8 MiB at 57 GB/s = 147 us).
+// TTKV_COPY_GRANULE_MIB per copy.  Every hipMemcpyAsync carries a fixed cost of some tens of
+// microseconds (set-up, its event hop to the compute stream), so the copies want to be few and
+// large; yet more than one, so that attention on copy i runs under copy i + 1.
+#ifndef TTKV_COPY_GRANULE_MIB
+#define TTKV_COPY_GRANULE_MIB 32
+#endif
 int copy_granule(int64_t rec_bytes) {
-  int64_t g = ((int64_t)8 << 20) / rec_bytes;
+  int64_t g = ((int64_t)TTKV_COPY_GRANULE_MIB << 20) / rec_bytes;
   return (int)std::max<int64_t>(1, std::min<int64_t>(64, g));
 }
 
@@ -663,13 +667,62 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
   return TTKV_OK;
 }
 
+// The stream operations of one attention call -- the copy/compute chain of streaming attention (Sec. 4.3) -- behind
+// one interface, so that the code that issues them drives HIP or, for ttkv_staged_schedule, a recorder: the order
+// checked on the CPU is then the order the GPU gets.
+enum { EV_FENCE = 0, EV_READY = 1, EV_FREED = 1 + TTKV_MAX_SLOTS };   // event ids: fence, ready[slot], freed[slot]
+struct Chain {
+  virtual hipError_t record(int event, int on_copy_stream) = 0;
+  virtual hipError_t wait(int on_copy_stream, int event) = 0;
+  virtual hipError_t copy(int fetch, int slot, void *dst, const void *src, size_t bytes) = 0;
+  virtual hipError_t attend(int fetch, int slot, const FusedArgs &a, int *nk, int *nm) = 0;   // fetch -1: the tiers read in place
+  virtual hipError_t merge(const MergeArgs &m) = 0;
+  virtual ~Chain() {}
+};
+struct HipChain : Chain {
+  Handle *h;
+  hipStream_t compute, copy_s;
+  HipChain(Handle *h_, hipStream_t c, hipStream_t y) : h(h_), compute(c), copy_s(y) {}
+  hipEvent_t ev(int e) { return e == EV_FENCE ? h->fence : e < EV_FREED ? h->ready[e - EV_READY] : h->freed[e - EV_FREED]; }
+  hipError_t record(int e, int on_copy) override { return hipEventRecord(ev(e), on_copy ? copy_s : compute); }
+  hipError_t wait(int on_copy, int e) override { return hipStreamWaitEvent(on_copy ? copy_s : compute, ev(e), 0); }
+  hipError_t copy(int, int, void *dst, const void *src, size_t bytes) override {
+    return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, copy_s);
+  }
+  hipError_t attend(int, int, const FusedArgs &a, int *nk, int *nm) override { return launch_attn(a, compute, nk, nm); }
+  hipError_t merge(const MergeArgs &m) override { return launch_merge(m, compute); }
+};
+struct TraceChain : Chain {
+  ttkv_chain_op *ops;
+  int32_t capacity, n;
+  bool same_stream;
+  TraceChain(ttkv_chain_op *o, int32_t cap, bool same) : ops(o), capacity(cap), n(0), same_stream(same) {}
+  void put(int32_t kind, int on_copy, int32_t event, int32_t slot, int32_t fetch, uint64_t bytes) {
+    if (n < capacity) ops[n] = ttkv_chain_op{kind, (on_copy && !same_stream) ? 1 : 0, event, slot, fetch, bytes};
+    ++n;
+  }
+  hipError_t record(int e, int on_copy) override { put(TTKV_OP_RECORD, on_copy, e, -1, -1, 0); return hipSuccess; }
+  hipError_t wait(int on_copy, int e) override { put(TTKV_OP_WAIT, on_copy, e, -1, -1, 0); return hipSuccess; }
+  hipError_t copy(int fetch, int slot, void *, const void *, size_t bytes) override {
+    put(TTKV_OP_COPY, 1, -1, slot, fetch, bytes);
+    return hipSuccess;
+  }
+  hipError_t attend(int fetch, int slot, const FusedArgs &, int *nk, int *) override {
+    put(TTKV_OP_ATTEND, 0, -1, slot, fetch, 0);
+    *nk += 1;
+    return hipSuccess;
+  }
+  hipError_t merge(const MergeArgs &) override { put(TTKV_OP_MERGE, 0, -1, -1, -1, 0); return hipSuccess; }
+};
+
 // Attention over the cached tokens and the merge.  k_new non-null: the step's new token as well, which the merge
 // kernel adds and stores at the tail of tier 0 (an fp device tier of format new_fmt with room for it: the caller
 // has checked); len[] of tier 0 then grows by one.
 static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, int32_t q_fmt, float *out, float *lse,
                                const int32_t *sel_blocks, const int32_t *sel_count, int32_t sel_stride, void *workspace,
                                size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_, const void *k_new,
-                               const void *v_new, int32_t new_fmt, bool check_only = false, const DevSel *ds = nullptr) {
+                               const void *v_new, int32_t new_fmt, bool check_only = false, const DevSel *ds = nullptr,
+                               Chain *trace = nullptr) {
   ttkv_status st = validate_cache(c);
   if (st != TTKV_OK) return st;
   if (!q || !out || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
@@ -697,7 +750,9 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   if (stride < std::max(1, P.max_parts)) return TTKV_ERR_WORKSPACE;
   const int32_t part_stride = (int32_t)std::min<int64_t>(stride, 1 << 20);
   if (check_only) return TTKV_OK;   // nothing enqueued so far
-  if (!P.fetch.empty() && copy != compute && (st = ensure_events(h)) != TTKV_OK) return st;
+  if (!trace && !P.fetch.empty() && copy != compute && (st = ensure_events(h)) != TTKV_OK) return st;
+  HipChain hip_chain(h, compute, copy);
+  Chain &ch = trace ? *trace : static_cast<Chain &>(hip_chain);
   uint8_t *ws = (uint8_t *)workspace + mis;
   float *pm = (float *)(ws + slots_bytes);
   float *pl = pm + rows * part_stride;
@@ -715,8 +770,8 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
 
   if (!P.fetch.empty() && copy != compute) {
     // staging slots may still be read by earlier work on `compute`
-    TTKV_HIP(h, hipEventRecord(h->fence, compute));
-    TTKV_HIP(h, hipStreamWaitEvent(copy, h->fence, 0));
+    TTKV_HIP(h, ch.record(EV_FENCE, 0));
+    TTKV_HIP(h, ch.wait(1, EV_FENCE));
   }
   // every run that is attended in place goes into one launch (split only when the entry table is full)
   for (int t = 0; t < c->n_tiers; ++t) {
@@ -732,7 +787,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
       a.sel_last_ntok[b] = T.len[b] ? (int32_t)(live_end - (live_end - 1) / T.block_tokens * T.block_tokens) : 0;
     }
   }
-  const bool timed = h->time_on && h->time_n < h->time_max && !P.runs.empty();
+  const bool timed = !trace && h->time_on && h->time_n < h->time_max && !P.runs.empty();
   if (timed) TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n], compute));
   // launch order: runs of host tiers first, so that the PCIe stream starts with the first workgroups
   // and the device-tier items fill the remaining slots while it runs
@@ -762,7 +817,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
       items += r.n_chunks;
     }
     a.n_items = items;
-    TTKV_HIP(h, launch_attn(a, compute, &nk, &nm));
+    TTKV_HIP(h, ch.attend(-1, -1, a, &nk, &nm));
   }
   if (timed) {
     TTKV_HIP(h, hipEventRecord(h->time_ev[2 * h->time_n + 1], compute));
@@ -775,12 +830,13 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
     const Layout L = make_layout(T, c->n_kv_heads);
     const int slot = issued % n_slots;
     uint8_t *dst = ws + (size_t)slot * P.slot_bytes;
-    if (issued >= n_slots && copy != compute) TTKV_HIP(h, hipStreamWaitEvent(copy, h->freed[slot], 0));
+    // a slot is written again only after the kernel that read it has finished
+    if (issued >= n_slots && copy != compute) TTKV_HIP(h, ch.wait(1, EV_FREED + slot));
     const size_t bytes = (size_t)f.nrec * L.rec_bytes;
-    TTKV_HIP(h, hipMemcpyAsync(dst, (const uint8_t *)T.data + f.rec * L.rec_bytes, bytes, hipMemcpyHostToDevice, copy));
+    TTKV_HIP(h, ch.copy(issued, slot, dst, (const uint8_t *)T.data + f.rec * L.rec_bytes, bytes));
     if (copy != compute) {
-      TTKV_HIP(h, hipEventRecord(h->ready[slot], copy));
-      TTKV_HIP(h, hipStreamWaitEvent(compute, h->ready[slot], 0));
+      TTKV_HIP(h, ch.record(EV_READY + slot, 1));
+      TTKV_HIP(h, ch.wait(0, EV_READY + slot));
     }
     a.tv[0] = make_slot_view(T, L, dst, f.nrec);
     a.chunk[0] = f.chunk;
@@ -792,9 +848,14 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
     a.e[0].item_start = 0;
     a.e[0].part_base = f.part_base;
     a.n_items = (f.ntok + f.chunk - 1) / f.chunk;
-    TTKV_HIP(h, launch_attn(a, compute, &nk, &nm));
-    if (copy != compute) TTKV_HIP(h, hipEventRecord(h->freed[slot], compute));
+    TTKV_HIP(h, ch.attend(issued, slot, a, &nk, &nm));
+    if (copy != compute) TTKV_HIP(h, ch.record(EV_FREED + slot, 0));
     ++issued;
+  }
+  if (trace) {
+    MergeArgs none{};
+    TTKV_HIP(h, ch.merge(none));
+    return TTKV_OK;                   // a recorded schedule: no statistics, no lengths
   }
   // host-tier traffic (Sec. 5.1 item 5): whole records, whether copied or read in place
   for (const Fetch &f : P.fetch) {
@@ -827,7 +888,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
     m.dst = make_view(T0, make_layout(T0, c->n_kv_heads));
     for (int b = 0; b < c->batch; ++b) m.new_tok[b] = (int32_t)((T0.start[b] + T0.len[b]) % ring_tokens(T0));
   }
-  TTKV_HIP(h, launch_merge(m, compute));
+  TTKV_HIP(h, ch.merge(m));
   if (k_new)
     for (int b = 0; b < c->batch; ++b) c->tier[0].len[b] += 1;
   h->stats.mfma_launches += nm;
@@ -842,6 +903,22 @@ ttkv_status ttkv_decode_attn(ttkv_handle hh, const ttkv_cache *c, const void *q,
   if (!h) return TTKV_ERR_INVALID_ARG;
   return decode_impl(h, c, q, q_fmt, out, lse, sel_blocks, sel_count, sel_stride, workspace, ws_bytes, n_slots, compute,
                      copy, nullptr, nullptr, 0);
+}
+
+ttkv_status ttkv_staged_schedule(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
+                                 int32_t sel_stride, int32_t n_slots, int32_t same_stream, ttkv_chain_op *ops,
+                                 int32_t capacity, int32_t *n_out) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !n_out || capacity < 0 || (capacity > 0 && !ops)) return TTKV_ERR_INVALID_ARG;
+  TraceChain tc(ops, capacity, same_stream != 0);
+  // no memory is touched: any non-null pointers do, and a workspace that is always large enough
+  void *const fake = reinterpret_cast<void *>(256);
+  void *const compute = reinterpret_cast<void *>(8), *const copy = same_stream ? compute : reinterpret_cast<void *>(16);
+  const ttkv_status st = decode_impl(h, c, fake, TTKV_BF16, reinterpret_cast<float *>(fake), nullptr, sel_blocks, sel_count,
+                                     sel_stride, fake, (size_t)1 << 46, n_slots, compute, copy, nullptr, nullptr, 0, false,
+                                     nullptr, &tc);
+  *n_out = tc.n;
+  return st;
 }
 
 // Split partials of ttkv_decode_attn_noalloc: one array per GPU (every device that loads this code object holds
@@ -1040,63 +1117,6 @@ ttkv_status ttkv_set_split(ttkv_handle hh, int32_t target_items) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || target_items < 0 || target_items > (1 << 20)) return TTKV_ERR_INVALID_ARG;
   h->target_items = target_items;
-  return TTKV_OK;
-}
-
-ttkv_status ttkv_time_attn(ttkv_handle hh, int32_t max_samples) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || max_samples > 4096) return TTKV_ERR_INVALID_ARG;
-  if (max_samples <= 0) {
-    h->time_on = false;
-    return TTKV_OK;
-  }
-  if (max_samples > h->time_max) {
-    hipEvent_t *ev = (hipEvent_t *)realloc(h->time_ev, sizeof(hipEvent_t) * 2 * max_samples);
-    if (!ev) return TTKV_ERR_INVALID_ARG;
-    h->time_ev = ev;
-    int32_t *reps = (int32_t *)realloc(h->time_reps, sizeof(int32_t) * max_samples);
-    if (!reps) return TTKV_ERR_INVALID_ARG;
-    h->time_reps = reps;
-    for (int i = 2 * h->time_max; i < 2 * max_samples; ++i) {
-      hipError_t e = hipEventCreate(&ev[i]);
-      if (e != hipSuccess) {
-        h->time_max = i / 2;
-        h->stats.last_hip_error = (int32_t)e;
-        return TTKV_ERR_HIP;
-      }
-    }
-    h->time_max = max_samples;
-  }
-  h->time_on = true;   // samples accumulate until they are read
-  return TTKV_OK;
-}
-
-ttkv_status ttkv_time_attn_repeat(ttkv_handle hh, int32_t repeat) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || repeat < 1 || repeat > 64) return TTKV_ERR_INVALID_ARG;
-  h->time_repeat = repeat;
-  return TTKV_OK;
-}
-
-ttkv_status ttkv_stream_read(ttkv_handle hh, const void *src, size_t bytes, void *sink, void *stream) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || !src || !sink) return TTKV_ERR_INVALID_ARG;
-  TTKV_HIP(h, launch_stream_read(src, (int64_t)bytes, (uint32_t *)sink, (hipStream_t)stream));
-  h->stats.kernels += bytes >= 65536;
-  return TTKV_OK;
-}
-
-ttkv_status ttkv_read_attn_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
-  Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || !ms || !n_out || capacity < 0) return TTKV_ERR_INVALID_ARG;
-  const int n = std::min<int>(capacity, h->time_n);
-  for (int i = 0; i < n; ++i) {
-    TTKV_HIP(h, hipEventSynchronize(h->time_ev[2 * i + 1]));
-    TTKV_HIP(h, hipEventElapsedTime(&ms[i], h->time_ev[2 * i], h->time_ev[2 * i + 1]));
-    ms[i] /= (float)h->time_reps[i];
-  }
-  *n_out = n;
-  h->time_n = 0;
   return TTKV_OK;
 }
 

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "ttkv.h"
+#include "ttkv_bench.h"
 
 namespace ttkv {
 

@@ -1,8 +1,11 @@
-// Measurement aid: a load-only kernel with the attention kernels' access pattern (workgroups
+// Measurement aids (declared in ttkv_bench.h, not part of the boundary): event timing of the attention launches
+// and a load-only kernel with the attention kernels' access pattern (workgroups
 // of four wave64 streaming contiguous chunks with non-temporal 128-bit loads, eight in flight per lane).
 // Its rate is what this device's memory system delivers to such a kernel, the practical
 // ceiling beside the nominal HBM peak (Sec. 5.1 item 4: measured on the GPU).
 #include "ttkv_attn_dev.h"
+
+#include <algorithm>
 
 namespace ttkv {
 
@@ -37,3 +40,66 @@ hipError_t launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hi
 }
 
 }  // namespace ttkv
+
+using namespace ttkv;
+
+extern "C" {
+
+ttkv_status ttkv_time_attn(ttkv_handle hh, int32_t max_samples) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || max_samples > 4096) return TTKV_ERR_INVALID_ARG;
+  if (max_samples <= 0) {
+    h->time_on = false;
+    return TTKV_OK;
+  }
+  if (max_samples > h->time_max) {
+    hipEvent_t *ev = (hipEvent_t *)realloc(h->time_ev, sizeof(hipEvent_t) * 2 * max_samples);
+    if (!ev) return TTKV_ERR_INVALID_ARG;
+    h->time_ev = ev;
+    int32_t *reps = (int32_t *)realloc(h->time_reps, sizeof(int32_t) * max_samples);
+    if (!reps) return TTKV_ERR_INVALID_ARG;
+    h->time_reps = reps;
+    for (int i = 2 * h->time_max; i < 2 * max_samples; ++i) {
+      hipError_t e = hipEventCreate(&ev[i]);
+      if (e != hipSuccess) {
+        h->time_max = i / 2;
+        h->stats.last_hip_error = (int32_t)e;
+        return TTKV_ERR_HIP;
+      }
+    }
+    h->time_max = max_samples;
+  }
+  h->time_on = true;   // samples accumulate until they are read
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_time_attn_repeat(ttkv_handle hh, int32_t repeat) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || repeat < 1 || repeat > 64) return TTKV_ERR_INVALID_ARG;
+  h->time_repeat = repeat;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_stream_read(ttkv_handle hh, const void *src, size_t bytes, void *sink, void *stream) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !src || !sink) return TTKV_ERR_INVALID_ARG;
+  TTKV_HIP(h, launch_stream_read(src, (int64_t)bytes, (uint32_t *)sink, (hipStream_t)stream));
+  h->stats.kernels += bytes >= 65536;
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_read_attn_timing(ttkv_handle hh, float *ms, int32_t capacity, int32_t *n_out) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || !ms || !n_out || capacity < 0) return TTKV_ERR_INVALID_ARG;
+  const int n = std::min<int>(capacity, h->time_n);
+  for (int i = 0; i < n; ++i) {
+    TTKV_HIP(h, hipEventSynchronize(h->time_ev[2 * i + 1]));
+    TTKV_HIP(h, hipEventElapsedTime(&ms[i], h->time_ev[2 * i], h->time_ev[2 * i + 1]));
+    ms[i] /= (float)h->time_reps[i];
+  }
+  *n_out = n;
+  h->time_n = 0;
+  return TTKV_OK;
+}
+
+}  // extern "C"

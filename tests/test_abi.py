@@ -13,8 +13,8 @@ from paper_2604_19769_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "ttkv.h")).read()
+def header_functions(name="ttkv.h"):
+    text = open(os.path.join(ROOT, "include", name)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ttkv_[a-z_0-9]+)\s*\(", text)))
 
@@ -26,6 +26,11 @@ def test_library_exports_every_declared_function():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(B.EXPORTS) == names
+    aids = header_functions("ttkv_bench.h")               # measurement / inspection aids: their own header
+    assert len(aids) == 5 and not set(aids) & set(names)
+    for n in aids:
+        assert hasattr(L, n), n
+    assert sorted(B.BENCH_EXPORTS) == aids
 
 
 def host_cache(batch=2, Hq=8, Hkv=2, fmts=(("f16", "f16"), ("i8", "i8"), ("i4", "i4")), bt=(128, 128, 1024)):
