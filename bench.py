@@ -27,8 +27,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 # HBM bytes per mha32k attention launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, each scaled by
-# a plain copy kernel's reading (profiles/attn_fused_mha32k_hbm_traffic_pmc.txt); 1.004 x algorithmic
+# a plain copy kernel's reading (profiles/attn_fused_mha32k_hbm_traffic_pmc.txt); 1.004 x algorithmic.
+# A profile constant, not a reading of this run: the object says where it is from.
 MHA32K_MEASURED_TRAFFIC_BYTES = 697.0e6
+MHA32K_TRAFFIC_SOURCE = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel at this workload: profiles/attn_fused_mha32k_hbm_traffic_pmc.txt"
 PCIE_PEAK_GBS = 64.0        # PCIe Gen5 x16 per direction, nominal
 SEED = 1976900
 
@@ -38,7 +40,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "ablation", "grid"])
+    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "tiny", "serving_ragged", "sparse128k", "ablation", "grid"])
+    ap.add_argument("--mode", default="all", choices=["all", "staged"],
+                    help="offload128k only: 'staged' runs nothing but attention calls in the staged-copy mode (for a trace)")
+    ap.add_argument("--overlap-from-trace", metavar="DIR", help="no GPU work: summarise the copy/compute overlap of a rocprofv3 "
+                    "--kernel-trace --memory-copy-trace csv output in DIR (files <prefix>_kernel_trace.csv, <prefix>_memory_copy_trace.csv)")
+    ap.add_argument("--trace-prefix", default="kt")
     ap.add_argument("--no-offload", action="store_true", help="skip the 128K offload object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offload-steps", type=int, default=20)
@@ -163,6 +170,55 @@ def cpu_baseline_mha32k(kv, steps, shape, gpu_outs):
             "ms_per_step": round(secs / n_steps * 1e3, 1), "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
 
 
+
+# ------------------------------------------------------------------ shared: sampled oracle baselines, PCIe roofline
+
+def host_tier_live_bytes(cache):
+    """Stored bytes of the live rows of the host tiers: what actually crosses PCIe when the kernel reads them in
+    place (the library's h2d counter counts whole block records, as the oracle's does)."""
+    total, by_tier = algorithmic_bytes(cache)
+    return sum(n for n, cfg in zip(by_tier, cache.cfg) if cfg.mem == "host")
+
+
+def pcie_roofline(host_bytes, seconds, what):
+    gbs = host_bytes / seconds / 1e9
+    return {"bound": "pcie", "kernel": what, "achieved": round(gbs, 2), "peak": PCIE_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / PCIE_PEAK_GBS, 4), "traffic": None, "bytes_per_step": int(host_bytes),
+            "note": "host-tier bytes of live rows / attention time; traffic: no PCIe counter is read"}
+
+
+def oracle_sample(tier_specs, max_tokens, Hq, Hkv, heads, seqs, steps_in, step, gpu_out, what, select_k=None):
+    """The oracle as it stands on a sample of the workload: for each (sequence index b, K, V) in seqs, KV heads
+    `heads` (all their query heads, every token), loaded in bulk, then ONE decode step timed on this machine's host
+    cores and compared with the GPU's output of that step.  Returns the cpu_baseline object (GB/s of stored bytes)."""
+    import numpy as np
+    from oracle import OracleCache
+    q, kn, vn = steps_in
+    G = Hq // Hkv
+    rows = np.concatenate([np.arange(h * G, (h + 1) * G) for h in heads])
+    cores = min(len(os.sched_getaffinity(0)), len(rows))      # the oracle's threads run over query heads
+    secs, bytes_, err = 0.0, 0, 0.0
+    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68}
+    for b, K, V in seqs:
+        ora = OracleCache(1, G * len(heads), len(heads), 128, tier_specs, max_tokens)
+        ora.load(0, K[heads].float().cpu().numpy(), V[heads].float().cpu().numpy())
+        args = (q[step, b][rows][None].float().cpu().numpy(), kn[step, b, heads, 0][None].float().cpu().numpy(),
+                vn[step, b, heads, 0][None].float().cpu().numpy())
+        t0 = time.perf_counter()
+        r = ora.step(*args) if select_k is None else ora.step(*args, select_k=select_k)
+        secs += time.perf_counter() - t0
+        if select_k is None:
+            bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs))
+        else:   # only the selected blocks of the last tier are attended
+            last = len(tier_specs) - 1
+            bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs[:-1]))
+            bytes_ += len(r[2][0]) * tier_specs[last].block_tokens * len(heads) * (per[tier_specs[last].k_fmt] + per[tier_specs[last].v_fmt])
+        g = gpu_out[b][rows].float().cpu().numpy()
+        err = max(err, float(np.max(np.abs(g - r[0][0]) / (2e-3 + 1e-2 * np.abs(r[0][0])))))
+        del ora
+    return {"value": round(bytes_ / secs / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle", "sample": what,
+            "seconds": round(secs, 2), "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
+
 # ------------------------------------------------------------------ workload: 128K offload
 
 def build_offload128k(steps_total):
@@ -243,20 +299,36 @@ def build_serving_ragged(steps_total, batch=16):
     return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, ctx=ctx)
 
 
-def run_serving_ragged(steps, warmup):
-    cache, kv, (q, kn, vn), shape = build_serving_ragged(steps + warmup)
-    del kv
+def run_serving_ragged(steps, warmup, cpu_baseline=True):
+    from oracle import TierSpec
+    cache, kv, steps_in, shape = build_serving_ragged(steps + warmup)
+    q, kn, vn = steps_in
     try:
-        timed_steps(cache, q, kn, vn, 0, warmup)
+        keep = []
+        timed_steps(cache, q, kn, vn, 0, 1, keep=keep)                   # the first step is also the oracle's
+        timed_steps(cache, q, kn, vn, 1, warmup - 1)
         total, by_tier = algorithmic_bytes(cache)
+        live0 = host_tier_live_bytes(cache)
         s0 = cache.stats()
         t = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        live = (live0 + host_tier_live_bytes(cache)) / 2
         h2d = (cache.stats()["h2d_bytes"] - s0["h2d_bytes"]) / steps
+        cpu = None
+        if cpu_baseline:
+            import numpy as np
+            b = int(np.argmin(shape["ctx"]))
+            tiers = [TierSpec("f16", "f16", 4096, 256), TierSpec("i8", "i8", 12288, 256), TierSpec("i4", "i4", 10**9, 256, mem="host")]
+            cpu = oracle_sample(tiers, [4096 + 512, 12288 + 1024, 65536], 32, 8, [0, 5], [(b, kv[b][0], kv[b][1])], steps_in, 0, keep[0],
+                                f"sequence {b} (the shortest, {int(shape['ctx'][b])} tokens) of 16, KV heads 0 and 5 of 8 (8 query "
+                                f"heads), the first decode step incl. append+evict")
         return {"workload": "batch 16, 32 q / 8 kv heads, contexts U[16K, 64K] (mean %d), 256-token pages, 4K fp16 + 12K int8 in HBM, "
                             "rest int4 in pinned host memory" % int(shape["ctx"].mean()),
-                "ms_per_step": round(t * 1e3, 3), "tokens_per_s": round(shape["B"] / t, 1),
-                "host_tier_bytes_per_step": int(h2d), "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
-                "pcie_h2d_GBs": round(h2d / t / 1e9, 2), "pcie_frac_of_nominal_64": round(h2d / t / 1e9 / PCIE_PEAK_GBS, 4)}
+                "steps": steps, "ms_per_step": round(t * 1e3, 3), "tokens_per_s": round(shape["B"] / t, 1),
+                "host_tier_record_bytes_per_step": int(h2d), "host_tier_live_bytes_per_step": int(live),
+                "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
+                "effective_kv_GBs": round(total / t / 1e9, 2),
+                "roofline": pcie_roofline(live, t, "attn_mfma_kernel<4>: every tier in one launch, host pages read in place"),
+                "cpu_baseline": cpu}
     finally:
         cache.close()
 
@@ -303,12 +375,16 @@ def build_sparse128k(steps_total, batch=4, planted=8):
     return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, N=N, planted=plant_ids)
 
 
-def run_sparse128k(steps, warmup, k=64):
-    cache, kv, (q, kn, vn), shape = build_sparse128k(steps + warmup)
-    del kv
+def run_sparse128k(steps, warmup, k=64, cpu_baseline=True):
+    from oracle import TierSpec
+    cache, kv, steps_in, shape = build_sparse128k(steps + warmup)
+    q, kn, vn = steps_in
     try:
+        first = None
         for s in range(warmup):
-            cache.step(q[s], kn[s], vn[s], select_k=k)
+            out, _ = cache.step(q[s], kn[s], vn[s], select_k=k)
+            if s == 0:
+                first = out.clone()
         total, by_tier = algorithmic_bytes(cache)
         s0 = cache.stats()
         t0 = sync_time()
@@ -317,12 +393,71 @@ def run_sparse128k(steps, warmup, k=64):
         t = (sync_time() - t0) / steps
         st = cache.stats()
         h2d = (st["h2d_bytes"] - s0["h2d_bytes"]) / steps
+        # selected blocks: whole 1024-token records except a partly filled newest one (none here: the host tier only
+        # grows by whole blocks), so live bytes = record bytes
+        cpu = None
+        if cpu_baseline:
+            tiers = [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 1024),
+                     TierSpec("i4", "i4", 10**9, 1024, mem="host", summary=True)]
+            cpu = oracle_sample(tiers, [4096 + 256, 28672 + 2048, 98304 + 4096], 32, 8, list(range(8)), [(1, kv[1][0], kv[1][1])],
+                                steps_in, 0, first, "sequence 1 of 4, all 8 KV heads (block identification sums over every head), the "
+                                "first decode step: scoring + top-64 of 96 + attention + append+evict", select_k=k)
         return {"workload": "batch 4, 32 q / 8 kv heads, 131072 tokens: 4K bf16 + 28K int8 in HBM, 96K int4 on the host in "
                             "1024-token blocks with mean-key summaries; top-64 of 96 blocks fetched per sequence",
-                "ms_per_step": round(t * 1e3, 3), "blocks_fetched_per_step": (st["blocks_fetched"] - s0["blocks_fetched"]) / steps,
+                "steps": steps, "ms_per_step": round(t * 1e3, 3), "blocks_fetched_per_step": (st["blocks_fetched"] - s0["blocks_fetched"]) / steps,
                 "host_tier_bytes_per_step": int(h2d), "dense_host_tier_bytes": 4 * 96 * 1179648,
                 "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
-                "pcie_h2d_GBs": round(h2d / t / 1e9, 2), "pcie_frac_of_nominal_64": round(h2d / t / 1e9 / PCIE_PEAK_GBS, 4)}
+                "effective_kv_GBs": round((h2d + by_tier[0] + by_tier[1]) / t / 1e9, 2),
+                "roofline": pcie_roofline(h2d, t, "score_kernel + topk_kernel + attn_mfma_kernel<4> (selected host blocks read in place)"),
+                "cpu_baseline": cpu}
+    finally:
+        cache.close()
+
+
+# ------------------------------------------------------------------ workload: tiny (launch-latency floor)
+
+def run_tiny(steps=200, warmup=20, cpu_baseline=True):
+    """BASELINE config 1: batch 1, 8 q / 2 kv heads, 4096 tokens, recent 512 fp16 + 3584 int8 (group 32), all in HBM.
+    2.5 MB per step: 0.3 us at the HBM peak, so the step is launch latency (two launches: attention, merge)."""
+    import numpy as np
+    import torch
+    from oracle import TierSpec
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    Hq, Hkv, N, R, bt = 8, 2, 4096, 512, 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 1)
+    total_steps = steps + warmup
+    cache = TieredCache(1, Hq, Hkv, [TierConfig("f16", "f16", R, bt, R // bt + 1),
+                                     TierConfig("i8", "i8", 10**9, bt, (N - R + 2 * total_steps) // bt + 3)])
+    try:
+        K = device_normal(gen, (1, Hkv, N - 1, 128), torch.float16)
+        V = device_normal(gen, (1, Hkv, N - 1, 128), torch.float16)
+        cache.append(1, K[:, :, :N - R].contiguous(), V[:, :, :N - R].contiguous(), through_tiers=True)
+        cache.append(0, K[:, :, N - R:].contiguous(), V[:, :, N - R:].contiguous())
+        q = device_normal(gen, (total_steps, 1, Hq, 128), torch.float16)
+        kn = device_normal(gen, (total_steps, 1, Hkv, 1, 128), torch.float16)
+        vn = device_normal(gen, (total_steps, 1, Hkv, 1, 128), torch.float16)
+        keep = []
+        timed_steps(cache, q, kn, vn, 0, 1, keep=keep)
+        timed_steps(cache, q, kn, vn, 1, warmup - 1)
+        total, by_tier = algorithmic_bytes(cache)
+        t = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        lat = step_latencies(cache, q, kn, vn, warmup, steps)       # replays the same inputs on the grown cache: timing only
+        cpu = None
+        if cpu_baseline:
+            tiers = [TierSpec("f16", "f16", R, bt), TierSpec("i8", "i8", 10**9, bt)]
+            cpu = oracle_sample(tiers, [R + 256, N + 512], Hq, Hkv, [0, 1], [(0, K[0], V[0])], (q, kn, vn), 0, keep[0],
+                                "the whole workload (1 sequence, both KV heads), the first decode step incl. append+evict")
+        gbs = total / t / 1e9
+        return {"workload": "batch 1, 8 q / 2 kv heads, 4096 tokens: recent 512 fp16 + 3584 int8 (group 32) in HBM",
+                "steps": steps, "us_per_step": round(t * 1e6, 2), "us_per_step_p50_p95_event_timed":
+                    [round(lat[len(lat) // 2] * 1e6, 1), round(lat[int(0.95 * len(lat))] * 1e6, 1)],
+                "bytes_per_step": int(total), "effective_kv_GBs": round(gbs, 1),
+                "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel<4> + merge_kernel: launch-latency floor (0.3 us of traffic at the peak)",
+                             "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 5),
+                             "traffic": None},
+                "cpu_baseline": cpu}
     finally:
         cache.close()
 
@@ -394,14 +529,32 @@ def decode_only_seconds(cache, q, reps):
     return (sync_time() - t0) / reps
 
 
-def run_offload128k(steps, warmup):
+def spread(xs):
+    xs = sorted(xs)
+    return [round(xs[len(xs) // 2] * 1e6, 1), round(xs[0] * 1e6, 1), round(xs[-1] * 1e6, 1)]      # median, min, max in us
+
+
+def run_offload128k(steps, warmup, cpu_baseline=True, staged_only=False):
     """128K context with the oldest 96K tokens in pinned host DRAM.  Reported for the default mode
     (the attention kernel reads the host records in place over PCIe) and for the staged mode
-    (hipMemcpyAsync of runs of block records into staging slots, event-chained with the kernels)."""
+    (hipMemcpyAsync of runs of block records into staging slots, event-chained with the kernels).
+    staged_only: nothing but `steps` attention calls in the staged mode after the warm-up (the run a
+    rocprofv3 kernel + memory-copy trace is taken of)."""
+    from oracle import TierSpec
     from paper_2604_19769_amd import binding as B
-    cache, _, (q, kn, vn), shape = build_offload128k(2 * (steps + warmup) + 4)
+    cache, kv, steps_in, shape = build_offload128k(2 * (steps + warmup) + 4)
+    q, kn, vn = steps_in
     try:
-        timed_steps(cache, q, kn, vn, 0, warmup)
+        if staged_only:
+            cache.n_slots = 4
+            decode_only_seconds(cache, q, warmup)
+            t = decode_only_seconds(cache, q, steps)
+            live = host_tier_live_bytes(cache)
+            return {"mode": "staged copies, 4 slots", "attn_only_us": round(t * 1e6, 1), "steps": steps,
+                    "roofline": pcie_roofline(live, t, "hipMemcpyAsync x4 + attn_mfma_kernel<4> per copy, event-chained")}
+        keep = []
+        timed_steps(cache, q, kn, vn, 0, 1, keep=keep)
+        timed_steps(cache, q, kn, vn, 1, warmup - 1)
         total, by_tier = algorithmic_bytes(cache)
         s0 = cache.stats()
         # every step bracketed by a HIP event pair on its stream as well: median and p95 (Sec. 5.1 item 4)
@@ -415,12 +568,13 @@ def run_offload128k(steps, warmup):
         t_step = (sync_time() - t0) / steps
         per_step = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
         h2d_per_step = (cache.stats()["h2d_bytes"] - s0["h2d_bytes"]) / steps
-        # copy/compute overlap: host-tier streaming alone, device tiers alone, both together, each as the duration
-        # of the attention launch itself (HIP event pair on its stream), so that the merge kernel and the launch
-        # overheads, which all three share, cancel.  The device tiers are ~1 % of the step: the three are measured
-        # in interleaved rounds and compared by their medians (drift of the PCIe rate would swamp the difference).
+        live = host_tier_live_bytes(cache)      # the state the attention-only figures below are measured on
+        # In-place mode: copy and compute are ONE launch, so there are no copy and kernel intervals to intersect.
+        # What can be shown: the attention launch alone (HIP event pair on its stream) over the host tier only, the
+        # device tiers only, and everything, in interleaved rounds.  The device tiers are ~1 % of the launch, less
+        # than the spread of the other two, so a fraction is not resolvable from them; the three durations are.
         t_all = decode_only_seconds(cache, q, steps)
-        keep = [cache.len[t].copy() for t in range(3)]
+        keep_len = [cache.len[t].copy() for t in range(3)]
         rounds, per = 7, max(4, steps // 4)
         ts = {"all": [], "dev": [], "host": []}
 
@@ -434,20 +588,26 @@ def run_offload128k(steps, warmup):
             ts["all"].append(launch_seconds())
             cache.len[2][:] = 0
             ts["dev"].append(launch_seconds())
-            cache.len[2][:] = keep[2]
+            cache.len[2][:] = keep_len[2]
             cache.len[0][:] = 0
             cache.len[1][:] = 0
             ts["host"].append(launch_seconds())
-            cache.len[0][:] = keep[0]
-            cache.len[1][:] = keep[1]
-        k_all, t_dev, t_host = (sorted(ts[k])[rounds // 2] for k in ("all", "dev", "host"))
-        overlap = (t_host + t_dev - k_all) / min(t_host, t_dev)
+            cache.len[0][:] = keep_len[0]
+            cache.len[1][:] = keep_len[1]
         peak = measure_h2d_peak()
-        # staged mode on the same cache
-        cache.n_slots = 16          # 14 copies of 7 records (8 MiB) each: no slot is reused within a step
+        # staged mode on the same cache: 4 copies of up to 27 records (32 MiB), one slot each
+        cache.n_slots = 4
         decode_only_seconds(cache, q, 4)
         t_staged = decode_only_seconds(cache, q, max(3, steps // 2))
         cache.n_slots = 0
+        cpu = None
+        if cpu_baseline:
+            tiers = [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 128), TierSpec("i4", "i4", 10**9, 1024, mem="host")]
+            cpu = oracle_sample(tiers, [4096 + 256, 28672 + 512, 98304 + 2048], 32, 8, [1, 6], [(0, kv[0][0], kv[1][0])], steps_in, 0,
+                                keep[0], "KV heads 1 and 6 of 8 (8 query heads), all 131072 tokens, the first decode step incl. append+evict")
+        roof = pcie_roofline(live, t_all, "attn_mfma_kernel<4>: device tiers + host records read in place, one launch")
+        roof["frac_of_measured_link_peak"] = round(live / t_all / 1e9 / peak, 4)
+        roof["measured_link_peak_GBs"] = round(peak, 2)
         return {
             "workload": "batch 1, 32 q / 8 kv heads, 131072 tokens: 4K bf16 + 28K int8 in HBM, 96K int4 in pinned host "
                         "DRAM in 1024-token block records",
@@ -455,18 +615,22 @@ def run_offload128k(steps, warmup):
             "us_per_token_p50": round(per_step[len(per_step) // 2], 1),
             "us_per_token_p95": round(per_step[min(len(per_step) - 1, int(0.95 * len(per_step)))], 1),
             "attn_only_us": round(t_all * 1e6, 1),
-            "host_tier_bytes_per_step": int(h2d_per_step),
+            "host_tier_record_bytes_per_step": int(h2d_per_step),
+            "host_tier_live_bytes_per_step": int(live),
             "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
-            "pcie_h2d_GBs": round(h2d_per_step / t_all / 1e9, 2),
-            "pcie_frac_of_nominal_64": round(h2d_per_step / t_all / 1e9 / PCIE_PEAK_GBS, 4),
-            "pcie_measured_peak_GBs": round(peak, 2),
-            "pcie_frac_of_measured_peak": round(h2d_per_step / t_all / 1e9 / peak, 4),
-            "attn_launch_us": round(k_all * 1e6, 1),
-            "host_tier_alone_us": round(t_host * 1e6, 1),
-            "device_tiers_alone_us": round(t_dev * 1e6, 1),
-            "overlap_fraction": round(overlap, 4),
-            "staged_copy_mode_attn_only_us": round(t_staged * 1e6, 1),
             "effective_kv_GBs": round(total / t_step / 1e9, 2),
+            "roofline": roof,
+            "cpu_baseline": cpu,
+            "in_place_overlap": {
+                "attn_launch_us_median_min_max": spread(ts["all"]),
+                "host_tier_alone_us_median_min_max": spread(ts["host"]),
+                "device_tiers_alone_us_median_min_max": spread(ts["dev"]),
+                "note": "copy and compute are one launch: PCIe loads of some waves are in flight while others compute; the device "
+                        "tiers' time is smaller than the run-to-run spread of the launch, so no overlap fraction is derived here"},
+            "staged_copy_mode": {
+                "n_slots": 4, "attn_only_us": round(t_staged * 1e6, 1),
+                "pcie_GBs": round(live / t_staged / 1e9, 2), "pcie_frac_of_nominal_64": round(live / t_staged / 1e9 / PCIE_PEAK_GBS, 4),
+                "overlap_fraction": "from a rocprofv3 kernel + memory-copy trace: profiles/offload128k_staged_overlap_trace.txt"},
             "prefill_tiering_ms": round(shape["tiering_s"] * 1e3, 2),
             "prefill_tiering_tokens_per_s": round((shape["N"] - 1) / shape["tiering_s"], 0),
             "prefill_d2h_GBs": round(shape["d2h_bytes"] / shape["tiering_s"] / 1e9, 2),
@@ -474,6 +638,81 @@ def run_offload128k(steps, warmup):
         }
     finally:
         cache.close()
+
+
+def overlap_from_trace(trace_dir, prefix):
+    """Copy/compute overlap of the staged mode from a rocprofv3 --kernel-trace --memory-copy-trace run (csv output):
+    per attention call, T_copy = union of the host-to-device copy intervals, T_compute = union of the kernel
+    intervals, T_step = first start to last end; overlap = (T_copy + T_compute - T_step) / min(T_copy, T_compute).
+    A call = the copies and kernels between two merge kernels.  Prints a summary (what profiles/ keeps)."""
+    import csv
+
+    def union(iv):
+        tot, end = 0, None
+        for a, b in sorted(iv):
+            if end is None or a > end:
+                tot += b - a
+                end = b
+            elif b > end:
+                tot += b - end
+                end = b
+        return tot
+
+    ks = list(csv.DictReader(open(os.path.join(trace_dir, prefix + "_kernel_trace.csv"))))
+    cs = list(csv.DictReader(open(os.path.join(trace_dir, prefix + "_memory_copy_trace.csv"))))
+    ev = [(int(r["Start_Timestamp"]), int(r["End_Timestamp"]), "k", r["Kernel_Name"]) for r in ks]
+    ev += [(int(r["Start_Timestamp"]), int(r["End_Timestamp"]), "c", r.get("Direction", "")) for r in cs
+           if "HOST_TO_DEVICE" in r.get("Direction", "").upper() or "H2D" in r.get("Direction", "").upper()]
+    ev.sort()
+    calls, cur = [], []
+    for e in ev:
+        cur.append(e)
+        if e[2] == "k" and "merge_kernel" in e[3]:
+            calls.append(cur)
+            cur = []
+    def merged(iv):
+        out = []
+        for a, b in sorted(iv):
+            if out and a <= out[-1][1]:
+                out[-1][1] = max(out[-1][1], b)
+            else:
+                out.append([a, b])
+        return out
+
+    def intersection(x, y):
+        tot = 0
+        for a, b in merged(x):
+            for c, d in merged(y):
+                tot += max(0, min(b, d) - max(a, c))
+        return tot
+
+    rows = []
+    for call in calls:
+        cop = [(a, b) for a, b, k, _ in call if k == "c"]
+        ker = [(a, b) for a, b, k, n in call if k == "k" and ("attn_" in n or "merge_kernel" in n)]
+        if len(cop) < 2 or not ker:
+            continue                       # not a staged attention call
+        t_copy, t_comp = union(cop), union(ker)
+        t_step = max(b for _, b in cop + ker) - min(a for a, _ in cop + ker)
+        rows.append((t_copy, t_comp, t_step, (t_copy + t_comp - t_step) / min(t_copy, t_comp), len(cop), len(ker),
+                     intersection(cop, ker) / t_comp, t_step - union(cop + ker)))
+    rows = rows[len(rows) // 4:]           # the first quarter is warm-up
+    med = lambda i: sorted(r[i] for r in rows)[len(rows) // 2]
+    print(f"staged attention calls analysed: {len(rows)} (copies per call {rows[0][4]}, kernels per call {rows[0][5]})")
+    print(f"T_copy    (union of H2D copy intervals)  median {med(0) / 1e3:9.1f} us")
+    print(f"T_compute (union of kernel intervals)    median {med(1) / 1e3:9.1f} us")
+    print(f"T_step    (first start .. last end)      median {med(2) / 1e3:9.1f} us")
+    print(f"idle inside the step (neither a copy nor a kernel running) median {med(7) / 1e3:.1f} us")
+    print(f"overlap = (T_copy + T_compute - T_step) / min(T_copy, T_compute): median {med(3):.3f}, "
+          f"min {min(r[3] for r in rows):.3f}, max {max(r[3] for r in rows):.3f}")
+    print(f"share of the kernel time that ran while a copy was in flight: median {med(6):.3f}")
+    print(f"exposed beyond the copies (T_step - T_copy) median {(med(2) - med(0)) / 1e3:.1f} us")
+    call = calls[len(calls) // 2]
+    t0 = call[0][0]
+    print("timeline of one call (us from its first operation): start, end, what")
+    for a, b, k, n in call:
+        name = "copy H2D" if k == "c" else next((x for x in ("attn_mfma_kernel", "attn_fused_kernel", "merge_kernel") if x in n), n[:40])
+        print(f"  {(a - t0) / 1e3:8.1f} {(b - t0) / 1e3:8.1f}  {name}")
 
 
 # ------------------------------------------------------------------ workload: grouped-query tiers resident in HBM
@@ -692,6 +931,9 @@ def run_ablation(steps, warmup):
 
 def main():
     args = parse()
+    if args.overlap_from_trace:
+        overlap_from_trace(args.overlap_from_trace, args.trace_prefix)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
@@ -726,14 +968,26 @@ def main():
                 "data": "synthetic", "config": {"workload": "ablation: " + r["workload"]}, "ablation": r}
         print(json.dumps(line))
         return
+    base = {"n_gpus": 1, "steps": K, "warmup": W, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
+    cpu_on = not args.no_cpu_baseline
     if args.workload == "offload128k":
-        r = run_offload128k(K, W)
-        line = {"metric": "decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K", "value": r["effective_kv_GBs"],
-                "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(r["us_per_token"] / 1e3, 4),
-                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16/int8/int4 -> f32",
-                "data": "synthetic", "config": {"workload": "offload128k: " + r["workload"]}, "offload_128k": r,
-                "roofline": {"bound": "pcie", "achieved": r["pcie_h2d_GBs"], "peak": PCIE_PEAK_GBS, "unit": "GB/s",
-                             "frac": r["pcie_frac_of_nominal_64"], "traffic": None}, "cpu_baseline": None}
+        r = run_offload128k(K, W, cpu_on, staged_only=args.mode == "staged")
+        roof = r["roofline"]
+        t_us = r["attn_only_us"] if args.mode == "staged" else r["us_per_token"]
+        line = dict(base, metric="decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K", value=roof["achieved"],
+                    unit="GB/s", ms_per_step=round(t_us / 1e3, 4), higher_is_better=True, dtype="bf16/int8/int4 -> f32",
+                    config={"workload": "offload128k" + (" (staged copies only)" if args.mode == "staged" else ": " + r["workload"])},
+                    roofline=roof, cpu_baseline=r.get("cpu_baseline"), offload_128k=r)
+        print(json.dumps(line))
+        return
+    if args.workload in ("tiny", "serving_ragged", "sparse128k"):
+        r = {"tiny": lambda: run_tiny(K, W, cpu_on), "serving_ragged": lambda: run_serving_ragged(K, W, cpu_on),
+             "sparse128k": lambda: run_sparse128k(K, W, 64, cpu_on)}[args.workload]()
+        ms = r["us_per_step"] / 1e3 if "us_per_step" in r else r["ms_per_step"]
+        line = dict(base, metric="decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K", value=r["effective_kv_GBs"],
+                    unit="GB/s", ms_per_step=round(ms, 4), higher_is_better=True, dtype="f16/bf16/int8/int4 -> f32",
+                    config={"workload": args.workload + ": " + r["workload"]}, roofline=r["roofline"], cpu_baseline=r["cpu_baseline"])
+        line[args.workload] = r
         print(json.dumps(line))
         return
 
@@ -756,6 +1010,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": "attn_fused_kernel<G=1>: fp16 tier + int4 tier in one launch",
                 "achieved": round(k_bytes / (kms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(k_bytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": MHA32K_MEASURED_TRAFFIC_BYTES,
+                "traffic_source": MHA32K_TRAFFIC_SOURCE,
                 "kernel_us": round(kms * 1e3, 2), "bytes_per_launch": int(k_bytes), "launches_timed": len(kernel_ms)}
     hbm_read = measure_hbm_read_peak(cache.h)
     roofline["load_only_kernel_GBs"] = round(hbm_read, 1)
@@ -792,7 +1047,7 @@ def main():
     torch.cuda.empty_cache()
     off = None
     if not args.no_offload:
-        off = run_offload128k(args.offload_steps, 3)
+        off = run_offload128k(args.offload_steps, 3, cpu_on)
     line = {
         "metric": "decode-attn effective KV GB/s (HBM & PCIe % peak), us/token at 128K",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 4),
@@ -804,8 +1059,9 @@ def main():
                    "step_us_p50_p95_of_64_event_timed": [round(lat[len(lat) // 2] * 1e6, 1),
                                                          round(lat[int(0.95 * len(lat))] * 1e6, 1)]},
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
-        "serving_ragged": None if args.no_extra else run_serving_ragged(8, 2),
-        "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2),
+        "tiny": None if args.no_extra else run_tiny(200, 20, cpu_on),
+        "serving_ragged": None if args.no_extra else run_serving_ragged(64, 2, cpu_on),
+        "sparse_recall_128k": None if args.no_extra else run_sparse128k(8, 2, 64, cpu_on),
         "gqa_hbm": None if args.no_extra else run_gqa_hbm(),
         "key_grouping": None if args.no_extra else run_key_grouping(),
     }
