@@ -40,7 +40,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "tiny", "serving_ragged", "sparse128k", "ablation", "grid"])
+    ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "tiny", "serving_ragged", "sparse128k", "gqa_hbm", "ablation", "grid"])
+    ap.add_argument("--gqa-formats", default="", help="gqa_hbm only: comma-separated K/V formats to run, e.g. i8/i4,i4/i4 (default: all)")
     ap.add_argument("--mode", default="all", choices=["all", "staged"],
                     help="offload128k only: 'staged' runs nothing but attention calls in the staged-copy mode (for a trace)")
     ap.add_argument("--overlap-from-trace", metavar="DIR", help="no GPU work: summarise the copy/compute overlap of a rocprofv3 "
@@ -717,7 +718,7 @@ def overlap_from_trace(trace_dir, prefix):
 
 # ------------------------------------------------------------------ workload: grouped-query tiers resident in HBM
 
-def run_gqa_hbm(reps=12):
+def run_gqa_hbm(reps=12, only=None):
     """32 q / 8 kv heads, batch 4, one HBM-resident tier per case (~0.55-0.6 GB per launch): the attention
     launch alone (HIP event pair), i.e. the matrix-core kernel's rate per stored format."""
     import torch
@@ -729,6 +730,8 @@ def run_gqa_hbm(reps=12):
     rows = []
     for fmt, N, dt in ((("i8", "i8"), 65536, torch.float16), (("i8", "i4"), 81920, torch.float16), (("i4", "i4"), 131072, torch.float16),
                        (("f16", "f16"), 32768, torch.float16), (("bf16", "bf16"), 32768, torch.bfloat16)):
+        if only and "/".join(fmt) not in only:
+            continue
         fp = "f16" if dt == torch.float16 else "bf16"
         tiers = [TierConfig(fp, fp, 10**9, 128, N // 128 + 2)] if fmt[0] in ("f16", "bf16") else \
                 [TierConfig(fp, fp, 256, 128, 3), TierConfig(fmt[0], fmt[1], 10**9, 128, N // 128 + 2)]
@@ -743,20 +746,26 @@ def run_gqa_hbm(reps=12):
             for i in range(3):
                 cache.decode(q[i])
             s0 = cache.stats()
+            # the launch four times back to back between one event pair (the pair's own cost, a few microseconds of
+            # marker dispatch, spread over four launches: what rocprofv3 reports as the kernel's duration), `reps` samples
+            B.ttkv_time_attn_repeat(cache.h, 4)
             B.ttkv_time_attn(cache.h, reps)
             for i in range(reps):
                 cache.decode(q[i % 4])
             ms = sorted(B.ttkv_read_attn_timing(cache.h))
             B.ttkv_time_attn(cache.h, 0)
+            B.ttkv_time_attn_repeat(cache.h, 1)
             us = ms[len(ms) // 2] * 1e3
             rows.append({"tier": f"K {fmt[0]} / V {fmt[1]} x {N} tokens", "bytes_per_launch": int(total), "kernel_us": round(us, 1),
                          "GBs": round(total / us / 1e3, 1), "frac_of_hbm_peak": round(total / us / 1e3 / HBM_PEAK_GBS, 4),
+                         "kernel_us_min_max": [round(ms[0] * 1e3, 1), round(ms[-1] * 1e3, 1)],
                          "matrix_core_launches": cache.stats()["mfma_launches"] - s0["mfma_launches"]})
         finally:
             cache.close()
             del K, V
             torch.cuda.empty_cache()
-    return {"workload": "batch 4, 32 q / 8 kv heads (4 query heads per KV head), one tier in HBM per row, attention launch alone",
+    return {"workload": "batch 4, 32 q / 8 kv heads (4 query heads per KV head), one tier in HBM per row, attention launch alone "
+                        "(x4 back to back per event pair, median of 12 samples)",
             "rows": rows}
 
 
@@ -957,6 +966,15 @@ def main():
                 "unit": "TB/s", "n_gpus": 1, "steps": 24, "warmup": 3, "ms_per_step": None, "higher_is_better": True,
                 "scaling": "weak", "vs_baseline": None, "dtype": "f16/int8/int4 -> f32", "data": "synthetic",
                 "config": {"workload": "grid: " + r["workload"]}, "grid": r}
+        print(json.dumps(line))
+        return
+    if args.workload == "gqa_hbm":
+        r = run_gqa_hbm(12, [x for x in args.gqa_formats.split(",") if x] or None)
+        worst = min(row["GBs"] for row in r["rows"])
+        line = {"metric": "decode-attn effective KV GB/s of the grouped-query kernel per stored format (HBM-resident)", "value": worst,
+                "unit": "GB/s", "n_gpus": 1, "steps": 12, "warmup": 3, "ms_per_step": None, "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f16/int8/int4 -> f32", "data": "synthetic",
+                "config": {"workload": "gqa_hbm: " + r["workload"]}, "gqa_hbm": r}
         print(json.dumps(line))
         return
     if args.workload == "ablation":
