@@ -133,7 +133,7 @@ def build_mha32k(steps_total, N=32768, slow_k="i4"):
 
 def algorithmic_bytes(cache):
     """Stored bytes the step must read: codes + scales + zeros + fp K/V of every live token."""
-    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68}
+    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68, "i4c": 72}
     total, by_tier = 0, []
     for t, cfg in enumerate(cache.cfg):
         n = int(cache.len[t].sum()) * cache.Hkv * (per[cfg.k_fmt] + per[cfg.v_fmt])
@@ -199,7 +199,7 @@ def oracle_sample(tier_specs, max_tokens, Hq, Hkv, heads, seqs, steps_in, step, 
     rows = np.concatenate([np.arange(h * G, (h + 1) * G) for h in heads])
     cores = min(len(os.sched_getaffinity(0)), len(rows))      # the oracle's threads run over query heads
     secs, bytes_, err = 0.0, 0, 0.0
-    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68}
+    per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68, "i4c": 72}
     for b, K, V in seqs:
         ora = OracleCache(1, G * len(heads), len(heads), 128, tier_specs, max_tokens)
         ora.load(0, K[heads].float().cpu().numpy(), V[heads].float().cpu().numpy())
@@ -729,6 +729,7 @@ def run_gqa_hbm(reps=12, only=None):
     gen.manual_seed(SEED + 7)
     rows = []
     for fmt, N, dt in ((("i8", "i8"), 65536, torch.float16), (("i8", "i4"), 81920, torch.float16), (("i4", "i4"), 131072, torch.float16),
+                       (("i8", "i4c"), 81920, torch.float16), (("i4", "i4c"), 131072, torch.float16),
                        (("f16", "f16"), 32768, torch.float16), (("bf16", "bf16"), 32768, torch.bfloat16)):
         if only and "/".join(fmt) not in only:
             continue

@@ -31,6 +31,13 @@
  *                    I8_SYM_G32: codes = 128 x int8, meta = 4 x fp16 scale
  *                    I4_ASYM_G64: codes = 64 B (element 2i low nibble, 2i+1 high
  *                                 nibble of byte i), meta = fp16 {s0, z0, s1, z1}
+ *                    I4_ASYM_G64_T32 (V): Q_4bit exactly as I4_ASYM_G64 (same codes, same meta rows),
+ *                                 but the codes of 32 consecutive tokens (aligned to multiples of 32
+ *                                 in the block) are stored as one 2 KiB group in the operand order
+ *                                 of the matrix cores: the group's 16-byte piece p = 64 hh + 16 kg + c
+ *                                 (hh 0..1, kg 0..3, c 0..15) holds four 32-bit words w = 0..3; word w
+ *                                 carries channel 16 (4 hh + w) + c of eight tokens, nibble j (bits
+ *                                 4j..4j+3) = token {0, 2, 16, 18, 1, 3, 17, 19}[j] + 4 kg of the group
  *                    I4_ASYM_T128 (K): codes as I4_ASYM_G64; km = 4: the meta rows of
  *                                 tokens [128 g, 128 g + 128) of a block together hold
  *                                 fp16 {scale, zero} x 128 channels of token group g
@@ -71,6 +78,12 @@ typedef enum {
   TTKV_I8_SYM_G32 = 2,  /* Q_8bit: symmetric int8, group 32 along head_dim, fp16 scale */
   TTKV_I4_ASYM_G64 = 3, /* Q_4bit: asymmetric int4, group 64, fp16 scale + zero */
   TTKV_F32 = 4,         /* source format of ttkv_quantize_append only */
+  TTKV_I4_ASYM_G64_T32 = 6, /* values only: Q_4bit (Sec. 4.2) with the codes of every 32 tokens stored channel-major
+                           ("Block record" above), so that the grouped-query kernel feeds them to the matrix cores
+                           without transposing them: the decompressed values are those of I4_ASYM_G64 bit for bit.
+                           For caches with >= 2 query heads per KV head (UNSUPPORTED otherwise); K of the tier:
+                           I8_SYM_G32 or I4_ASYM_G64; tokens arrive in whole aligned groups of 32 (eviction of whole
+                           blocks, appends of multiples of 32); last tier of a chain only. */
   TTKV_I4_ASYM_T128 = 5 /* keys only: asymmetric int4 where a group is one channel over 128 consecutive
                            tokens (keys carry the larger dynamic range, Sec. 3 / 4.2, in a few channels:
                            such a channel then sets no scale but its own).  V of the tier: I4_ASYM_G64.

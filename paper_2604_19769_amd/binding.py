@@ -14,9 +14,10 @@ TTKV_MAX_SLOTS = 16
 TTKV_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(6)
-F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32, I4_ASYM_T128 = range(6)
+F16, BF16, I8_SYM_G32, I4_ASYM_G64, F32, I4_ASYM_T128, I4_ASYM_G64_T32 = range(7)
 MEM_DEVICE, MEM_HOST_PINNED = 0, 1
-FMT_NAMES = {"f16": F16, "bf16": BF16, "i8": I8_SYM_G32, "i4": I4_ASYM_G64, "f32": F32, "i4t": I4_ASYM_T128}
+FMT_NAMES = {"f16": F16, "bf16": BF16, "i8": I8_SYM_G32, "i4": I4_ASYM_G64, "f32": F32, "i4t": I4_ASYM_T128,
+             "i4c": I4_ASYM_G64_T32}   # i4c: values as i4, codes stored channel-major per 32 tokens
 
 
 class ttkv_tier(C.Structure):

@@ -14,7 +14,7 @@ from . import binding as B
 @dataclass
 class TierConfig:
     k_fmt: str                 # 'f16' | 'bf16' | 'i8' | 'i4' | 'i4t' (keys of the last tier: int4 grouped over 128 tokens per channel)
-    v_fmt: str
+    v_fmt: str                 # the same, or 'i4c' (last tier, >= 2 query heads per KV head: int4 as 'i4', stored channel-major per 32 tokens)
     capacity: int              # eviction threshold in tokens (L_fast for tier 0)
     block_tokens: int          # B_blk
     ring_blocks: int           # records per sequence ring
@@ -23,7 +23,7 @@ class TierConfig:
     summary: bool = False      # keep mean-key summaries (block identification)
 
 
-_SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 8), "i4t": (64, 4)}
+_SECTION_BYTES = {"f16": (256, 0), "bf16": (256, 0), "i8": (128, 8), "i4": (64, 8), "i4t": (64, 4), "i4c": (64, 8)}
 
 
 class TieredCache:

@@ -25,7 +25,12 @@ ttkv_status validate_cache(const ttkv_cache *c) {
     if (!attn_supported(T.k_fmt, T.v_fmt, c->n_q_heads / c->n_kv_heads)) return TTKV_ERR_UNSUPPORTED;
     if (T.mem != TTKV_MEM_DEVICE && T.mem != TTKV_MEM_HOST_PINNED) return TTKV_ERR_INVALID_ARG;
     if (T.block_tokens < 64 || T.block_tokens % 64) return TTKV_ERR_INVALID_ARG;
-    if (T.v_fmt == TTKV_I4_ASYM_T128) return TTKV_ERR_UNSUPPORTED;            // a key format
+    if (T.v_fmt == TTKV_I4_ASYM_T128 || T.k_fmt == TTKV_I4_ASYM_G64_T32) return TTKV_ERR_UNSUPPORTED;   // a key / a value format
+    if (T.v_fmt == TTKV_I4_ASYM_G64_T32) {
+      if (t == 0 || t + 1 < c->n_tiers) return TTKV_ERR_UNSUPPORTED;          // whole groups arrive; nothing passes through
+      for (int b = 0; b < c->batch; ++b)
+        if (T.len[b] % 32) return TTKV_ERR_INVALID_ARG;
+    }
     if (T.k_fmt == TTKV_I4_ASYM_T128) {
       if (T.block_tokens % 128) return TTKV_ERR_INVALID_ARG;
       if (t == 0 || t + 1 < c->n_tiers) return TTKV_ERR_UNSUPPORTED;          // whole groups arrive; nothing passes through
@@ -108,7 +113,7 @@ int default_items(const ttkv_cache *c) {
   for (int t = 0; t < c->n_tiers; ++t) {
     const ttkv_tier &T = c->tier[t];
     if (!attn_mfma_fits(T.k_fmt, T.v_fmt, G)) return 2560;
-    special |= T.k_fmt == TTKV_I4_ASYM_T128 || (T.k_fmt == TTKV_I8_SYM_G32 && T.v_fmt == TTKV_I4_ASYM_G64);
+    special |= T.k_fmt == TTKV_I4_ASYM_T128 || (T.k_fmt == TTKV_I8_SYM_G32 && T.v_fmt != T.k_fmt);
   }
   if (!attn_mfma_pays(G, special)) return 2560;
   for (int t = 0; t < c->n_tiers; ++t)
@@ -334,6 +339,7 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
   if ((is_fp(T.k_fmt) && T.k_fmt != src_fmt) || (is_fp(T.v_fmt) && T.v_fmt != src_fmt)) return TTKV_ERR_UNSUPPORTED;
   if (n_tokens == 0) return TTKV_OK;
   if (T.k_fmt == TTKV_I4_ASYM_T128 && n_tokens % 128) return TTKV_ERR_INVALID_ARG;   // whole token groups only
+  if (T.v_fmt == TTKV_I4_ASYM_G64_T32 && n_tokens % 32) return TTKV_ERR_INVALID_ARG;
   const int b0 = seq < 0 ? 0 : seq, b1 = seq < 0 ? c->batch : seq + 1;
   for (int b = b0; b < b1; ++b)
     if (T.len[b] + n_tokens > ring_tokens(T)) return TTKV_ERR_CAPACITY;

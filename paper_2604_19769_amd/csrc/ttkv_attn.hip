@@ -544,7 +544,9 @@ __global__ __launch_bounds__(256) void merge_kernel(const MergeArgs a) {
 int attn_group_width(int Gtot) { return Gtot % 2 == 0 ? 2 : 1; }
 
 bool attn_supported(int k_fmt, int v_fmt, int G) {
-  (void)G;
+  // values stored channel-major per 32 tokens exist for the matrix-core kernel only (two or more heads per KV head)
+  if (v_fmt == TTKV_I4_ASYM_G64_T32) return G >= 2 && (k_fmt == TTKV_I8_SYM_G32 || k_fmt == TTKV_I4_ASYM_G64);
+  if (k_fmt == TTKV_I4_ASYM_G64_T32) return false;
   if (k_fmt == TTKV_I4_ASYM_T128 || v_fmt == TTKV_I4_ASYM_T128) return k_fmt == TTKV_I4_ASYM_T128 && v_fmt == TTKV_I4_ASYM_G64;
   if (k_fmt == v_fmt) return is_tier_fmt(k_fmt);
   return k_fmt == TTKV_I8_SYM_G32 && v_fmt == TTKV_I4_ASYM_G64;

@@ -20,7 +20,8 @@ template <> struct Fmt<TTKV_BF16> { static constexpr int ROWB = 256, LPT = 16, T
 template <> struct Fmt<TTKV_I8_SYM_G32> { static constexpr int ROWB = 128, LPT = 8, TPL = 8, EPL = 16; };
 template <> struct Fmt<TTKV_I4_ASYM_G64> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };
 template <> struct Fmt<TTKV_I4_ASYM_T128> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };   // rows as int4
-template <int F> constexpr bool is_i4() { return F == TTKV_I4_ASYM_G64 || F == TTKV_I4_ASYM_T128; }
+template <> struct Fmt<TTKV_I4_ASYM_G64_T32> { static constexpr int ROWB = 64, LPT = 4, TPL = 16, EPL = 32; };   // bytes per token as int4
+template <int F> constexpr bool is_i4() { return F == TTKV_I4_ASYM_G64 || F == TTKV_I4_ASYM_T128 || F == TTKV_I4_ASYM_G64_T32; }
 
 // Streaming loads: K/V bytes are read exactly once per launch, so they are fetched with the
 // non-temporal hint (no reuse expected).  On MI355X a load-only kernel moves 6.5-7.0 TB/s this way

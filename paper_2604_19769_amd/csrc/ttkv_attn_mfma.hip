@@ -20,16 +20,22 @@
 //   The softmax is per column (lane-local over 4 tokens, two lane exchanges over kg); its scale
 //   is applied inside the exponent.
 //   V rows are loaded like K rows and dequantized in packed fp16 while the lane still owns
-//   one token and one group: (o + n) * s - o * s in one fused multiply-add (o a power of two),
-//   i.e. code x scale rounded once, to nearest even.  A product with the identity matrix brings
+//   one token and one group: the centred code (int8: signed code, int4: code - 8) is taken out of the
+//   splice exactly and multiplied by the scale, one rounding to nearest even.  A product with the identity matrix brings
 //   the tile from [token][channel] to [channel][token]: the fp32 result (exact) has lane (c, kg)
 //   holding channel-row c for tokens 4 kg .. 4 kg + 3, exactly the A layout of
 //       O[channel][column] += sum_token V^T[channel][token] * P[token][column].
-//   Two 16-token tiles feed one 32-deep product.  The int4 zero points, and the 128 that the
-//   int8 splice leaves on every code, ride along as a 4-channel V (the meta words transposed
-//   the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32.  P is rounded to
-//   fp16 once and that rounded value is used for the row sum as well, so the normalisation is
-//   consistent.
+//   Two 16-token tiles feed one 32-deep product.  The int4 zero points and scales ride along as a
+//   4-channel V (the meta words transposed the same way), giving sum_t p_t z_t and sum_t p_t s_t per group in fp32
+//   (zero point + 8 x scale is what the centred codes leave out).  P is rounded to
+//   fp16 once and that rounded value is used for the row sum as well, so the normalisation is consistent.
+//   Values stored channel-major per 32 tokens (TTKV_I4_ASYM_G64_T32) need neither the dequantization nor the
+//   transposition: a lane's 32-bit word IS eight tokens of one channel, i.e. after the splice the A operand of a
+//   32-deep product, and the token's scale goes into the other operand instead: B_g = fp16(p_t * s_{t,g}), one per
+//   channel group g (the four meta values of a token reach the score layout through the selector product that the
+//   key meta uses).  The splice offsets (1024 / 64 per nibble position) and the centre 8 are removed by one more
+//   product of B_g with a constant operand of "code 8" words; the zero points and the centre come back as
+//   sum_t p_t (z_{t,g} + 8 s_{t,g}) in fp32 on the vector units.
 //   Keys grouped over 128 tokens per channel have no channel groups (one column per head); the token
 //   group's scales fold into the q operand, carried as fp16 rounded product + exact remainder
 //   (two products per step), rebuilt for every 64 tokens in flight.
@@ -87,7 +93,7 @@ __device__ __forceinline__ uint32_t pk(float x, float y) {
 
 template <int F>
 constexpr int n_groups() {
-  return F == TTKV_I4_ASYM_G64 ? 2 : (F == TTKV_I8_SYM_G32 ? 4 : 1);
+  return (F == TTKV_I4_ASYM_G64 || F == TTKV_I4_ASYM_G64_T32) ? 2 : (F == TTKV_I8_SYM_G32 ? 4 : 1);
 }
 // Channel, relative to the lane's 32-channel slice, of k-value i of step s: step s takes
 // the packed registers 2s and 2s+1 that unpack16 produced (int4 pairs are (0,4) (1,5) | (2,6) (3,7)).
@@ -179,18 +185,21 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
-  constexpr int NT = NLK == 4 ? 2 : 4 / NLK;                 // tiles in flight per wave (int4: 4; with 2 the kernel is 10 % slower)
+  // int8 keys (with int8 or int4 values): rows prefetched through LDS.  Measured per format against the register
+  // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; fp16 / bf16 rows take the one-region variant further
+  // down.  int4 keys with token-major int4 values, whose unpack / dequantize / transpose arithmetic fills the issue
+  // slots, gained nothing (4.9-5.0 either way) and stay on the register loads; with channel-major values that
+  // arithmetic is gone and the waits for the loads are what is left, so they are prefetched as well.
+  constexpr bool PF = (KF == TTKV_I8_SYM_G32 && (VF == TTKV_I8_SYM_G32 || VF == TTKV_I4_ASYM_G64 || VF == TTKV_I4_ASYM_G64_T32)) ||
+                      (KF == TTKV_I4_ASYM_G64 && VF == TTKV_I4_ASYM_G64_T32);
+  // tiles in flight per wave (int4 on register loads: 4; with 2 that kernel is 10 % slower)
+  constexpr int NT = (NLK == 4 || PF) ? 2 : 4 / NLK;
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
   constexpr bool KT = KF == TTKV_I4_ASYM_T128;   // keys grouped over 128 tokens per channel: the scales fold into q
   constexpr bool KBF = KF == TTKV_BF16, VBF = VF == TTKV_BF16;
-  // int8 keys (with int8 or int4 values): rows prefetched through LDS.  Measured per format against the register
-  // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; int4 keys, whose unpack arithmetic already fills the
-  // issue slots, gain nothing (4.9-5.0 either way) and stay on the register loads; fp16 / bf16 rows take the
-  // one-region variant further down.
-  constexpr bool PF = KF == TTKV_I8_SYM_G32 && VQ;
-
+  constexpr bool VT = VF == TTKV_I4_ASYM_G64_T32;   // values channel-major per 32 tokens: no dequantization, no transposition
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, kg = lane >> 4;
@@ -288,6 +297,13 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       }
     }
   }
+  // VT: 0/1 selectors of the token's V meta value number v = 0..3 (s0, z0, s1, z1) for every column at once
+  uint32_t vm_sel[4][2];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    vm_sel[v][0] = (VT && kg == 0 && v < 2) ? (v == 0 ? 0x3C00u : 0x3C000000u) : 0u;
+    vm_sel[v][1] = (VT && kg == 0 && v >= 2) ? (v == 2 ? 0x3C00u : 0x3C000000u) : 0u;
+  }
   // byte selectors that duplicate the fp16 scale of the group of this lane's piece x out of the V meta words:
   // int4 (s0, z0, s1, z1): one piece, group kg / 2; int8 (s0, s1, s2, s3): piece x lies in group 2 x + kg / 2
   uint32_t vsel[2];
@@ -296,14 +312,18 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     const uint32_t vh = VF == TTKV_I4_ASYM_G64 ? (kg >> 1) * 2 : 2 * x + (kg >> 1);
     vsel[x] = (2 * vh) | ((2 * vh + 1) << 8) | ((2 * vh) << 16) | ((2 * vh + 1) << 24);
   }
-  // minus the splice offsets, as packed fp16 pairs: -1024, -64
-  uint32_t no_a = 0xE400E400u, no_b = 0xD400D400u;
-  asm volatile("" : "+s"(no_a), "+s"(no_b));
+  // minus (splice offset + centre) as packed fp16 pairs: int4 -(1024 + 8), -(64 + 8); int8 -(1024 + 128)
+  uint32_t no_a = 0xE408E408u, no_b = 0xD480D480u, no_c = 0xE480E480u;
+  asm volatile("" : "+s"(no_a), "+s"(no_b), "+s"(no_c));
 
   const f4 zero4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
   f4 acc[8], accz = zero4;
+  f4 accoff[VT ? 2 : 1];          // VT: sum_t B_g[t] * (splice offset of t's nibble position + 8), per channel group
+  float zs[2] = {0.0f, 0.0f};     // VT: sum_t p_t (z_{t,g} + 8 s_{t,g})
 #pragma unroll
   for (int s = 0; s < 8; ++s) acc[s] = zero4;
+#pragma unroll
+  for (int g2 = 0; g2 < (VT ? 2 : 1); ++g2) accoff[g2] = zero4;
   float m = -INFINITY, l = 0.0f;
 
   Splice sp;
@@ -349,8 +369,15 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       const uint32_t vo = FULL ? vdoff + tt * 16 * FV::ROWB : row * FV::ROWB + kg * 16;
 #pragma unroll
       for (int x = 0; x < NLK; ++x) t.kw[tt][x] = *(const uint4 *)(kb + ko + 64 * x);
+      if constexpr (VT) {
+        // piece hh = tt % 2 of the 32-token group tt / 2 (a group past the end re-reads the last live one):
+        // lane L's piece is number 64 hh + L of the group's 2 KiB
+        const uint32_t grp = FULL ? tt / 2 : min(tt / 2, (nv - 1) / 32);
+        t.vw[tt][0] = *(const uint4 *)(vb + grp * 2048 + (tt & 1) * 1024 + lane * 16);
+      } else {
 #pragma unroll
-      for (int x = 0; x < NLV; ++x) t.vw[tt][x] = *(const uint4 *)(vb + vo + 64 * x);
+        for (int x = 0; x < NLV; ++x) t.vw[tt][x] = *(const uint4 *)(vb + vo + 64 * x);
+      }
       if constexpr (KQ) t.kmeta[tt] = *(const uint2 *)(kmb + row * 8);
       if constexpr (VQ) t.vmeta[tt] = *(const uint2 *)(vmb + row * 8);
     }
@@ -362,7 +389,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   constexpr int PK = FK::ROWB / 16, PV = FV::ROWB / 16;              // pieces per row
   constexpr int NDK = TT * FK::ROWB / 1024, NDV = TT * FV::ROWB / 1024;   // copy instructions of 1 KiB per half
   constexpr int N_K = NDK + 2, N_V = NDV + 2;                          // with the two meta planes
-  static_assert(!PF || (NT == 2 && PK == 8 && NDK == 4 && (NDV == 4 || NDV == 2)), "the batch the LDS readers cover");
+  static_assert(!PF || (NT == 2 && ((PK == 8 && NDK == 4) || (PK == 4 && NDK == 2)) && (NDV == 4 || NDV == 2)),
+                "the batch the LDS readers cover");
   auto swz = [](int pieces, int r) { return pieces == 4 ? (r >> 2) & 3 : (r >> 1) & 7; };
   // per-lane byte offset of copy instruction j inside a full batch, minus j KiB (even and odd j differ for 8 pieces)
   uint32_t dko[2], dvo[2];
@@ -378,7 +406,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     return n * rowb + (((kg + 4 * x) ^ swz(pieces, n)) * 16);
   };
   const uint32_t lka0 = lds0 + piece_addr(PK, FK::ROWB, 0), lka1 = lds0 + piece_addr(PK, FK::ROWB, PK == 8 ? 1 : 0);
-  const uint32_t lva0 = lds0 + 4096 + piece_addr(PV, FV::ROWB, 0), lva1 = lds0 + 4096 + piece_addr(PV, FV::ROWB, PV == 8 ? 1 : 0);
+  const uint32_t lva0 = VT ? lds0 + 4096 + lane * 16 : lds0 + 4096 + piece_addr(PV, FV::ROWB, 0);
+  const uint32_t lva1 = lds0 + 4096 + piece_addr(PV, FV::ROWB, PV == 8 ? 1 : 0);
   const uint32_t lkm = lds0 + kTileRowsLds + n * 4, lvm = lkm + 512;
   const uint8_t *nx_head = nullptr;   // batch whose K half was issued last
   int nx_row0 = 0, nx_nv = 0;
@@ -388,7 +417,9 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     const uint8_t *kb = nx_head + nx_row0 * FK::ROWB, *kmb = nx_head + tv.k_meta_off + nx_row0 * 8;
     if (nx_nv == TT) {
       dma16<0>(kb + dko[0], wbuf); dma16<1024>(kb + dko[1], wbuf);
-      dma16<2048>(kb + dko[0], wbuf); dma16<3072>(kb + dko[1], wbuf);
+      if constexpr (NDK == 4) {
+        dma16<2048>(kb + dko[0], wbuf); dma16<3072>(kb + dko[1], wbuf);
+      }
     } else {
 #pragma unroll
       for (int j = 0; j < NDK; ++j) {
@@ -402,7 +433,9 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   };
   auto issue_v = [&]() {
     const uint8_t *vb = nx_head + tv.v_off + nx_row0 * FV::ROWB, *vmb = nx_head + tv.v_meta_off + nx_row0 * 8;
-    if (nx_nv == TT) {
+    if constexpr (VT) {   // the batch is one whole 2 KiB group (its length is a multiple of 32): copied as it lies
+      dma16<0>(vb + lane * 16, wbuf + 4096); dma16<1024>(vb + lane * 16, wbuf + 4096);
+    } else if (nx_nv == TT) {
       dma16<0>(vb + dvo[0], wbuf + 4096); dma16<1024>(vb + dvo[1], wbuf + 4096);
       if constexpr (NDV == 4) {
         dma16<2048>(vb + dvo[0], wbuf + 4096); dma16<3072>(vb + dvo[1], wbuf + 4096);
@@ -421,7 +454,8 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   auto fetch_k = [&](auto &t) {   // generic: compiled only where it is called, i.e. for the formats of PF
     u32x4 w[4];
     uint32_t mw[8];
-    lds_half_i8(lka0, lka1, lkm, w, mw);
+    if constexpr (PK == 8) lds_half_i8(lka0, lka1, lkm, w, mw);
+    else lds_half_i4x2(lka0, lkm, w, mw);
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
 #pragma unroll
@@ -539,6 +573,10 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
       const float alpha = __builtin_amdgcn_exp2f((m - mn) * cs);
       l *= alpha;
       accz *= alpha;
+      if constexpr (VT) {
+        accoff[0] *= alpha; accoff[1] *= alpha;
+        zs[0] *= alpha; zs[1] *= alpha;
+      }
 #pragma unroll
       for (int s = 0; s < 8; ++s) acc[s] *= alpha;
       m = mn;
@@ -548,6 +586,44 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 
     // ---- weighted V, two 16-token tiles per 32-deep product
     before_v();
+    if constexpr (VT) {
+      // Values channel-major per 32 tokens: tiles tp, tp + 1 are one group; its two pieces are the A operands of the
+      // eight channel blocks as they lie (after the splice), the scales ride on the weights.  What is removed with
+      // the offsets is the spliced word of eight codes 8, so that a weight's rounding error multiplies code - 8.
+      const uint32_t code8[4] = {sp.c0 | 0x00080008u, sp.c1 | 0x00800080u, sp.c0 | 0x00080008u, sp.c1 | 0x00800080u};
+#pragma unroll
+      for (int tp = 0; tp < NT; tp += 2) {
+        uint32_t Bg[2][4];       // fp16(p_t * s_{t,g}) of the pair's 8 tokens per lane, per channel group g
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int tt = tp + u;
+          // the token's meta values (s0, z0, s1, z1) in the score layout: tokens 4 kg + i of the tile, any column
+          f4 mv[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) mv[v] = mma<false>(t.vmeta[tt].x, t.vmeta[tt].y, vm_sel[v][0], vm_sel[v][1], zero4);
+          float p[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(fmaf(S[tt][i], cs, mcs));
+            l += p[i];
+            zs[0] = fmaf(p[i], fmaf(8.0f, mv[0][i], mv[1][i]), zs[0]);   // zero point + the centre 8 * scale
+            zs[1] = fmaf(p[i], fmaf(8.0f, mv[2][i], mv[3][i]), zs[1]);
+          }
+          Bg[0][2 * u] = pk(p[0] * mv[0][0], p[1] * mv[0][1]);
+          Bg[0][2 * u + 1] = pk(p[2] * mv[0][2], p[3] * mv[0][3]);
+          Bg[1][2 * u] = pk(p[0] * mv[2][0], p[1] * mv[2][1]);
+          Bg[1][2 * u + 1] = pk(p[2] * mv[2][2], p[3] * mv[2][3]);
+        }
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          uint32_t vr[16];       // word w of piece hh -> registers 4 w .. 4 w + 3: channel 16 (4 hh + w) + (lane % 16)
+          unpack16<TTKV_I4_ASYM_G64>(t.vw[tp + hh][0], vr, sp);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) acc[4 * hh + w] = mma32<false>(vr + 4 * w, Bg[hh], acc[4 * hh + w]);
+          accoff[hh] = mma32<false>(code8, Bg[hh], accoff[hh]);
+        }
+      }
+    } else {
 #pragma unroll
     for (int tp = 0; tp < NT; tp += 2) {
       uint32_t pB[4];          // softmax weights of the pair, rounded to fp16: the B operand
@@ -566,26 +642,19 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 #pragma unroll
         for (int x = 0; x < NLV; ++x) unpack16<VF>(t.vw[tt][x], vr[u] + x * (16 / NLV), sp);
         if constexpr (VQ) {
-          // codes -> code * scale in fp16 with one rounding (to nearest even), while the lane still owns one
-          // token and one group.  (o + n) * s - o * s in one fused step, o = 1024 or 64: o * s is exact while
-          // |s| <= 60; beyond that the offset is removed first.  int8 bytes come out as (code + 128) * s, the
-          // 128 leaves with the zero-point sum below.
+          // codes -> code * scale in fp16 with one rounding (to nearest even), while the lane still owns one token
+          // and one group.  The splice holds offset + code; the centred code (int8: the signed code, int4: code - 8)
+          // is taken out first, which is exact, and then scaled, so that the one rounding is relative to a value of
+          // the size of the element itself (scaling offset + code in one fused step and removing offset * scale
+          // afterwards would round a value up to the row's whole range: an error of range x 2^-11 on its smallest
+          // elements).  The int4 centre 8 * scale rejoins with the zero points at the end.
           const uint32_t vsb0 = __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel[0]);
           const uint32_t vsb1 = VF == TTKV_I8_SYM_G32 ? __builtin_amdgcn_perm(t.vmeta[tt].y, t.vmeta[tt].x, vsel[1]) : vsb0;
           const h2 vs2[2] = {as_h2(vsb0), as_h2(vsb1)};
-          if (!__any(((vsb0 | vsb1) & 0x7fffu) > 0x5380u)) {   // (an upper bound of both magnitudes)
-            const h2 na[2] = {as_h2(no_a) * vs2[0], as_h2(no_a) * vs2[1]};
-            const h2 nb = as_h2(no_b) * vs2[0];
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-              vr[u][r] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(as_h2(vr[u][r]), vs2[r / 8],
-                                                                               (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? nb : na[r / 8]));
-          } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const uint32_t no = (VF == TTKV_I4_ASYM_G64 && (r & 1)) ? no_b : no_a;
-              vr[u][r] = __builtin_bit_cast(uint32_t, (as_h2(vr[u][r]) + as_h2(no)) * vs2[r / 8]);
-            }
+          for (int r = 0; r < 16; ++r) {
+            const uint32_t no = VF == TTKV_I8_SYM_G32 ? no_c : ((r & 1) ? no_b : no_a);
+            vr[u][r] = __builtin_bit_cast(uint32_t, (as_h2(vr[u][r]) + as_h2(no)) * vs2[r / 8]);
           }
         }
       }
@@ -596,14 +665,15 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
         const uint32_t A[4] = {pk(d0[0], d0[1]), pk(d0[2], d0[3]), pk(d1[0], d1[1]), pk(d1[2], d1[3])};
         acc[s] = mma32<false>(A, pB, acc[s]);
       }
-      if constexpr (VQ) {
+      if constexpr (VF == TTKV_I4_ASYM_G64) {
         // the meta words transposed like a 4-channel V: every row group of four then accumulates
-        // sum_t p_t * (s0, z0, s1, z1) (int4) or sum_t p_t * (s0, s1, s2, s3) (int8)
+        // sum_t p_t * (s0, z0, s1, z1)
         const f4 d0 = mma<false>(t.vmeta[tp].x, t.vmeta[tp].y, id0, id1, zero4);
         const f4 d1 = mma<false>(t.vmeta[tp + 1].x, t.vmeta[tp + 1].y, id0, id1, zero4);
         const uint32_t A[4] = {pk(d0[0], d0[1]), pk(d0[2], d0[3]), pk(d1[0], d1[1]), pk(d1[2], d1[3])};
         accz = mma32<false>(A, pB, accz);
       }
+    }
     }
   };
 
@@ -724,18 +794,26 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   // chan(s, i); the zero-point sums of that channel's group are added here
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  float z[2] = {0.0f, 0.0f};   // for the channels of piece 0 / piece 1 (int8), of the one piece (int4)
-  if constexpr (VF == TTKV_I4_ASYM_G64) z[0] = z[1] = (kg >> 1) ? accz[3] : accz[1];   // sum_t p_t * zero
-  if constexpr (VF == TTKV_I8_SYM_G32) {                                               // -128 * sum_t p_t * scale
-    z[0] = -128.0f * ((kg >> 1) ? accz[1] : accz[0]);
-    z[1] = -128.0f * ((kg >> 1) ? accz[3] : accz[2]);
+  float z[2] = {0.0f, 0.0f};   // zero-point sum of the channels' group
+  if constexpr (VF == TTKV_I4_ASYM_G64)   // sum_t p_t * (zero + 8 * scale)
+    z[0] = z[1] = (kg >> 1) ? fmaf(8.0f, accz[2], accz[3]) : fmaf(8.0f, accz[0], accz[1]);
+  if constexpr (VT) {   // per channel group: the lanes' zero-point sums over their tokens, minus the splice offsets
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+      zs[g2] += __shfl_xor(zs[g2], 16);
+      zs[g2] += __shfl_xor(zs[g2], 32);
+      z[g2] = zs[g2] - accoff[g2][0];   // every row of accoff holds the column's sum
+    }
   }
   float (*w_acc)[128] = (float (*)[128])wbuf;   // [head][channel]; the wave's last batch has been consumed
   if (n < Gr) {
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) w_acc[n][slice_channel<VF>(kg, chan<VF>(s, i))] = acc[s][i] + z[s / 4];
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (VT) w_acc[n][16 * s + 4 * kg + i] = acc[s][i] + z[s / 4];   // block s row 4 kg + i, as the product leaves it
+        else w_acc[n][slice_channel<VF>(kg, chan<VF>(s, i))] = acc[s][i] + z[s / 4];
+      }
     if (kg == 0) {
       s_m[wave][n] = m * cs;   // log2 domain
       s_l[wave][n] = l;
@@ -796,6 +874,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
     case TTKV_I4_ASYM_T128 * 8 + TTKV_I4_ASYM_G64:
       if constexpr (T128) TTKV_MFMA_CASE(TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, 0);
       break;
+    case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64_T32:
+      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64_T32, GQ);
+      break;
+    case TTKV_I4_ASYM_G64 * 8 + TTKV_I4_ASYM_G64_T32:
+      if constexpr (GQ <= 8 || WIDE) TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64_T32, GQ);
+      break;
     default:
       if constexpr (GQ <= 8 || WIDE) TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, GQ);
       break;
@@ -835,6 +919,7 @@ int mfma_block_heads(int k_fmt) { return k_fmt == TTKV_I8_SYM_G32 ? 8 : 16; }
 // Do the kernel's cases take these formats?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
   if (G < 2) return false;
+  if (v_fmt == TTKV_I4_ASYM_G64_T32) return k_fmt == TTKV_I8_SYM_G32 || k_fmt == TTKV_I4_ASYM_G64;
   if (k_fmt == TTKV_I4_ASYM_G64) return v_fmt == k_fmt;
   return true;
 }
@@ -866,7 +951,7 @@ MfmaShape mfma_shape(const FusedArgs &a) {
     m.ok &= attn_mfma_fits(tv.k_fmt, tv.v_fmt, G);
     m.heads = std::min(m.heads, mfma_block_heads(tv.k_fmt));
     m.t128 |= tv.k_fmt == TTKV_I4_ASYM_T128;
-    m.mixed |= tv.k_fmt == TTKV_I8_SYM_G32 && tv.v_fmt == TTKV_I4_ASYM_G64;
+    m.mixed |= tv.k_fmt == TTKV_I8_SYM_G32 && tv.v_fmt != tv.k_fmt;
     quant |= quantized_per_token(tv.k_fmt);
   }
   m.heads = std::min(m.heads, G);

@@ -21,7 +21,8 @@ inline FmtBytes fmt_bytes(int fmt) {
     case TTKV_F16:
     case TTKV_BF16: return {256, 0};
     case TTKV_I8_SYM_G32: return {128, 8};
-    case TTKV_I4_ASYM_G64: return {64, 8};
+    case TTKV_I4_ASYM_G64:
+    case TTKV_I4_ASYM_G64_T32: return {64, 8};
     case TTKV_I4_ASYM_T128: return {64, 4};   // 128 tokens x 4 B = 128 channels x fp16 {scale, zero}
     default: return {0, 0};
   }
@@ -141,7 +142,9 @@ struct Handle {
   } while (0)
 
 inline bool is_fp(int f) { return f == TTKV_F16 || f == TTKV_BF16; }
-inline bool is_tier_fmt(int f) { return (f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64) || f == TTKV_I4_ASYM_T128; }
+inline bool is_tier_fmt(int f) {
+  return (f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64) || f == TTKV_I4_ASYM_T128 || f == TTKV_I4_ASYM_G64_T32;
+}
 
 ttkv_status validate_cache(const ttkv_cache *c);
 

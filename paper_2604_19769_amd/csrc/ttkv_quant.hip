@@ -314,6 +314,53 @@ __global__ __launch_bounds__(128) void convert_keys_t128_kernel(const ConvArgs a
   }
 }
 
+// Values of a tier that stores Q_4bit codes channel-major per 32 tokens (TTKV_I4_ASYM_G64_T32): one workgroup per
+// (group of 32 arriving tokens, KV head, entry).  Rows are quantized exactly as convert_rows_kernel does (a 16-lane
+// group per row, 8 channels per lane); the meta rows go to their token-major section as usual, the codes meet in LDS
+// and leave as the group's 2 KiB in the operand order of the matrix-core kernel: piece p = 64 hh + 16 kg + c, word w:
+// channel 16 (4 hh + w) + c, nibble j: token kTok[j] + 4 kg.
+__global__ __launch_bounds__(256) void convert_values_t32_kernel(const ConvArgs a) {
+  __shared__ uint8_t s_code[32][128];
+  const int g = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
+  const int seq = a.seq_id[j];
+  const int l16 = threadIdx.x & 15;
+  int row0;
+  uint8_t *head = head_ptr(a.dst, seq, a.dst_rec_base[j], wrap(a.dst_first_tok[j] + g * 32, a.dst), h, &row0);   // row0 % 32 == 0
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (threadIdx.x >> 4), t = g * 32 + r;
+    float x[8];
+    if (!a.s.from_tier) {
+      load8_flat(a.s.v_flat, a.s.flat_fmt, ((int64_t)j * a.Hkv + h) * a.n_tokens + t, l16, x);
+    } else {
+      int row;
+      const uint8_t *src = head_ptr(a.s.src, seq, a.s.src_rec_base[j], wrap(a.s.src_first_tok[j] + t, a.s.src), h, &row);
+      load8_tier(src, a.s.src.v_fmt, a.s.src.v_off, a.s.src.v_meta_off, row, l16, x);
+    }
+    for (int u = 0; u < a.n_via; ++u) roundtrip<8, 4, 8>(a.via_v[u], x);
+    int c[8];
+    uint16_t sh, zh;
+    q2_group<8, 8>(x, c, &sh, &zh);
+    if ((l16 & 7) == 0) *(uint32_t *)(head + a.dst.v_meta_off + (row0 + r) * 8 + (l16 >> 3) * 4) = (uint32_t)sh | ((uint32_t)zh << 16);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s_code[r][l16 * 8 + i] = (uint8_t)c[i];
+  }
+  __syncthreads();
+  const int kTok[8] = {0, 2, 16, 18, 1, 3, 17, 19};
+  uint32_t *out = (uint32_t *)(head + a.dst.v_off + row0 * 64);     // the group's 2 KiB: 512 words, two per thread
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int d = threadIdx.x + 256 * k;          // word index: piece d / 4, word d % 4
+    const int p = d >> 2, w = d & 3;
+    const int hh = p >> 6, kg = (p >> 4) & 3, c = p & 15;
+    const int ch = 16 * (4 * hh + w) + c;
+    uint32_t v = 0;
+#pragma unroll
+    for (int jn = 0; jn < 8; ++jn) v |= (uint32_t)s_code[kTok[jn] + 4 * kg][ch] << (4 * jn);
+    out[d] = v;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
@@ -325,6 +372,13 @@ hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
     v.which0 = 1;
     hipLaunchKernelGGL(convert_rows_kernel, dim3((unsigned)((total + 15) / 16), 1), dim3(256), 0, s, v);
     hipLaunchKernelGGL(convert_keys_t128_kernel, dim3(a.n_tokens / 128, a.Hkv, a.n_seq), dim3(128), 0, s, a);
+    *n_kernels += 2;
+    return hipGetLastError();
+  }
+  if (a.dst.v_fmt == TTKV_I4_ASYM_G64_T32) {
+    // keys row by row, values by groups of 32 tokens (the caller has checked alignment)
+    hipLaunchKernelGGL(convert_rows_kernel, dim3((unsigned)((total + 15) / 16), 1), dim3(256), 0, s, a);   // which0 = 0: K only
+    hipLaunchKernelGGL(convert_values_t32_kernel, dim3(a.n_tokens / 32, a.Hkv, a.n_seq), dim3(256), 0, s, a);
     *n_kernels += 2;
     return hipGetLastError();
   }

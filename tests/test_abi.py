@@ -82,6 +82,28 @@ def test_invalid_arguments_are_status_codes():
     assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1
     assert L.ttkv_quantize_append(h, C.byref(c), 1, -1, dummy, dummy, B.F16, 4, 0, None) == B.ERR_UNSUPPORTED
     c.tier[1].k_fmt = c.tier[1].v_fmt = B.I8_SYM_G32
+    # values stored channel-major per 32 tokens: a value format of the last tier, int8 or int4 keys, >= 2 heads per KV
+    # head, whole groups of 32 tokens
+    c.tier[2].v_fmt = B.I4_ASYM_G64_T32
+    assert B.ttkv_record_bytes(c, 2) == 1024 * 2 * 144
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 48, 0, None) == B.ERR_INVALID_ARG
+    assert L.ttkv_quantize_append(h, C.byref(c), 2, -1, dummy, dummy, B.F16, 0, 0, None) == B.OK
+    c._keep[8][:] = 40                                                     # tier 2's len[]: not whole groups
+    assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1
+    c._keep[8][:] = 0
+    c.tier[2].k_fmt = B.F16
+    assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1        # fp16 keys with int4 values: no kernel
+    c.tier[2].k_fmt = B.I4_ASYM_G64_T32
+    assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1        # not a key format
+    c.tier[2].k_fmt = B.I8_SYM_G32
+    assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == 0         # K 8-bit + these values: fine (nothing cached yet)
+    c.n_q_heads = c.n_kv_heads
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_UNSUPPORTED   # one head per KV head
+    c.n_q_heads = 8
+    c.tier[2].k_fmt = c.tier[2].v_fmt = B.I4_ASYM_G64
+    c.tier[1].v_fmt = B.I4_ASYM_G64_T32
+    assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_UNSUPPORTED   # a middle tier
+    c.tier[1].v_fmt = B.I8_SYM_G32
     # block_tokens not a multiple of 64, batch out of range, GQA ratio
     c.tier[0].block_tokens = 100
     assert L.ttkv_quantize_append(h, C.byref(c), 0, -1, dummy, dummy, B.F16, 1, 0, None) == B.ERR_INVALID_ARG

@@ -387,3 +387,79 @@ def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host, n_slots):
         assert (st["mfma_launches"] > 0) == (Hq // Hkv >= 2)
     finally:
         p.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype,kfmt,host,n_slots", [(8, 2, "f16", "i8", False, 0), (8, 2, "f16", "i4", False, 0), (4, 2, "bf16", "i8", False, 0),
+                                                            (6, 2, "f16", "i4", False, 0), (16, 2, "f16", "i8", False, 0), (16, 2, "bf16", "i4", False, 0),
+                                                            (32, 2, "f16", "i4", False, 0), (8, 2, "f16", "i8", True, 0), (8, 2, "bf16", "i4", True, 2),
+                                                            (8, 2, "f16", "i4", True, 3)])
+def test_values_stored_channel_major_per_32_tokens(Hq, Hkv, dtype, kfmt, host, n_slots):
+    """Last tier with Q_4bit values stored channel-major per 32 tokens (the matrix cores take them without a
+    transposition): the codes, decoded from that packing, and the scales / zeros equal the oracle's Q_4bit bit for
+    bit -- bulk load of whole groups, evictions of 64-token blocks, through an int8 tier in the three-tier cases --
+    and the outputs stay within tolerance with peaked softmax; int8 and int4 keys, 2 to 16 heads per KV head (one-
+    and two-pass cases), HBM and pinned host (read in place, through staging slots, bulk load stored by the kernels)."""
+    three = host
+    tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=64, ring_blocks=6)]
+    if three:
+        tiers.append(dict(k_fmt="i8", v_fmt="i8", capacity=512, block_tokens=128, ring_blocks=8))
+    tiers.append(dict(k_fmt=kfmt, v_fmt="i4c", capacity=10**9, block_tokens=256 if host else 128, ring_blocks=30,
+                      mem="host" if host else "device"))
+    p = Pair(3, Hq, Hkv, tiers, dtype, n_slots=n_slots, host_append_direct=host and n_slots == 3)
+    try:
+        g = synth.rng(synth.SEED_BASE + 80 + Hq)
+        fixed = 255 + (512 if three else 0)
+        for b, n_old in enumerate((32 * 1, 32 * 33, 32 * 90 + 64)):       # whole groups of 32 in the last tier
+            k, v = synth.kv((synth.SEED_BASE + 80) * 31 + b, Hkv, fixed + n_old, dtype)
+            k[:, ::97] *= 4.0                                              # a few keys aligned with nothing in particular: O(1) weights
+            p.load(b, synth.round_to(k, dtype), v)
+        p.assert_state_equal()
+        worst = 0.0
+        for s in range(200):
+            q = synth.normal(g, (3, Hq, 128), dtype)
+            kn, vn = synth.normal(g, (3, Hkv, 128), dtype), synth.normal(g, (3, Hkv, 128), dtype)
+            r = p.step(q, kn, vn)
+            worst = max(worst, assert_close(r[0], r[2], f"out step {s}"))
+            assert_close(r[1], r[3], f"lse step {s}")
+            if s % 100 == 99:
+                p.assert_state_equal()
+        st = p.gpu.stats()
+        assert st["demotions"] == sum(sum(d) for d in p.ora.demotions) >= 6
+        assert st["mfma_launches"] > 0 and st["h2d_bytes"] == p.ora.h2d_bytes
+        for b in range(3):
+            total = sum(int(p.gpu.len[t][b]) for t in range(len(tiers)))
+            p.assert_locate_equal(b, [0, total // 2, total - 1])
+    finally:
+        p.close()
+
+
+def test_channel_major_values_are_refused_where_no_kernel_takes_them():
+    """One query head per KV head runs on the vector kernel, which reads token-major rows only; the format is for
+    the last tier and for whole groups of 32 tokens."""
+    ok = [dict(k_fmt="f16", v_fmt="f16", capacity=256, block_tokens=64, ring_blocks=6),
+          dict(k_fmt="i8", v_fmt="i4c", capacity=10**9, block_tokens=128, ring_blocks=8)]
+    p = Pair(1, 4, 4, ok, "f16")           # 4 q / 4 kv heads
+    try:
+        k = dev(np.zeros((1, 4, 64, 128), np.float32), "f16")
+        with pytest.raises(B.TTKVError) as e:
+            p.gpu.append(1, k, k)
+        assert e.value.status == B.ERR_UNSUPPORTED
+    finally:
+        p.close()
+    p = Pair(1, 8, 4, ok, "f16")
+    try:
+        k = dev(np.zeros((1, 4, 48, 128), np.float32), "f16")
+        with pytest.raises(B.TTKVError) as e:
+            p.gpu.append(1, k, k)            # 48 tokens: not whole groups of 32
+        assert e.value.status == B.ERR_INVALID_ARG and int(p.gpu.len[1][0]) == 0
+        middle = [ok[0], dict(k_fmt="i8", v_fmt="i4c", capacity=512, block_tokens=128, ring_blocks=8),
+                  dict(k_fmt="i4", v_fmt="i4", capacity=10**9, block_tokens=128, ring_blocks=8)]
+    finally:
+        p.close()
+    p = Pair(1, 8, 4, middle, "f16")
+    try:
+        with pytest.raises(B.TTKVError) as e:
+            p.gpu.append(0, k, k)
+        assert e.value.status == B.ERR_UNSUPPORTED    # a middle tier: values would have to pass through it
+    finally:
+        p.close()

@@ -30,7 +30,7 @@ def tier_positions(lo, hi, chunk, bt):
     """Sequence positions inside [lo, hi) worth a planted key: both sides of the first 16-, 32- and 64-token tile
     boundaries, of the first chunk boundary, of the last whole chunk and block, and the range's two ends."""
     n = hi - lo
-    rel = {0, 1, 15, 16, 31, 32, 63, 64, chunk - 1, chunk, bt - 1, bt, n - 2, n - 1,
+    rel = {0, 1, 2, 3, 4, 15, 16, 17, 18, 19, 31, 32, 63, 64, chunk - 1, chunk, bt - 1, bt, n - 2, n - 1, n - 31, n - 32, n - 33,
            n // chunk * chunk - 1, n // chunk * chunk, n // bt * bt - 1, n // bt * bt, n // 64 * 64 - 1, n // 64 * 64,
            n // 16 * 16 - 1, n // 16 * 16}
     return sorted(lo + r for r in rel if 0 <= r < n)
@@ -105,6 +105,21 @@ def test_dominant_key_at_tile_chunk_and_tier_ends(Hq, Hkv, dtype, slow):
     try:
         run_planted(p, 2, Hq, Hkv, dtype, [1033, 2890], synth.SEED_BASE + 300 + Hq, chunks=(256, 256))
         assert (p.gpu.stats()["mfma_launches"] > 0) == (Hq > Hkv)
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 2), (8, 2), (16, 2), (32, 2)])
+@pytest.mark.parametrize("dtype,kfmt", [("f16", "i8"), ("bf16", "i4")])
+def test_dominant_key_with_values_stored_channel_major(Hq, Hkv, dtype, kfmt):
+    """The last tier's values as Q_4bit stored channel-major per 32 tokens (whole groups only): every nibble position
+    of a group, both sides of the 32-token group, tile, chunk and block boundaries inside the tier."""
+    tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=64, ring_blocks=5),
+             dict(k_fmt=kfmt, v_fmt="i4c", capacity=10**9, block_tokens=128, ring_blocks=24)]
+    p = Pair(2, Hq, Hkv, tiers, dtype)
+    try:
+        run_planted(p, 2, Hq, Hkv, dtype, [255 + 32 * 25, 255 + 32 * 83], synth.SEED_BASE + 330 + Hq, chunks=(256, 256))
+        assert p.gpu.stats()["mfma_launches"] > 0
     finally:
         p.close()
 

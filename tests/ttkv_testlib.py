@@ -21,6 +21,33 @@ def dev(x, dtype, device="cuda:0"):
     return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(device).to(TORCH_DT[dtype]).contiguous()
 
 
+def oracle_fmt(fmt):
+    """'i4c' is Q_4bit exactly as 'i4' (same codes, scales, zeros); only the device's record packing differs."""
+    return "i4" if fmt == "i4c" else fmt
+
+
+def decode_i4c(raw):
+    """Value codes stored channel-major per 32 tokens -> the token-major packing of 'i4' (element 2i in the low
+    nibble of byte i).  raw: uint8 [Hkv][n][64], the V code section's bytes in token order, n a multiple of 32; every
+    32 rows are one 2 KiB group of 512 32-bit words: word d belongs to piece p = d / 4 = 64 hh + 16 kg + c and is its
+    word w = d % 4: channel 16 (4 hh + w) + c, nibble j = token {0, 2, 16, 18, 1, 3, 17, 19}[j] + 4 kg of the group
+    (the layout include/ttkv.h documents)."""
+    Hkv, n, _ = raw.shape
+    assert n % 32 == 0
+    words = np.ascontiguousarray(raw).reshape(Hkv, n // 32, 2048).view(np.uint32)          # [Hkv][groups][512]
+    d = np.arange(512)
+    p, w = d >> 2, d & 3
+    hh, kg, c = p >> 6, (p >> 4) & 3, p & 15
+    ch = 16 * (4 * hh + w) + c
+    tokmap = np.array([0, 2, 16, 18, 1, 3, 17, 19])
+    codes = np.full((Hkv, n // 32, 32, 128), 255, np.uint8)
+    for j in range(8):
+        codes[:, :, tokmap[j] + 4 * kg, ch] = (words >> np.uint32(4 * j)) & np.uint32(15)
+    assert codes.max() <= 15                                                                # every (token, channel) was written
+    codes = codes.reshape(Hkv, n, 128)
+    return codes[..., 0::2] | (codes[..., 1::2] << 4)
+
+
 class Pair:
     """tiers: list of dicts(k_fmt, v_fmt, capacity, block_tokens, ring_blocks, mem, paged_seed, summary)."""
 
@@ -37,7 +64,7 @@ class Pair:
         if oracle_max_tokens is None:
             oracle_max_tokens = [t["ring_blocks"] * t["block_tokens"] * 4 for t in tiers]
         self.ora = OracleCache(B, Hq, Hkv, 128,
-                               [TierSpec(t["k_fmt"], t["v_fmt"], t["capacity"], t["block_tokens"], t.get("mem", "device"),
+                               [TierSpec(t["k_fmt"], oracle_fmt(t["v_fmt"]), t["capacity"], t["block_tokens"], t.get("mem", "device"),
                                          t.get("summary", False)) for t in tiers], oracle_max_tokens)
 
     def close(self):
@@ -92,7 +119,8 @@ class Pair:
                         assert np.array_equal(d[name], q["codes"][:, sl].view(np.uint8)), (t, b, name, "codes")
                         assert np.array_equal(d[name + "_meta"].view(np.uint16), q["scale"][:, sl]), (t, b, name, "scale")
                     else:
-                        assert np.array_equal(d[name], q["codes"][:, sl]), (t, b, name, "codes")
+                        got = decode_i4c(d[name]) if fmt == "i4c" else d[name]
+                        assert np.array_equal(got, q["codes"][:, sl]), (t, b, name, "codes")
                         meta = d[name + "_meta"].view(np.uint16)
                         assert np.array_equal(meta[:, :, 0::2], q["scale"][:, sl]), (t, b, name, "scale")
                         assert np.array_equal(meta[:, :, 1::2], q["zero"][:, sl]), (t, b, name, "zero")
