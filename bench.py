@@ -828,11 +828,13 @@ def run_grid():
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(SEED + 9)
-    per = {("f16", "f16"): 512, ("i8", "i8"): 272, ("i8", "i4"): 208, ("i4", "i4"): 144}
+    per = {("f16", "f16"): 512, ("i8", "i8"): 272, ("i8", "i4"): 208, ("i4", "i4"): 144, ("i8", "i4c"): 208, ("i4", "i4c"): 144}
     rows = []
     for Hq, Hkv in ((32, 32), (32, 16), (24, 8), (32, 8), (48, 8), (64, 8), (64, 4), (64, 2)):
         row = {"q_heads": Hq, "kv_heads": Hkv}
         for (kf, vf), bytes_per in per.items():
+            if vf == "i4c" and Hq == Hkv:
+                continue              # values channel-major per 32 tokens: a layout for two or more heads per KV head
             N = int(560e6 / (4 * Hkv * bytes_per)) // 256 * 256
             tiers = [TierConfig(kf, vf, 10**9, 128, N // 128 + 2)] if kf == "f16" else \
                     [TierConfig("f16", "f16", 256, 128, 3), TierConfig(kf, vf, 10**9, 128, N // 128 + 2)]
