@@ -463,3 +463,12 @@ def test_channel_major_values_are_refused_where_no_kernel_takes_them():
         assert e.value.status == B.ERR_UNSUPPORTED    # a middle tier: values would have to pass through it
     finally:
         p.close()
+
+
+@pytest.mark.parametrize("n_slots,paged", [(0, False), (2, False), (0, True)])
+def test_block_selection_over_channel_major_values(n_slots, paged):
+    """Block identification + top-k + attention of the selected host blocks when the host tier's values are stored
+    channel-major per 32 tokens: ids left on the device (the kernel looks the blocks up and takes the newest one's
+    live length, a multiple of 32, from the launch arguments), ids on the host with staged copies, paged records."""
+    tiers = tiers3("bf16", fmts=(("i8", "i8"), ("i4", "i4c")), summary=True, bts=(64, 128, 128), rings=(6, 8, 40), paged=paged)
+    run_config(2, 8, 2, tiers, "bf16", 255 + 512 + 32 * 85, 40, synth.SEED_BASE + 90, select_k=6, check_state_every=20, n_slots=n_slots)
