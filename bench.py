@@ -67,6 +67,18 @@ def sync_time():
     return time.perf_counter()
 
 
+SETTLE_LAUNCHES = 192
+
+
+def settle(cache, q, launches=SETTLE_LAUNCHES):
+    """Untimed attention launches on the cache as it stands (no append, no eviction: the cache state is untouched)
+    before a measurement: after idle time the launch durations of these kernels drift for about 15 ms of continuous
+    work (first short, then up to 20 % long, then steady: the device's clock management), and a decode loop lives
+    in the steady state.  192 launches of ~0.1 ms cover that."""
+    for i in range(launches):
+        cache.decode(q[i % len(q)])
+
+
 def timed_steps(cache, q, kn, vn, first, count, overlap=True, keep=None, sample_every=0):
     """Run steps [first, first+count) and return seconds, bracketed by full synchronisation.
     sample_every > 0: every sample_every-th step has its attention launch timed by a HIP event pair."""
@@ -744,8 +756,7 @@ def run_gqa_hbm(reps=12, only=None):
                 cache.append(0, K[:, :, :128].contiguous(), V[:, :, :128].contiguous())
             q = device_normal(gen, (4, 4, 32, 128), dt)
             total, _ = algorithmic_bytes(cache)
-            for i in range(3):
-                cache.decode(q[i])
+            settle(cache, q)
             s0 = cache.stats()
             # the launch four times back to back between one event pair (the pair's own cost, a few microseconds of
             # marker dispatch, spread over four launches: what rocprofv3 reports as the kernel's duration), `reps` samples
@@ -766,7 +777,7 @@ def run_gqa_hbm(reps=12, only=None):
             del K, V
             torch.cuda.empty_cache()
     return {"workload": "batch 4, 32 q / 8 kv heads (4 query heads per KV head), one tier in HBM per row, attention launch alone "
-                        "(x4 back to back per event pair, median of 12 samples)",
+                        f"(x4 back to back per event pair, median of 12 samples, after {SETTLE_LAUNCHES} untimed launches)",
             "rows": rows}
 
 
@@ -801,6 +812,7 @@ def run_key_grouping(steps=12):
             if slow_k is None:
                 rows.append({"keys": name, "bytes_per_launch": int(total)})
             else:
+                settle(cache, q)
                 timed_steps(cache, q, kn, vn, 0, 3)
                 B.ttkv_read_attn_timing(cache.h)
                 secs = timed_steps(cache, q, kn, vn, 3, steps, sample_every=4)
@@ -845,8 +857,7 @@ def run_grid():
             del K, V
             q = device_normal(gen, (4, 4, Hq, 128), torch.float16)
             total, _ = algorithmic_bytes(cache)
-            for _ in range(3):
-                cache.decode(q[0])
+            settle(cache, q)
             B.ttkv_time_attn_repeat(cache.h, 4)
             B.ttkv_time_attn(cache.h, 6)
             for i in range(6):
@@ -1016,6 +1027,7 @@ def main():
     cache, kv, steps_in, shape = build_mha32k(W + K + L)
     q, kn, vn = steps_in
     keep = []
+    settle(cache, q)
     timed_steps(cache, q, kn, vn, 0, W, keep=keep)
     total_bytes, by_tier = algorithmic_bytes(cache)        # state at the start of the timed region
     # the attention launch of every 4th timed step is bracketed by a HIP event pair on its stream (each pair
@@ -1078,7 +1090,9 @@ def main():
                    "algorithmic_bytes_per_step": int(step_bytes), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
                    "fp16_equivalent_GBs": round(shape["B"] * shape["Hkv"] * shape["N"] * 512 / (secs / K) / 1e9, 1),
                    "step_us_p50_p95_of_64_event_timed": [round(lat[len(lat) // 2] * 1e6, 1),
-                                                         round(lat[int(0.95 * len(lat))] * 1e6, 1)]},
+                                                         round(lat[int(0.95 * len(lat))] * 1e6, 1)],
+                   "settle": f"{SETTLE_LAUNCHES} untimed attention launches (~20 ms, cache state untouched) precede the {W} warm-up "
+                             "steps: after idle the launch durations drift for ~15 ms (clock management) before they are steady"},
         "roofline": roofline, "cpu_baseline": cpu, "offload_128k": off,
         "tiny": None if args.no_extra else run_tiny(200, 20, cpu_on),
         "serving_ragged": None if args.no_extra else run_serving_ragged(64, 2, cpu_on),
