@@ -136,7 +136,7 @@ ttkv_status ttkv_create(ttkv_handle *out);
 ttkv_status ttkv_destroy(ttkv_handle h);
 void ttkv_get_stats(ttkv_handle h, ttkv_stats *out);
 void ttkv_reset_stats(ttkv_handle h);
-const char *ttkv_status_string(ttkv_status s);
+const char *ttkv_status_string(ttkv_status s); /* utility: a status code as text (no passage of the paper applies) */
 
 /* Bytes of one block record of `tier` (all KV heads). 0 on invalid formats. */
 size_t ttkv_record_bytes(const ttkv_cache *c, int32_t tier);
@@ -148,7 +148,9 @@ size_t ttkv_record_bytes(const ttkv_cache *c, int32_t tier);
 ttkv_status ttkv_locate(const ttkv_cache *c, int32_t b, int64_t pos, int32_t *tier, int64_t *block_id,
                         int32_t *row, int64_t *record);
 
-/* [device] workspace ttkv_decode_attn needs for this cache: split partials for
+/* Utilities around Alg. 1's accumulation "o <- o + Attn(q, K_j, V_j)": the un-normalised partials of its terms live in
+ * a caller-owned workspace until the merge.
+ * [device] workspace ttkv_decode_attn needs for this cache: split partials for
  * up to max_parts parts per (sequence, query head) plus n_slots staging slots, each
  * holding the largest run of adjacent host-tier records one copy moves (up to 32 MiB or 64 records).  ttkv_tier_demote needs batch records of its
  * destination tier when that is a host tier (always covered when n_slots >= batch,
@@ -158,7 +160,8 @@ size_t ttkv_demote_workspace_bytes(const ttkv_cache *c, int32_t src_tier);
 /* Parts per (sequence, query head) ttkv_decode_attn would use right now with this n_slots. */
 int32_t ttkv_count_parts(ttkv_handle h, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
                          int32_t sel_stride, int32_t n_slots);
-/* Split-K granularity: ttkv_decode_attn cuts the device-resident tiers into about
+/* Split-K granularity (how many terms Alg. 1's sum over blocks is cut into; the result is the same up to fp32
+ * rounding, Sec. 4.3): ttkv_decode_attn cuts the device-resident tiers into about
  * target_items workgroups of equal bytes, counted over all sequences and KV heads;
  * 0 restores the default (a whole number of rounds of resident workgroups, chosen by
  * the kernel the cache's formats and head counts select).  More items: better balance

@@ -176,3 +176,27 @@ def test_selection_ids_with_non_finite_scores_and_more_than_64_heads():
                 assert len(got) == min(kk, len(p.ora.live_blocks(1, b)))
     finally:
         p.close()
+
+
+def channel_major_layout(seed):
+    """random_layout(seed) with the last tier's values stored channel-major per 32 tokens, where that format applies
+    (two or more heads per KV head, at least two tiers, int8 or int4 keys in the last tier); the lengths are rounded
+    so that the last tier receives whole groups of 32 tokens."""
+    B_, Hq, Hkv, tiers, dtype, lens, n_slots = random_layout(seed)
+    last = tiers[-1]
+    if Hq == Hkv or len(tiers) < 2 or (last["k_fmt"], last["v_fmt"]) not in (("i8", "i4"), ("i4", "i4")):
+        return None
+    last["v_fmt"] = "i4c"
+    fixed = tiers[0]["capacity"] - 1 + sum(t["capacity"] for t in tiers[1:-1])
+    lens = [n if n <= fixed else fixed + (n - fixed) // 32 * 32 for n in lens]
+    return B_, Hq, Hkv, tiers, dtype, lens, n_slots
+
+
+@pytest.mark.parametrize("seed", [s for s in range(120) if channel_major_layout(s) is not None][:16])
+def test_randomized_layouts_with_channel_major_values(seed):
+    """Seeded random caches (tiers, block sizes, capacities, host / paged / staged variants as in the test above)
+    whose last tier stores its int4 values channel-major per 32 tokens."""
+    B_, Hq, Hkv, tiers, dtype, lens, n_slots = channel_major_layout(seed)
+    run_config(B_, Hq, Hkv, tiers, dtype, None, 12, synth.SEED_BASE + 1200 + seed, lens=lens, n_slots=n_slots,
+               check_state_every=6, host_append_direct=bool(seed & 1), host_demote_direct=bool(seed & 2),
+               one_call_step=bool(seed % 3))
