@@ -281,7 +281,7 @@ def build_offload128k(steps_total):
 # ------------------------------------------------------------------ workload: ragged paged serving batch
 
 def build_serving_ragged(steps_total, batch=16):
-    """BASELINE config 4: batch 16, 32 q / 8 kv heads, contexts uniform in [16K, 64K], 256-token pages with
+    """The ragged serving benchmark configuration: batch 16, 32 q / 8 kv heads, contexts uniform in [16K, 64K], 256-token pages with
     shuffled page tables; 4K fp16 + 12K int8 in HBM, the rest int4 in pinned host memory."""
     import numpy as np
     import torch
@@ -351,7 +351,7 @@ def run_serving_ragged(steps, warmup, cpu_baseline=True):
 # ------------------------------------------------------------------ workload: sparse recall of the host tier
 
 def build_sparse128k(steps_total, batch=4, planted=8):
-    """BASELINE config 5: batch 4, 128K tokens, tiers as the offload workload (1024-token host blocks) plus fp16
+    """The sparse recall benchmark configuration: batch 4, 128K tokens, tiers as the offload workload (1024-token host blocks) plus fp16
     mean-key summaries; only the top-64 of 96 host blocks by q . summary are fetched.  `planted` seeded host blocks per
     sequence have their keys shifted along the mean query of each KV head's group (of the first step's query)."""
     import numpy as np
@@ -432,7 +432,7 @@ def run_sparse128k(steps, warmup, k=64, cpu_baseline=True):
 # ------------------------------------------------------------------ workload: tiny (launch-latency floor)
 
 def run_tiny(steps=200, warmup=20, cpu_baseline=True):
-    """BASELINE config 1: batch 1, 8 q / 2 kv heads, 4096 tokens, recent 512 fp16 + 3584 int8 (group 32), all in HBM.
+    """The smallest benchmark configuration ("tiny"): batch 1, 8 q / 2 kv heads, 4096 tokens, recent 512 fp16 + 3584 int8 (group 32), all in HBM.
     2.5 MB per step: 0.3 us at the HBM peak, so the step is launch latency (two launches: attention, merge)."""
     import numpy as np
     import torch

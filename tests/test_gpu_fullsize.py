@@ -73,7 +73,7 @@ def compare_codes_of(cache, ora, b, heads, fmts):
 
 
 def test_mha32k_full_size_every_head():
-    """BASELINE config 2: batch 4, 32 heads, 32K tokens, 2K fp16 + 30K int4 in HBM, append + attend + evict.
+    """The HBM-bound benchmark configuration ("mha32k"): batch 4, 32 heads, 32K tokens, 2K fp16 + 30K int4 in HBM, append + attend + evict.
     The oracle holds the whole workload: every (sequence, head) row of every step is compared, element-wise and
     relative to the largest output (on N(0,1) data at 32K tokens the outputs are ~5e-3, so the absolute term of
     the element-wise tolerance alone would be most of the signal)."""
@@ -131,7 +131,7 @@ def test_mha32k_with_keys_grouped_over_tokens_full_size_sampled_heads():
 
 
 def test_offload128k_full_size_sampled_heads():
-    """BASELINE config 3: 128K tokens, 4K bf16 + 28K int8 in HBM, 96K int4 in pinned host memory."""
+    """The 128K offload benchmark configuration: 128K tokens, 4K bf16 + 28K int8 in HBM, 96K int4 in pinned host memory."""
     steps = 2
     cache, (K, V), (q, kn, vn), shape = bench.build_offload128k(steps)
     try:
@@ -167,7 +167,7 @@ def test_offload128k_full_size_sampled_heads():
 
 
 def test_serving_ragged_full_size_sampled():
-    """BASELINE config 4: batch 16, ragged contexts in [16K, 64K], paged 256-token blocks on every tier."""
+    """The ragged serving benchmark configuration: batch 16, ragged contexts in [16K, 64K], paged 256-token blocks on every tier."""
     steps = 2
     cache, kv, (q, kn, vn), shape = bench.build_serving_ragged(steps)
     try:
@@ -201,7 +201,7 @@ def test_serving_ragged_full_size_sampled():
 
 
 def test_sparse_recall_full_size_one_sequence():
-    """BASELINE config 5: top-64 of 96 host blocks by q . mean-key; the oracle recomputes one whole sequence
+    """The sparse recall benchmark configuration: top-64 of 96 host blocks by q . mean-key; the oracle recomputes one whole sequence
     (selection needs every head): selected block ids identical, planted blocks selected, outputs within tolerance."""
     steps = 2
     cache, kv, (q, kn, vn), shape = bench.build_sparse128k(steps)
