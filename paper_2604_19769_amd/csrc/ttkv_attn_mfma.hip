@@ -155,6 +155,18 @@ __device__ __forceinline__ void lds_half_i4x2(uint32_t a0, uint32_t m0, u32x4 *w
                : "=&v"(w[0]), "=&v"(w[1]), "=&v"(m[0]), "=&v"(m[1]), "=&v"(m[2]), "=&v"(m[3])
                : "v"(a0), "v"(m0) : "memory");
 }
+// a batch of 64 tokens = four tiles: w[tt] = the lane's one piece of tile tt (a0, 1 KiB apart); meta: tile tt's two
+// words from m0 + 64 tt and m0 + 256 + 64 tt
+__device__ __forceinline__ void lds_half_i4x4(uint32_t a0, uint32_t m0, u32x4 *w, uint32_t *m) {
+  asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %12 offset:1024\n\tds_read_b128 %2, %12 offset:2048\n\t"
+               "ds_read_b128 %3, %12 offset:3072\n\t"
+               "ds_read_b32 %4, %13\n\tds_read_b32 %5, %13 offset:256\n\tds_read_b32 %6, %13 offset:64\n\t"
+               "ds_read_b32 %7, %13 offset:320\n\tds_read_b32 %8, %13 offset:128\n\tds_read_b32 %9, %13 offset:384\n\t"
+               "ds_read_b32 %10, %13 offset:192\n\tds_read_b32 %11, %13 offset:448\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(m[0]), "=&v"(m[1]), "=&v"(m[2]), "=&v"(m[3]),
+                 "=&v"(m[4]), "=&v"(m[5]), "=&v"(m[6]), "=&v"(m[7])
+               : "v"(a0), "v"(m0) : "memory");
+}
 // fp16 / bf16: w[4 tt + x] = piece x of the lane of tile tt, from ax (tile 1: 4 KiB further); no meta words.
 __device__ __forceinline__ void lds_half_fp(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, u32x4 *w) {
   asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
@@ -189,11 +201,13 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; fp16 / bf16 rows take the one-region variant further
   // down.  int4 keys with token-major int4 values, whose unpack / dequantize / transpose arithmetic fills the issue
   // slots, gained nothing (4.9-5.0 either way) and stay on the register loads; with channel-major values that
-  // arithmetic is gone and the waits for the loads are what is left, so they are prefetched as well.
+  // arithmetic is gone and the waits for the loads are what is left, so they are prefetched as well, in batches of
+  // 64 tokens (two 32-token groups of values; 5.85 -> 5.97 TB/s against batches of 32).
   constexpr bool PF = (KF == TTKV_I8_SYM_G32 && (VF == TTKV_I8_SYM_G32 || VF == TTKV_I4_ASYM_G64 || VF == TTKV_I4_ASYM_G64_T32)) ||
                       (KF == TTKV_I4_ASYM_G64 && VF == TTKV_I4_ASYM_G64_T32);
   // tiles in flight per wave (int4 on register loads: 4; with 2 that kernel is 10 % slower)
-  constexpr int NT = (NLK == 4 || PF) ? 2 : 4 / NLK;
+  constexpr bool PF64 = KF == TTKV_I4_ASYM_G64 && VF == TTKV_I4_ASYM_G64_T32;   // prefetched in batches of 64 tokens
+  constexpr int NT = PF64 ? 4 : (NLK == 4 || PF) ? 2 : 4 / NLK;
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
   constexpr bool KQ = NGK > 1, VQ = NGV > 1;
@@ -389,7 +403,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   constexpr int PK = FK::ROWB / 16, PV = FV::ROWB / 16;              // pieces per row
   constexpr int NDK = TT * FK::ROWB / 1024, NDV = TT * FV::ROWB / 1024;   // copy instructions of 1 KiB per half
   constexpr int N_K = NDK + 2, N_V = NDV + 2;                          // with the two meta planes
-  static_assert(!PF || (NT == 2 && ((PK == 8 && NDK == 4) || (PK == 4 && NDK == 2)) && (NDV == 4 || NDV == 2)),
+  static_assert(!PF || PF64 || (NT == 2 && ((PK == 8 && NDK == 4) || (PK == 4 && NDK == 2)) && (NDV == 4 || NDV == 2)),
                 "the batch the LDS readers cover");
   auto swz = [](int pieces, int r) { return pieces == 4 ? (r >> 2) & 3 : (r >> 1) & 7; };
   // per-lane byte offset of copy instruction j inside a full batch, minus j KiB (even and odd j differ for 8 pieces)
@@ -433,8 +447,11 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   };
   auto issue_v = [&]() {
     const uint8_t *vb = nx_head + tv.v_off + nx_row0 * FV::ROWB, *vmb = nx_head + tv.v_meta_off + nx_row0 * 8;
-    if constexpr (VT) {   // the batch is one whole 2 KiB group (its length is a multiple of 32): copied as it lies
+    if constexpr (VT) {   // whole 2 KiB groups (lengths are multiples of 32), copied as they lie
       dma16<0>(vb + lane * 16, wbuf + 4096); dma16<1024>(vb + lane * 16, wbuf + 4096);
+      if constexpr (PF64) {   // the second group: inside the record even when the run ends before it (its weights are 0)
+        dma16<2048>(vb + lane * 16, wbuf + 4096); dma16<3072>(vb + lane * 16, wbuf + 4096);
+      }
     } else if (nx_nv == TT) {
       dma16<0>(vb + dvo[0], wbuf + 4096); dma16<1024>(vb + dvo[1], wbuf + 4096);
       if constexpr (NDV == 4) {
@@ -455,6 +472,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     u32x4 w[4];
     uint32_t mw[8];
     if constexpr (PK == 8) lds_half_i8(lka0, lka1, lkm, w, mw);
+    else if constexpr (PF64) lds_half_i4x4(lka0, lkm, w, mw);
     else lds_half_i4x2(lka0, lkm, w, mw);
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
@@ -470,6 +488,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
     u32x4 w[4];
     uint32_t mw[8];
     if constexpr (PV == 8) lds_half_i8(lva0, lva1, lvm, w, mw);
+    else if constexpr (PF64) lds_half_i4x4(lva0, lvm, w, mw);
     else lds_half_i4x2(lva0, lvm, w, mw);
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
