@@ -197,16 +197,16 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   constexpr int NLK = FK::ROWB / 64, NLV = FV::ROWB / 64;   // 16-byte loads per lane per 16-token tile
-  // int8 keys (with int8 or int4 values): rows prefetched through LDS.  Measured per format against the register
-  // loads: K8/V8 5.2 -> 6.0-6.2 TB/s, K8/V4 4.9-5.1 -> 5.7-5.8; fp16 / bf16 rows take the one-region variant further
-  // down.  int4 keys with token-major int4 values, whose unpack / dequantize / transpose arithmetic fills the issue
-  // slots, gained nothing (4.9-5.0 either way) and stay on the register loads; with channel-major values that
-  // arithmetic is gone and the waits for the loads are what is left, so they are prefetched as well, in batches of
-  // 64 tokens (two 32-token groups of values; 5.85 -> 5.97 TB/s against batches of 32).
+  // Quantized keys: rows prefetched through LDS (asynchronous global -> LDS copies with the streaming hint, the batch
+  // after next in flight while one is computed).  Measured per format against register loads: K8/V8 5.2 -> 6.0-6.2
+  // TB/s, K8/V4 4.9-5.1 -> 5.7-5.8 (batches of 32 tokens); int4 keys in batches of 64 tokens: with channel-major
+  // values 5.2 -> 5.97 (of which 32 -> 64 tokens per batch 5.85 -> 5.97), with token-major values 5.09 -> 5.27 (in
+  // batches of 32 they gained nothing: their unpack / dequantize / transpose arithmetic fills the issue slots).
+  // fp16 / bf16 rows take the one-region variant further down.
   constexpr bool PF = (KF == TTKV_I8_SYM_G32 && (VF == TTKV_I8_SYM_G32 || VF == TTKV_I4_ASYM_G64 || VF == TTKV_I4_ASYM_G64_T32)) ||
-                      (KF == TTKV_I4_ASYM_G64 && VF == TTKV_I4_ASYM_G64_T32);
+                      (KF == TTKV_I4_ASYM_G64 && (VF == TTKV_I4_ASYM_G64_T32 || VF == TTKV_I4_ASYM_G64));
   // tiles in flight per wave (int4 on register loads: 4; with 2 that kernel is 10 % slower)
-  constexpr bool PF64 = KF == TTKV_I4_ASYM_G64 && VF == TTKV_I4_ASYM_G64_T32;   // prefetched in batches of 64 tokens
+  constexpr bool PF64 = KF == TTKV_I4_ASYM_G64 && (VF == TTKV_I4_ASYM_G64_T32 || VF == TTKV_I4_ASYM_G64);   // prefetched in batches of 64 tokens
   constexpr int NT = PF64 ? 4 : (NLK == 4 || PF) ? 2 : 4 / NLK;
   constexpr int TT = 16 * NT;
   constexpr int NGK = n_groups<KF>(), NGV = n_groups<VF>();
