@@ -81,6 +81,8 @@ class TieredCache:
         self.ws = None
         self.ws_parts = 0
         self.demote_ws = None
+        self._demote_need = None          # per tier: bytes of staging ttkv_tier_demote wants (constant for a cache)
+        self._parts_age = None            # dense steps since the parts per row were last counted (None: never)
         self.sel_blocks = self.sel_count = self.sel_scratch = None
         self.out = torch.empty(batch, n_q_heads, 128, dtype=torch.float32, device=self.device)
         self.lse = torch.empty(batch, n_q_heads, dtype=torch.float32, device=self.device)
@@ -113,6 +115,7 @@ class TieredCache:
         fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16, torch.float32: B.F32}[k.dtype]
         assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape and k.dtype == v.dtype
         n = k.shape[-2]
+        self._parts_age = None            # lengths jump: count the parts again at the next step
         if self.cfg[tier].mem == "host" and self.host_append_direct:
             # no staging: the conversion kernels store into the pinned records
             B.ttkv_quantize_append_host(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), None, 0, self._compute())
@@ -126,8 +129,10 @@ class TieredCache:
 
     def demote(self, overlap=True):
         """Cascade eviction through all tiers (Alg. 1, last lines)."""
+        if self._demote_need is None:
+            self._demote_need = [B.ttkv_demote_workspace_bytes(self.c, t) for t in range(len(self.cfg) - 1)]
         for t in range(len(self.cfg) - 1):
-            need = 0 if self.host_demote_direct else B.ttkv_demote_workspace_bytes(self.c, t)
+            need = 0 if self.host_demote_direct else self._demote_need[t]
             if need and (self.demote_ws is None or self.demote_ws.numel() < need):
                 self.demote_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
             B.ttkv_tier_demote(self.h, self.c, t, 0, self.demote_ws if need else None, need, self._compute(),
@@ -152,21 +157,36 @@ class TieredCache:
         if selected is not None:
             sb, sc = selected
             stride = sb.shape[1]
-        if new is not None:
-            self.len[0] += 1            # size the workspace for the lengths the attention may see
-        parts = B.ttkv_count_parts(self.h, self.c, sb, sc, stride, self.n_slots)
-        if new is not None:
-            self.len[0] -= 1
-        if parts < 0:
-            raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
-        ws = self._workspace(max(parts, 1))
+        # Parts per row: counted by the library.  A dense decode step adds one token per sequence, i.e. at most one
+        # part per tier every 256 steps, and the workspace is sized with 16 parts to spare: inside step() the count is
+        # therefore refreshed only every 64 steps (the library still checks the workspace on every call).
+        if selected is None and new is not None and self.ws is not None and self._parts_age is not None and self._parts_age < 64 \
+                and self.ws_slots == self.n_slots:
+            self._parts_age += 1
+            ws = self.ws
+        else:
+            if new is not None:
+                self.len[0] += 1            # size the workspace for the lengths the attention may see
+            parts = B.ttkv_count_parts(self.h, self.c, sb, sc, stride, self.n_slots)
+            if new is not None:
+                self.len[0] -= 1
+            if parts < 0:
+                raise B.TTKVError(B.ERR_INVALID_ARG, "ttkv_count_parts")
+            ws = self._workspace(max(parts, 1))
+            self._parts_age = 0 if (selected is None and new is not None) else None
         if new is not None:
             k_new, v_new = new
             fmt = {torch.float16: B.F16, torch.bfloat16: B.BF16}[k_new.dtype]
             assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == v_new.dtype
             assert tuple(k_new.shape) == tuple(v_new.shape) == (self.B, self.Hkv, 1, 128)
-            B.ttkv_decode_step(self.h, self.c, q, q_fmt, k_new, v_new, fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(),
-                               self.n_slots, self._compute(), self._copy(overlap))
+            try:
+                B.ttkv_decode_step(self.h, self.c, q, q_fmt, k_new, v_new, fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(),
+                                   self.n_slots, self._compute(), self._copy(overlap))
+            except B.TTKVError as e:
+                if e.status != B.ERR_WORKSPACE or self._parts_age in (None, 0):
+                    raise
+                self._parts_age = None    # the split changed under a cached count (nothing was enqueued): count and go again
+                return self.decode(q, selected, overlap, new)
         else:
             B.ttkv_decode_attn(self.h, self.c, q, q_fmt, self.out, self.lse, sb, sc, stride, ws, ws.numel(), self.n_slots,
                                self._compute(), self._copy(overlap))
