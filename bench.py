@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mha32k", choices=["mha32k", "offload128k", "tiny", "serving_ragged", "sparse128k", "gqa_hbm", "ablation", "grid"])
+    ap.add_argument("--grid-rows", default="", help="grid only: comma-separated q/kv head counts, e.g. 64/4,64/2 (default: the whole table)")
     ap.add_argument("--gqa-formats", default="", help="gqa_hbm only: comma-separated K/V formats to run, e.g. i8/i4,i4/i4 (default: all)")
     ap.add_argument("--mode", default="all", choices=["all", "staged"],
                     help="offload128k only: 'staged' runs nothing but attention calls in the staged-copy mode (for a trace)")
@@ -832,7 +833,7 @@ def run_key_grouping(steps=12):
 
 # ------------------------------------------------------------------ workload: formats x head groupings in HBM
 
-def run_grid():
+def run_grid(only=None):
     """One HBM-resident tier of ~560 MB (plus a 256-token fp16 window for the quantized ones), batch 4, every stored
     format against head groupings from multi-head to multi-query: attention launch issued four times back to back
     between one event pair, median of six samples.  Effective TB/s of stored bytes; which kernel served it."""
@@ -844,7 +845,9 @@ def run_grid():
     gen.manual_seed(SEED + 9)
     per = {("f16", "f16"): 512, ("i8", "i8"): 272, ("i8", "i4"): 208, ("i4", "i4"): 144, ("i8", "i4c"): 208, ("i4", "i4c"): 144}
     rows = []
-    for Hq, Hkv in ((32, 32), (32, 16), (24, 8), (32, 8), (48, 8), (64, 8), (64, 4), (64, 2)):
+    for Hq, Hkv in ((32, 32), (32, 16), (24, 8), (32, 8), (48, 8), (28, 4), (64, 8), (48, 4), (64, 4), (64, 2)):
+        if only and f"{Hq}/{Hkv}" not in only:
+            continue
         row = {"q_heads": Hq, "kv_heads": Hkv}
         for (kf, vf), bytes_per in per.items():
             if vf == "i4c" and Hq == Hkv:
@@ -976,7 +979,7 @@ def main():
         del src, dst
 
     if args.workload == "grid":
-        r = run_grid()
+        r = run_grid([x for x in args.grid_rows.split(",") if x] or None)
         best = max(v["TBs"] for row in r["rows"] for k, v in row.items() if isinstance(v, dict))
         line = {"metric": "decode-attn effective KV TB/s by stored format and head grouping (HBM-resident)", "value": best,
                 "unit": "TB/s", "n_gpus": 1, "steps": 24, "warmup": 3, "ms_per_step": None, "higher_is_better": True,

@@ -43,10 +43,12 @@
 // Column budget: (group, head) columns come 16 to a pass of the score product, heads padded to 4, 8 or 16 where
 // the keys have channel groups (idle columns cost nothing).  One pass serves int4 keys (2 groups) with up to 8
 // heads per KV head and int8 keys (4 groups) with up to 4; two passes (a second q operand and selector, summed
-// before the softmax) int8 keys with up to 8 heads and int4 keys with up to 16.  fp16 / bf16 and keys grouped
-// over tokens take any count up to 16.  More heads per KV head are cut into blocks of 16 (8 if a tier has int8
-// keys), one workgroup and one pass over the bytes per block.  Launches where the vector kernel is as fast or
-// faster (two heads per KV head of one format) stay on the vector kernel.
+// before the softmax) int8 keys with up to 8 heads and int4 keys with up to 16; four passes (one per group, the
+// instantiation for 16 heads runs two waves per SIMD and has the registers for four q operands) int8 keys with up
+// to 16.  fp16 / bf16 and keys grouped over tokens take any count up to 16.  More heads per KV head are cut into
+// blocks of 16, one workgroup and one pass over the bytes per block (measured, 64 q / 4 kv heads, int8 keys: one
+// block of 16 heads 5.8 TB/s of stored bytes against 4.0 as two blocks of 8).  Launches where the vector kernel is
+// as fast or faster (two heads per KV head of one format) stay on the vector kernel.
 #include "ttkv_attn_dev.h"
 
 #include <algorithm>
@@ -224,7 +226,7 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   const float cs = a.scale * kLog2e;       // scores are kept in the log2 domain
 
   // (group, head) columns: groups x heads of them, 16 per pass of the score product (NP = 2 when they exceed
-  // one tile: int8 keys with 8 heads, int4 keys with 16).  Column n of pass pp is group (16 pp + n) / G of head n % G.
+  // one tile: int8 keys with 8 heads, int4 keys with 16; NP = 4: int8 keys with 16 heads).  Column n of pass pp is group (16 pp + n) / G of head n % G.
   constexpr int NP = KQ ? (NGK * GT + 15) / 16 : 1;
   const int g = n % G;                                   // head of this column
   int gam[NP];                                           // K group of this column, per pass
@@ -841,9 +843,9 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
 }
 
 // GQ: query heads per KV head the quantized-key cases are compiled for (4, 8 or 16; fp16 / bf16 tiers take any
-// count).  WIDE: the launch has a tier whose (group, head) columns need two passes of the score product (int8
-// keys with 8 heads, int4 keys with 16); those cases hold a second q operand, so they get instantiations of
-// their own and the one-pass cases keep their registers.
+// count).  WIDE: the launch has a tier whose (group, head) columns need more than one pass of the score product
+// (int8 keys with 8 or 16 heads, int4 keys with 16); those cases hold further q operands, so they get
+// instantiations of their own and the one-pass cases keep their registers.
 // T128: the launch has a tier whose keys are grouped over 128 tokens per channel (its own instantiations as well).
 template <int GQ, bool WIDE, bool T128>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 2 : 3, GQ == 16 ? 2 : 3))) void attn_mfma_kernel(const FusedArgs a) {
@@ -885,16 +887,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
     case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
     case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;
     case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32:
-      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, GQ);
+      if constexpr (GQ == 4 || ((GQ == 8 || GQ == 16) && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, GQ);
       break;
     case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64:
-      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, GQ);
+      if constexpr (GQ == 4 || ((GQ == 8 || GQ == 16) && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, GQ);
       break;
     case TTKV_I4_ASYM_T128 * 8 + TTKV_I4_ASYM_G64:
       if constexpr (T128) TTKV_MFMA_CASE(TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, 0);
       break;
     case TTKV_I8_SYM_G32 * 8 + TTKV_I4_ASYM_G64_T32:
-      if constexpr (GQ == 4 || (GQ == 8 && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64_T32, GQ);
+      if constexpr (GQ == 4 || ((GQ == 8 || GQ == 16) && WIDE)) TTKV_MFMA_CASE(TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64_T32, GQ);
       break;
     case TTKV_I4_ASYM_G64 * 8 + TTKV_I4_ASYM_G64_T32:
       if constexpr (GQ <= 8 || WIDE) TTKV_MFMA_CASE(TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64_T32, GQ);
@@ -930,10 +932,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
 
 // Can one 16-column tile hold every (group, head) column of these formats, and does the
 // single pass pay off (from four query heads per KV head on, measured)?
-// Heads one workgroup serves in a single pass over the bytes: 16 columns per pass of the score product, two
-// passes at most, groups x heads columns (heads padded to 4, 8 or 16 where the keys have channel groups; idle
-// columns cost nothing).  More heads per KV head are cut into blocks of this many.
-int mfma_block_heads(int k_fmt) { return k_fmt == TTKV_I8_SYM_G32 ? 8 : 16; }
+// Heads one workgroup serves in a single pass over the bytes: the 16 columns of the second product, whatever the
+// stored format.  More heads per KV head are cut into blocks of this many.
+int mfma_block_heads(int k_fmt) { (void)k_fmt; return 16; }
 
 // Do the kernel's cases take these formats?
 bool attn_mfma_fits(int k_fmt, int v_fmt, int G) {
@@ -977,7 +978,7 @@ MfmaShape mfma_shape(const FusedArgs &a) {
   if (quant) m.padded = padded_heads(m.heads);
   for (int j = 0; j < a.n_entries; ++j) {
     const int kf = a.tv[(a.e[j].tier_seq >> 16) & 0xff].k_fmt;
-    m.wide |= (kf == TTKV_I8_SYM_G32 && m.padded == 8) || (kf == TTKV_I4_ASYM_G64 && m.padded == 16);
+    m.wide |= (kf == TTKV_I8_SYM_G32 && m.padded >= 8) || (kf == TTKV_I4_ASYM_G64 && m.padded == 16);
   }
   return m;
 }

@@ -144,13 +144,15 @@ def test_gqa_ratios_and_ragged_lengths(Hq, Hkv):
                                                 (16, 4, "bf16", ("i8", "i8")), (16, 2, "f16", ("i8", "i8")), (8, 1, "bf16", ("i8", "i4")),
                                                 (16, 1, "f16", ("i4", "i4")), (6, 2, "f16", ("i8", "i8")), (12, 2, "bf16", ("i4", "i4")),
                                                 (10, 2, "f16", ("i8", "i4")), (4, 2, "f16", ("i8", "i4")), (24, 2, "f16", ("i4", "i4")),
-                                                (7, 1, "bf16", ("i8", "i8"))])
+                                                (7, 1, "bf16", ("i8", "i8")), (12, 1, "f16", ("i8", "i8")), (16, 1, "bf16", ("i8", "i4")),
+                                                (40, 2, "bf16", ("i8", "i4")), (64, 2, "f16", ("i8", "i8")), (48, 2, "f16", ("i4", "i4"))])
 def test_grouped_query_group_sizes_on_the_matrix_core_kernel(Hq, Hkv, dtype, slow):
     """Every (format, heads per KV head) case of the grouped-query kernel: int4 with 8 heads, fp16 with 16 and with
     counts that are not powers of two (5, 6), K 8-bit / V 4-bit and int8 with 4; the two-pass cases int8 and
-    K 8-bit / V 4-bit with 8 heads and int4 with 16; head counts that are padded to the next of 4, 8, 16 (3, 5, 6,
-    7, 12) and K 8-bit / V 4-bit with 2; ragged lengths leave partial 16-token tiles in both tiers, the rings wrap
-    during the steps."""
+    K 8-bit / V 4-bit with 8 heads and int4 with 16; the four-pass cases int8 and K 8-bit / V 4-bit with 12 and 16
+    heads; head counts that are padded to the next of 4, 8, 16 (3, 5, 6, 7, 12) and K 8-bit / V 4-bit with 2; more
+    than 16 heads per KV head cut into blocks (20 = 16 + 4, 24 = 16 + 8, 32 = 16 + 16); ragged lengths leave partial
+    16-token tiles in both tiers, the rings wrap during the steps."""
     tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=192, block_tokens=64, ring_blocks=4),
              dict(k_fmt=slow[0], v_fmt=slow[1], capacity=10**9, block_tokens=128, ring_blocks=24)]
     st = run_config(3, Hq, Hkv, tiers, dtype, None, 70, synth.SEED_BASE + 20 + Hq, lens=[5, 1033, 2890], check_state_every=35,
