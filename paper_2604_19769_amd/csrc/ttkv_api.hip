@@ -117,7 +117,8 @@ int default_items(const ttkv_cache *c) {
   }
   if (!attn_mfma_pays(G, special)) return 2560;
   for (int t = 0; t < c->n_tiers; ++t)
-    if (G > 8 && c->tier[t].k_fmt == TTKV_I4_ASYM_G64) return 512;   // that case runs 2 workgroups per CU
+    if (G > 8 && (c->tier[t].k_fmt == TTKV_I4_ASYM_G64 || c->tier[t].k_fmt == TTKV_I8_SYM_G32))
+      return 512;   // the 16-head cases run 2 workgroups per CU (64 q / 4 kv heads, int8 keys: 6.06 against 5.8 TB/s with 768)
   return 768;
 }
 
