@@ -394,13 +394,14 @@ def test_keys_grouped_over_tokens_per_channel(Hq, Hkv, dtype, host, n_slots):
 @pytest.mark.parametrize("Hq,Hkv,dtype,kfmt,host,n_slots", [(8, 2, "f16", "i8", False, 0), (8, 2, "f16", "i4", False, 0), (4, 2, "bf16", "i8", False, 0),
                                                             (6, 2, "f16", "i4", False, 0), (16, 2, "f16", "i8", False, 0), (16, 2, "bf16", "i4", False, 0),
                                                             (32, 2, "f16", "i4", False, 0), (8, 2, "f16", "i8", True, 0), (8, 2, "bf16", "i4", True, 2),
-                                                            (8, 2, "f16", "i4", True, 3)])
+                                                            (8, 2, "f16", "i4", True, 3), (32, 2, "f16", "i8", True, 0),
+                                                            (16, 1, "bf16", "i8", True, 2)])
 def test_values_stored_channel_major_per_32_tokens(Hq, Hkv, dtype, kfmt, host, n_slots):
     """Last tier with Q_4bit values stored channel-major per 32 tokens (the matrix cores take them without a
     transposition): the codes, decoded from that packing, and the scales / zeros equal the oracle's Q_4bit bit for
     bit -- bulk load of whole groups, evictions of 64-token blocks, through an int8 tier in the three-tier cases --
-    and the outputs stay within tolerance with peaked softmax; int8 and int4 keys, 2 to 16 heads per KV head (one-
-    and two-pass cases), HBM and pinned host (read in place, through staging slots, bulk load stored by the kernels)."""
+    and the outputs stay within tolerance with peaked softmax; int8 and int4 keys, 2 to 16 heads per KV head (one-,
+    two- and four-pass cases), HBM and pinned host (read in place, through staging slots, bulk load stored by the kernels)."""
     three = host
     tiers = [dict(k_fmt=dtype, v_fmt=dtype, capacity=256, block_tokens=64, ring_blocks=6)]
     if three:
