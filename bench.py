@@ -158,8 +158,8 @@ def algorithmic_bytes(cache):
 
 
 def cpu_baseline_mha32k(kv, steps, shape, gpu_outs):
-    """The oracle as it stands, timed on this machine's host cores on the same workload (whole batch, the warm-up
-    steps), each step compared with the GPU's output."""
+    """The oracle as it stands, timed on this machine's host cores on the same workload (whole batch; the warm-up
+    steps, each compared with the GPU's output, then further steps up to ~10 s of oracle time)."""
     import numpy as np
     import oracle as O
     from oracle import OracleCache, TierSpec
@@ -170,8 +170,12 @@ def cpu_baseline_mha32k(kv, steps, shape, gpu_outs):
     ora = OracleCache(B, H, H, 128, [TierSpec("f16", "f16", R, bt), TierSpec("i4", "i4", 10**9, bt)], [R + bt, N + bt])
     for b in range(B):
         ora.load(b, K[b].float().cpu().numpy(), V[b].float().cpu().numpy())
-    n_steps, secs, bytes_, err = len(gpu_outs), 0.0, 0, 0.0
-    for s in range(n_steps):
+    # the compared steps first, then further steps of the same inputs for the timing alone: ~10 s of oracle work
+    n_cmp, n_steps, secs, bytes_, err = len(gpu_outs), 0, 0.0, 0, 0.0
+    for s in range(q.shape[0]):
+        if s >= n_cmp and secs >= 10.0:
+            break
+        n_steps += 1
         qs = q[s].float().cpu().numpy()
         ks, vs = kn[s, :, :, 0].float().cpu().numpy(), vn[s, :, :, 0].float().cpu().numpy()
         # same accounting as the GPU line: stored bytes of every token the step attends (incl. the new one)
@@ -179,10 +183,12 @@ def cpu_baseline_mha32k(kv, steps, shape, gpu_outs):
         t0 = time.perf_counter()
         out, _ = ora.step(qs, ks, vs)
         secs += time.perf_counter() - t0
-        g = gpu_outs[s].cpu().numpy()
-        err = max(err, float(np.max(np.abs(g - out) / (2e-3 + 1e-2 * np.abs(out)))))
+        if s < n_cmp:
+            g = gpu_outs[s].cpu().numpy()
+            err = max(err, float(np.max(np.abs(g - out) / (2e-3 + 1e-2 * np.abs(out)))))
     return {"value": round(bytes_ / secs / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"whole workload (batch {B}, {H} heads, {N} tokens), {n_steps} decode steps incl. append+evict",
+            "sample": f"whole workload (batch {B}, {H} heads, {N} tokens), {n_steps} decode steps incl. append+evict "
+                      f"({secs:.1f} s of oracle time), the first {n_cmp} compared with the GPU's outputs",
             "ms_per_step": round(secs / n_steps * 1e3, 1), "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
 
 
@@ -205,35 +211,44 @@ def pcie_roofline(host_bytes, seconds, what):
 
 def oracle_sample(tier_specs, max_tokens, Hq, Hkv, heads, seqs, steps_in, step, gpu_out, what, select_k=None):
     """The oracle as it stands on a sample of the workload: for each (sequence index b, K, V) in seqs, KV heads
-    `heads` (all their query heads, every token), loaded in bulk, then ONE decode step timed on this machine's host
-    cores and compared with the GPU's output of that step.  Returns the cpu_baseline object (GB/s of stored bytes)."""
+    `heads` (all their query heads, every token), loaded in bulk, then one decode step timed on this machine's host
+    cores and compared with the GPU's output of that step, and up to 32 further steps (until ~2 s) for the timing.  Returns the cpu_baseline object (GB/s of stored bytes)."""
     import numpy as np
     from oracle import OracleCache
     q, kn, vn = steps_in
     G = Hq // Hkv
     rows = np.concatenate([np.arange(h * G, (h + 1) * G) for h in heads])
     cores = min(len(os.sched_getaffinity(0)), len(rows))      # the oracle's threads run over query heads
-    secs, bytes_, err = 0.0, 0, 0.0
+    secs, bytes_, err, n_steps = 0.0, 0, 0.0, 0
     per = {"f16": 256, "bf16": 256, "i8": 136, "i4": 72, "i4t": 68, "i4c": 72}
     for b, K, V in seqs:
         ora = OracleCache(1, G * len(heads), len(heads), 128, tier_specs, max_tokens)
         ora.load(0, K[heads].float().cpu().numpy(), V[heads].float().cpu().numpy())
-        args = (q[step, b][rows][None].float().cpu().numpy(), kn[step, b, heads, 0][None].float().cpu().numpy(),
-                vn[step, b, heads, 0][None].float().cpu().numpy())
-        t0 = time.perf_counter()
-        r = ora.step(*args) if select_k is None else ora.step(*args, select_k=select_k)
-        secs += time.perf_counter() - t0
-        if select_k is None:
-            bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs))
-        else:   # only the selected blocks of the last tier are attended
-            last = len(tier_specs) - 1
-            bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs[:-1]))
-            bytes_ += len(r[2][0]) * tier_specs[last].block_tokens * len(heads) * (per[tier_specs[last].k_fmt] + per[tier_specs[last].v_fmt])
-        g = gpu_out[b][rows].float().cpu().numpy()
-        err = max(err, float(np.max(np.abs(g - r[0][0]) / (2e-3 + 1e-2 * np.abs(r[0][0])))))
+        # the compared step, then up to 32 further steps of the same inputs for the timing alone (~2 s of oracle work)
+        mine = 0.0
+        for s in range(step, min(step + 33, q.shape[0])):
+            if s > step and mine >= 2.0:
+                break
+            args = (q[s, b][rows][None].float().cpu().numpy(), kn[s, b, heads, 0][None].float().cpu().numpy(),
+                    vn[s, b, heads, 0][None].float().cpu().numpy())
+            t0 = time.perf_counter()
+            r = ora.step(*args) if select_k is None else ora.step(*args, select_k=select_k)
+            mine += time.perf_counter() - t0
+            n_steps += 1
+            if select_k is None:
+                bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs))
+            else:   # only the selected blocks of the last tier are attended
+                last = len(tier_specs) - 1
+                bytes_ += sum(ora.seq[t][0].count * len(heads) * (per[sp.k_fmt] + per[sp.v_fmt]) for t, sp in enumerate(tier_specs[:-1]))
+                bytes_ += len(r[2][0]) * tier_specs[last].block_tokens * len(heads) * (per[tier_specs[last].k_fmt] + per[tier_specs[last].v_fmt])
+            if s == step:
+                g = gpu_out[b][rows].float().cpu().numpy()
+                err = max(err, float(np.max(np.abs(g - r[0][0]) / (2e-3 + 1e-2 * np.abs(r[0][0])))))
+        secs += mine
         del ora
-    return {"value": round(bytes_ / secs / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle", "sample": what,
-            "seconds": round(secs, 2), "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
+    return {"value": round(bytes_ / secs / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": what + f"; compared with the GPU's output, then {n_steps - len(seqs)} further steps for the timing alone",
+            "seconds": round(secs, 2), "steps_timed": n_steps, "gpu_vs_oracle_worst_err_over_tol": round(err, 4)}
 
 # ------------------------------------------------------------------ workload: 128K offload
 
