@@ -167,6 +167,13 @@ int32_t ttkv_count_parts(ttkv_handle h, const ttkv_cache *c, const int32_t *sel_
  * the kernel the cache's formats and head counts select).  More items: better balance
  * over 256 CUs, more partials. */
 ttkv_status ttkv_set_split(ttkv_handle h, int32_t target_items);
+/* Paged tiers (Eq. (1): the index maps a block to where it is stored): by default every call that takes the handle
+ * checks every entry of every host block table against pool_blocks before it enqueues anything -- batch x
+ * ring_blocks comparisons per table per call, which a pool of millions of pages makes longer than the step itself.
+ * on = 0 switches the per-call check off for this handle: the entries are then trusted as the caller's allocator
+ * wrote them (a wrong entry is an out-of-bounds access on the device); on = 1 restores it.  Everything else is
+ * still validated on every call. */
+ttkv_status ttkv_set_table_check(ttkv_handle h, int32_t on);
 
 /* Append n_tokens at the tail of `tier` (Sec. 4.1 "newly generated tokens are
  * appended to the fast tier"; also the bulk loader of any device tier).

@@ -49,7 +49,7 @@ EXPORTS = [
     "ttkv_locate", "ttkv_workspace_bytes", "ttkv_demote_workspace_bytes", "ttkv_append_host_workspace_bytes",
     "ttkv_count_parts", "ttkv_quantize_append", "ttkv_quantize_append_host", "ttkv_tier_demote", "ttkv_decode_attn",
     "ttkv_decode_step", "ttkv_decode_step_topk", "ttkv_decode_attn_noalloc",
-    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_set_split",
+    "ttkv_merge_partials", "ttkv_select_blocks", "ttkv_set_split", "ttkv_set_table_check",
 ]
 # include/ttkv_bench.h: measurement and inspection aids, not part of the boundary
 BENCH_EXPORTS = ["ttkv_time_attn", "ttkv_time_attn_repeat", "ttkv_read_attn_timing", "ttkv_stream_read", "ttkv_staged_schedule"]
@@ -98,6 +98,7 @@ def lib():
         L.ttkv_append_host_workspace_bytes.restype = sz
         L.ttkv_count_parts.argtypes = [p, cp, p, p, i32, i32]
         L.ttkv_set_split.argtypes = [p, i32]
+        L.ttkv_set_table_check.argtypes = [p, i32]
         L.ttkv_count_parts.restype = i32
         L.ttkv_quantize_append.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p]
         L.ttkv_quantize_append_host.argtypes = [p, cp, i32, i32, p, p, i32, i64, i32, p, sz, p]
@@ -193,6 +194,10 @@ def ttkv_stream_read(h, src, nbytes, sink, stream):
 
 def ttkv_set_split(h, target_items):
     _check(lib().ttkv_set_split(h, target_items), "ttkv_set_split")
+
+
+def ttkv_set_table_check(h, on):
+    _check(lib().ttkv_set_table_check(h, int(on)), "ttkv_set_table_check")
 
 
 def ttkv_quantize_append(h, cache, tier, seq, k_src, v_src, src_fmt, n_tokens, through_tiers, stream):

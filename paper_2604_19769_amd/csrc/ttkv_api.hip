@@ -12,7 +12,7 @@ using namespace ttkv;
 
 namespace ttkv {
 
-ttkv_status validate_cache(const ttkv_cache *c) {
+ttkv_status validate_cache(const ttkv_cache *c, bool check_tables) {
   if (!c) return TTKV_ERR_INVALID_ARG;
   if (c->head_dim != TTKV_HEAD_DIM) return TTKV_ERR_UNSUPPORTED;
   if (c->batch < 1 || c->batch > TTKV_MAX_BATCH) return TTKV_ERR_INVALID_ARG;
@@ -44,7 +44,7 @@ ttkv_status validate_cache(const ttkv_cache *c) {
     if (!T.block_table && T.pool_blocks < (int64_t)c->batch * T.ring_blocks) return TTKV_ERR_INVALID_ARG;
     if (T.block_table && (T.mem == TTKV_MEM_DEVICE || T.k_sum) && !T.block_table_dev) return TTKV_ERR_INVALID_ARG;
     if (T.k_sum && !T.k_summary) return TTKV_ERR_INVALID_ARG;
-    if (T.block_table)
+    if (T.block_table && check_tables)   // O(batch x ring_blocks) per call: the caller may take the responsibility (ttkv_set_table_check)
       for (int64_t i = 0; i < (int64_t)c->batch * T.ring_blocks; ++i)
         if (T.block_table[i] < 0 || T.block_table[i] >= T.pool_blocks) return TTKV_ERR_INVALID_ARG;
     for (int b = 0; b < c->batch; ++b) {
@@ -330,7 +330,7 @@ ttkv_status append_impl(Handle *h, ttkv_cache *c, int32_t tier, int32_t seq, con
                         int32_t src_fmt, int64_t n_tokens, int32_t through, void *workspace, size_t ws_bytes,
                         hipStream_t stream, bool host_variant) {
   if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h->check_tables);
   if (st != TTKV_OK) return st;
   if (tier < 0 || tier >= c->n_tiers || seq < -1 || seq >= c->batch || !k_src || !v_src || n_tokens < 0)
     return TTKV_ERR_INVALID_ARG;
@@ -440,6 +440,7 @@ ttkv_status ttkv_create(ttkv_handle *out) {
   }
   h->have_events = false;
   h->target_items = 0;
+  h->check_tables = true;
   h->time_on = false;
   h->time_max = h->time_n = 0;
   h->time_ev = nullptr;
@@ -548,7 +549,7 @@ size_t ttkv_append_host_workspace_bytes(const ttkv_cache *c, int32_t tier, int32
 int32_t ttkv_count_parts(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *sel_count,
                          int32_t sel_stride, int32_t n_slots) {
   Handle *h = reinterpret_cast<Handle *>(hh);
-  if (!h || validate_cache(c) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
+  if (!h || validate_cache(c, h->check_tables) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
   Plan &P = h->plan;
   build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items ? h->target_items : default_items(c), &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
@@ -572,7 +573,7 @@ ttkv_status ttkv_tier_demote(ttkv_handle hh, ttkv_cache *c, int32_t src_tier, in
                              size_t ws_bytes, void *compute_, void *copy_) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h->check_tables);
   if (st != TTKV_OK) return st;
   if (src_tier < 0 || src_tier + 1 >= c->n_tiers) return TTKV_ERR_INVALID_ARG;
   ttkv_tier &S = c->tier[src_tier];
@@ -730,7 +731,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
                                size_t ws_bytes, int32_t n_slots, void *compute_, void *copy_, const void *k_new,
                                const void *v_new, int32_t new_fmt, bool check_only = false, const DevSel *ds = nullptr,
                                Chain *trace = nullptr) {
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h ? h->check_tables : true);
   if (st != TTKV_OK) return st;
   if (!q || !out || (q_fmt != TTKV_F16 && q_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
   st = check_sel(c, sel_blocks, sel_count, sel_stride);
@@ -971,7 +972,7 @@ ttkv_status ttkv_decode_step(ttkv_handle hh, ttkv_cache *c, const void *q, int32
                              int32_t n_slots, void *compute, void *copy) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h->check_tables);
   if (st != TTKV_OK) return st;
   if (!k_new || !v_new || (new_fmt != TTKV_F16 && new_fmt != TTKV_BF16)) return TTKV_ERR_INVALID_ARG;
   ttkv_tier &T0 = c->tier[0];
@@ -1060,7 +1061,7 @@ ttkv_status ttkv_select_blocks(ttkv_handle hh, const ttkv_cache *c, const void *
                                size_t scratch_bytes, void *stream_) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h->check_tables);
   if (st != TTKV_OK) return st;
   if (!sel_blocks || !sel_count) return TTKV_ERR_INVALID_ARG;
   hipStream_t stream = (hipStream_t)stream_;
@@ -1081,7 +1082,7 @@ ttkv_status ttkv_decode_step_topk(ttkv_handle hh, ttkv_cache *c, const void *q, 
                                   size_t sel_scratch_bytes, void *workspace, size_t ws_bytes, void *stream_) {
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h) return TTKV_ERR_INVALID_ARG;
-  ttkv_status st = validate_cache(c);
+  ttkv_status st = validate_cache(c, h->check_tables);
   if (st != TTKV_OK) return st;
   if ((k_new == nullptr) != (v_new == nullptr) || (sel_blocks_out == nullptr) != (sel_count_out == nullptr))
     return TTKV_ERR_INVALID_ARG;
@@ -1117,6 +1118,13 @@ ttkv_status ttkv_decode_step_topk(ttkv_handle hh, ttkv_cache *c, const void *q, 
     TTKV_HIP(h, hipMemcpyAsync(sel_blocks_out, sel_out + c->batch, (size_t)c->batch * sel_stride * sizeof(int32_t),
                                hipMemcpyDeviceToHost, stream));
   }
+  return TTKV_OK;
+}
+
+ttkv_status ttkv_set_table_check(ttkv_handle hh, int32_t on) {
+  Handle *h = reinterpret_cast<Handle *>(hh);
+  if (!h || (on != 0 && on != 1)) return TTKV_ERR_INVALID_ARG;
+  h->check_tables = on != 0;
   return TTKV_OK;
 }
 

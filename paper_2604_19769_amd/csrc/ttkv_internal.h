@@ -126,6 +126,7 @@ struct Handle {
   // optional per-call timing of one device tier's partial kernel
   bool time_on;
   int target_items;     // split-K granularity of the fused launch
+  bool check_tables;    // every call checks every host block-table entry against pool_blocks
   int time_max, time_n;
   hipEvent_t *time_ev;  // 2 * time_max events
   int32_t *time_reps;   // launches between the events of each sample
@@ -146,7 +147,7 @@ inline bool is_tier_fmt(int f) {
   return (f >= TTKV_F16 && f <= TTKV_I4_ASYM_G64) || f == TTKV_I4_ASYM_T128 || f == TTKV_I4_ASYM_G64_T32;
 }
 
-ttkv_status validate_cache(const ttkv_cache *c);
+ttkv_status validate_cache(const ttkv_cache *c, bool check_tables = true);
 
 // ---------------------------------------------------------------- launchers (defined in the .hip files)
 struct ConvSource {

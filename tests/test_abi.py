@@ -254,3 +254,31 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_block_table_entries_are_checked_per_call_unless_switched_off():
+    """Paged tiers: an entry beyond pool_blocks is refused by every call that takes the handle; with the per-call check
+    switched off (ttkv_set_table_check, for pools of millions of pages) the same descriptor is taken as the caller
+    wrote it -- shown with ttkv_count_parts, which enqueues nothing -- and the switch can be turned back on."""
+    h = B.ttkv_create()
+    try:
+        c = host_cache()
+        T = c.tier[2]
+        T.mem = B.MEM_HOST_PINNED
+        table = np.arange(2 * 8, dtype=np.int32)
+        T.block_table = table.ctypes.data
+        lens = np.array([3000, 500], np.int64)
+        T.len = lens.ctypes.data
+        c._keep += [table, lens]
+        good = B.ttkv_count_parts(h, c)
+        assert good > 0
+        table[5] = 16                      # == pool_blocks: one past the last record
+        assert B.ttkv_count_parts(h, c) == -1
+        B.ttkv_set_table_check(h, 0)
+        assert B.ttkv_count_parts(h, c) == good
+        B.ttkv_set_table_check(h, 1)
+        assert B.ttkv_count_parts(h, c) == -1
+        assert B.lib().ttkv_set_table_check(h, 2) == B.ERR_INVALID_ARG
+        assert B.lib().ttkv_set_table_check(None, 0) == B.ERR_INVALID_ARG
+    finally:
+        B.ttkv_destroy(h)
