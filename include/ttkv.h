@@ -162,10 +162,12 @@ int32_t ttkv_count_parts(ttkv_handle h, const ttkv_cache *c, const int32_t *sel_
                          int32_t sel_stride, int32_t n_slots);
 /* Split-K granularity (how many terms Alg. 1's sum over blocks is cut into; the result is the same up to fp32
  * rounding, Sec. 4.3): ttkv_decode_attn cuts the device-resident tiers into about
- * target_items workgroups of equal bytes, counted over all sequences and KV heads;
- * 0 restores the default (a whole number of rounds of resident workgroups, chosen by
- * the kernel the cache's formats and head counts select).  More items: better balance
- * over 256 CUs, more partials. */
+ * target_items workgroups of equal bytes, counted over all sequences and KV heads; every
+ * (tier, sequence) run is cut into items of equal size (multiples of 64 tokens, 256 to 8192).
+ * 0 restores the default: chosen per call from the lengths -- the number of rounds of resident
+ * workgroups that suits the kernel the cache's formats and head counts select, raised in steps
+ * until the items of all runs are within 10 % of each other and the last round is filled.
+ * More items: better balance over 256 CUs, more partials. */
 ttkv_status ttkv_set_split(ttkv_handle h, int32_t target_items);
 /* Paged tiers (Eq. (1): the index maps a block to where it is stored): by default every call that takes the handle
  * checks every entry of every host block table against pool_blocks before it enqueues anything -- batch x

@@ -122,23 +122,90 @@ int default_items(const ttkv_cache *c) {
   return 768;
 }
 
-// Tokens per work item of tier t so that every item of the fused launch streams
-// about the same number of bytes: total bytes of the in-place tiers / target_items.
-int pick_chunk(const ttkv_cache *c, int t, int target_items) {
-  auto per_token = [](const ttkv_tier &U) {
-    return (int64_t)fmt_bytes(U.k_fmt).code + fmt_bytes(U.k_fmt).meta + fmt_bytes(U.v_fmt).code + fmt_bytes(U.v_fmt).meta;
-  };
-  int64_t total = 0;   // bytes one pass over a KV head's tokens streams, all sequences and KV heads
-  for (int u = 0; u < c->n_tiers; ++u) {
-    const ttkv_tier &U = c->tier[u];
-    if (U.mem == TTKV_MEM_HOST_PINNED) continue;   // host tiers get fixed items
-    int64_t tokens = 0;
-    for (int b = 0; b < c->batch; ++b) tokens += U.len[b];
-    total += tokens * c->n_kv_heads * per_token(U);
+inline int per_token_bytes(const ttkv_tier &U) {
+  return fmt_bytes(U.k_fmt).code + fmt_bytes(U.k_fmt).meta + fmt_bytes(U.v_fmt).code + fmt_bytes(U.v_fmt).meta;
+}
+
+// Items of a run of `len` tokens when about `want` are asked for: the count that its own equal item size gives.
+int even_items(int len, int want) {
+  int n = std::max(1, want);
+  for (;;) {
+    const int c = even_chunk(len, n), n2 = (len + c - 1) / c;
+    if (n2 == n) return n;
+    n = n2;
   }
-  int64_t want = total / std::max(1, target_items) / per_token(c->tier[t]);
-  want = std::max<int64_t>(256, std::min<int64_t>(8192, want));
-  return (int)((want + 63) / 64 * 64);
+}
+// Items for a run of `len` tokens of `per_token` bytes when an item should stream about item_bytes: between 256
+// and 8192 tokens each.
+int items_for(int64_t len, int per_token, double item_bytes) {
+  const int64_t lo = (len + 8191) / 8192, hi = std::max<int64_t>(1, len / 256);
+  const int64_t want = (int64_t)((double)len * per_token / item_bytes + 0.5);
+  return even_items((int)len, (int)std::max(lo, std::min(hi, want)));
+}
+
+// How the tiers read in place from HBM are cut into work items: bytes per item (one KV head's share of a chunk of
+// tokens), the same for every tier, so that all workgroups of the fused launch stream about the same amount.
+// Every run (tier, sequence) is cut into items of equal size, and a run cannot share an item with another, so with
+// many runs the item sizes and the number of workgroups come out in steps.  What costs time, measured at 16 and 64
+// sequences of a few thousand tokens: items of unequal size (one round of workgroups with 524 and 745 KB items
+// 5.45 TB/s, the same bytes as 350 and 331 KB items 5.98), and a last round of resident workgroups that is mostly
+// empty when there are few rounds (1024 workgroups on 768 slots 3.98-4.6 TB/s, 3072 on 768 4.9-5.7) -- fewer
+// workgroups per CU hide less latency, so the partly filled round does not run proportionally faster.  The
+// target is therefore raised from the kernel's default (default_items) in steps until the items are within 10 % of
+// their mean and the last round is filled (or there are at least three rounds); failing that, the candidate with
+// the smallest estimated loss is taken.  target_items != 0 (ttkv_set_split) is taken as given.
+double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_items) {
+  int64_t S = 0;   // bytes one pass over one KV head's tokens streams
+  for (int t = 0; t < c->n_tiers; ++t) {
+    if (!dense[t]) continue;
+    for (int b = 0; b < c->batch; ++b) S += c->tier[t].len[b] * per_token_bytes(c->tier[t]);
+  }
+  if (S == 0) return 1.0;
+  const int Hkv = c->n_kv_heads, G = c->n_q_heads / Hkv;
+  if (target_items) return std::max(1.0, (double)S * Hkv / target_items);
+  const int legacy = default_items(c);
+  const bool vector_kernel = legacy == 2560;
+  const int resident = vector_kernel ? 1024 : legacy;                             // workgroups on the chip at once
+  const int per_item = Hkv * (vector_kernel ? G / attn_group_width(G) : (G + 15) / 16);   // workgroups per item
+  // the vector kernel's default of 2.5 rounds is as fast as one round when the items are equal (measured)
+  static const float steps_v[] = {2.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 5.0f, 6.0f};
+  static const float steps_m[] = {1.0f, 1.5f, 2.0f, 2.5f, 3.0f, 4.0f, 5.0f, 6.0f};
+  double best_b = 0.0, best_loss = 1e30;
+  for (int k = 0; k < 8; ++k) {
+    const double target = (double)resident * (vector_kernel ? steps_v[k] : steps_m[k]);
+    const double b = std::max(1.0, (double)S * Hkv / target);
+    double largest = 0.0, sum_b = 0.0, sum_b2 = 0.0;
+    bool all_max = true;   // no run can be cut finer
+    for (int t = 0; t < c->n_tiers; ++t) {
+      if (!dense[t]) continue;
+      const int pt = per_token_bytes(c->tier[t]);
+      for (int q = 0; q < c->batch; ++q) {
+        const int64_t len = c->tier[t].len[q];
+        if (len == 0) continue;
+        const int n = items_for(len, pt, b);
+        const double ib = (double)even_chunk((int)len, n) * pt;
+        sum_b += n * ib;
+        sum_b2 += n * ib * ib;
+        largest = std::max(largest, ib);
+        all_max &= n >= std::max<int64_t>(1, len / 256);
+      }
+    }
+    // Short items (a 256-token window beside a long tier) neither unbalance a launch nor fill a round: both
+    // measures weigh an item by its bytes.  rounds: the launch in units of its largest item per resident slot.
+    const double imbalance = largest / (sum_b2 / sum_b);
+    const double rounds = sum_b * per_item / largest / resident;
+    const double frac = rounds - std::floor(rounds);
+    const double fill = frac <= 0.08 && rounds >= 1.0 ? 1.0 : frac;
+    const bool filled = rounds >= 3.0 || fill >= (vector_kernel ? 0.45 : 0.75) || (rounds < 1.0 && (all_max || rounds >= 0.75));
+    if (imbalance <= 1.10 && filled) return b;
+    const double loss = imbalance * (1.0 + (1.0 - fill) / std::max(1.0, std::ceil(rounds)));
+    if (loss < best_loss) {
+      best_loss = loss;
+      best_b = b;
+    }
+    if (all_max) break;   // finer targets change nothing
+  }
+  return best_b;
 }
 
 // staged: host tiers are copied block by block into staging slots (one kernel per
@@ -152,6 +219,9 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
   P->fetch.clear();
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
   const int last = c->n_tiers - 1;
+  for (int t = 0; t < c->n_tiers; ++t)
+    P->even[t] = c->tier[t].mem != TTKV_MEM_HOST_PINNED && !((sel_blocks || ds) && t == last);
+  const double item_bytes = choose_item_bytes(c, P->even, target_items);
   for (int t = 0; t < c->n_tiers; ++t) {
     const ttkv_tier &T = c->tier[t];
     const Layout L = make_layout(T, c->n_kv_heads);
@@ -159,7 +229,7 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const bool host = T.mem == TTKV_MEM_HOST_PINNED;
     // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured);
     // staged slots and selected blocks of a device tier: 256-token items for parallelism
-    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : pick_chunk(c, t, target_items);
+    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : 0;   // 0: items of equal size per run
     if (ds && t == last) P->chunk[t] = host ? 2048 : 256;
     const int chunk = P->chunk[t];
     if (ds && t == last) {
@@ -193,7 +263,7 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
         r.len = (int32_t)T.len[b];
         r.no_table = false;
         r.part_base = P->parts[b];
-        r.n_chunks = (int)((T.len[b] + chunk - 1) / chunk);
+        r.n_chunks = P->even[t] ? items_for(T.len[b], per_token_bytes(T), item_bytes) : (int)((T.len[b] + chunk - 1) / chunk);
         P->parts[b] += r.n_chunks;
         P->runs.push_back(r);
       }
@@ -551,7 +621,7 @@ int32_t ttkv_count_parts(ttkv_handle hh, const ttkv_cache *c, const int32_t *sel
   Handle *h = reinterpret_cast<Handle *>(hh);
   if (!h || validate_cache(c, h->check_tables) != TTKV_OK || check_sel(c, sel_blocks, sel_count, sel_stride) != TTKV_OK) return -1;
   Plan &P = h->plan;
-  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items ? h->target_items : default_items(c), &P);
+  build_plan(c, sel_blocks, sel_count, sel_stride, n_slots > 0, h->target_items, &P);
   return P.status == TTKV_OK ? P.max_parts : -1;
 }
 
@@ -746,7 +816,7 @@ static ttkv_status decode_impl(Handle *h, const ttkv_cache *c, const void *q, in
   const bool staged = n_slots > 0;
 
   Plan &P = h->plan;
-  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items ? h->target_items : default_items(c), &P, ds);
+  build_plan(c, sel_blocks, sel_count, sel_stride, staged, h->target_items, &P, ds);
   if (P.status != TTKV_OK) return P.status;
   if (!workspace) return TTKV_ERR_WORKSPACE;
   // workspace = [n_slots staging slots][m][l][acc]

@@ -876,7 +876,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   const int tier = (en.tier_seq >> 16) & 0xff, seq = en.tier_seq & 0xffff;
   TierView tv = a.tv[tier];
   if (en.tier_seq & (1 << 24)) tv.table = nullptr;   // the run names pool records directly
-  const int chunk_tokens = a.chunk[tier];
+  int chunk_tokens = a.chunk[tier];
+  if (chunk_tokens == 0) chunk_tokens = even_chunk(en.len, (lo + 1 < a.n_entries ? a.e[lo + 1].item_start : a.n_items) - en.item_start);
   const int part = en.part_base + item - en.item_start;   // this item's partial
   int chunk = item - en.item_start;
   resolve_selected(a, tv, en, seq, chunk_tokens, chunk);

@@ -107,6 +107,7 @@ struct Plan {
   std::vector<Fetch> fetch;
   std::vector<const Run *> order;   // launch order of `runs`
   int chunk[TTKV_MAX_TIERS];
+  bool even[TTKV_MAX_TIERS];   // the tier's runs are cut into items of equal size each (chunk[] is then the size aimed at)
   int parts[TTKV_MAX_BATCH];
   int max_parts;
   size_t slot_bytes;
@@ -193,9 +194,12 @@ struct Entry {
   int32_t item_start;   // first work item (chunk) of the run in this launch
   int32_t part_base;    // first partial index of the run
 };
+// A run of `len` tokens cut into n items of equal size, a multiple of 64 tokens (the last item may be shorter).
+// The host plans with it and the kernels derive an item's size from the run's length and item count with it.
+__host__ __device__ inline int even_chunk(int len, int n) { return ((len + n - 1) / n + 63) / 64 * 64; }
 struct FusedArgs {
   TierView tv[TTKV_MAX_TIERS];
-  int32_t chunk[TTKV_MAX_TIERS];
+  int32_t chunk[TTKV_MAX_TIERS];   // tokens per item of the tier's runs; 0: every run in items of equal size (even_chunk)
   Entry e[TTKV_MAX_ENTRIES];
   int32_t n_entries, n_items;
   const void *q;

@@ -282,3 +282,55 @@ def test_block_table_entries_are_checked_per_call_unless_switched_off():
         assert B.lib().ttkv_set_table_check(None, 0) == B.ERR_INVALID_ARG
     finally:
         B.ttkv_destroy(h)
+
+
+def plan_cache(batch, Hq, Hkv, tiers):
+    """tiers: (k_fmt, v_fmt, block_tokens, tokens per sequence); device tiers, pointers never dereferenced."""
+    c = B.ttkv_cache()
+    c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_tiers = batch, Hq, Hkv, 128, len(tiers)
+    c.softmax_scale = 0.088
+    keep = []
+    for t, (kf, vf, bt, n) in enumerate(tiers):
+        T = c.tier[t]
+        T.k_fmt, T.v_fmt, T.mem, T.block_tokens = B.FMT_NAMES[kf], B.FMT_NAMES[vf], B.MEM_DEVICE, bt
+        lens = np.full(batch, n, np.int64) if np.isscalar(n) else np.asarray(n, np.int64)
+        T.capacity_tokens, T.ring_blocks = 10**9, int(lens.max()) // bt + 2
+        T.pool_blocks = T.ring_blocks * batch
+        buf, s = np.zeros(16, np.uint8), np.zeros(batch, np.int64)
+        T.data, T.start, T.len = buf.ctypes.data, s.ctypes.data, lens.ctypes.data
+        keep += [buf, s, lens]
+    c._keep = keep
+    return c
+
+
+def test_split_plan_equal_items_and_whole_rounds():
+    """The split-K plan (how Alg. 1's sum over blocks is cut; host arithmetic only): one long run per tier and
+    sequence keeps the kernel's default number of workgroups; many short runs get finer, equal items instead of one
+    unequal item per run; a forced target is taken as given; no item is shorter than 256 or longer than 8192 tokens."""
+    h = B.ttkv_create()
+    try:
+        # batch 4, 32 q / 8 kv heads, 256-token window + one long int8 tier: one round of 768 workgroups = 24 items per run
+        c = plan_cache(4, 32, 8, [("f16", "f16", 128, 255), ("i8", "i8", 128, 65536)])
+        assert B.ttkv_count_parts(h, c) == 1 + 24
+        # the multi-head workload: 2.5 rounds of 1024 -> 4 + 16 items of 512 and 1920 tokens (262 and 276 KB)
+        c = plan_cache(4, 32, 32, [("f16", "f16", 128, 2048), ("i4", "i4", 128, 30720)])
+        assert B.ttkv_count_parts(h, c) == 4 + 16
+        # 64 sequences of 1024 fp16 + 3072 int8 tokens: one item per run would be 524 and 835 KB on 1024 workgroups for
+        # 768 slots; the plan goes to 2 + 3 items (262 and 278 KB)
+        c = plan_cache(64, 32, 8, [("f16", "f16", 128, 1024), ("i8", "i8", 128, 3072)])
+        assert B.ttkv_count_parts(h, c) == 2 + 3
+        B.ttkv_set_split(h, 768)
+        assert B.ttkv_count_parts(h, c) == 1 + 1
+        B.ttkv_set_split(h, 1 << 20)
+        assert B.ttkv_count_parts(h, c) == 1024 // 256 + 3072 // 256
+        B.ttkv_set_split(h, 1)
+        c = plan_cache(1, 8, 8, [("f16", "f16", 128, 100000)])
+        assert B.ttkv_count_parts(h, c) == -(-100000 // 8192)
+        B.ttkv_set_split(h, 0)
+        # ragged lengths: every sequence's parts cover its tokens in items of 256..8192 tokens
+        lens = [300, 5000, 70000, 129, 8192, 64, 33333, 2048]
+        c = plan_cache(8, 32, 8, [("bf16", "bf16", 128, 200), ("i4", "i4", 128, lens)])
+        parts = B.ttkv_count_parts(h, c)
+        assert 1 + -(-70000 // 8192) <= parts <= 1 + 70000 // 256
+    finally:
+        B.ttkv_destroy(h)

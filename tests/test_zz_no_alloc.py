@@ -79,10 +79,11 @@ def test_noalloc_entry_point_refuses_partials_beyond_its_array():
     tiers = [TierConfig("f16", "f16", 10**9, 256, 10)]
     c = TieredCache(64, 64, 1, tiers)
     try:
-        k = torch.zeros(64, 1, 2200, 128, dtype=torch.float16, device="cuda:0")
+        k = torch.zeros(64, 1, 2304, 128, dtype=torch.float16, device="cuda:0")
         c.append(0, k, k)
+        B.ttkv_set_split(c.h, 1 << 20)                          # the finest split: 256-token items, 9 per sequence
         parts = B.ttkv_count_parts(c.h, c.c)
-        assert 64 * 64 * parts * 520 > B.TTKV_NOALLOC_SCRATCH_BYTES, parts
+        assert parts == 9 and 64 * 64 * parts * 520 > B.TTKV_NOALLOC_SCRATCH_BYTES, parts
         q = torch.zeros(64, 64, 128, dtype=torch.float16, device="cuda:0")
         out = torch.full((64, 64, 128), 7.0, dtype=torch.float32, device="cuda:0")
         with pytest.raises(B.TTKVError) as e:
