@@ -154,11 +154,13 @@ int items_for(int64_t len, int per_token, double item_bytes) {
 // target is therefore raised from the kernel's default (default_items) in steps until the items are within 10 % of
 // their mean and the last round is filled (or there are at least three rounds); failing that, the candidate with
 // the smallest estimated loss is taken.  target_items != 0 (ttkv_set_split) is taken as given.
-double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_items) {
+double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_items, const int64_t *last_tokens) {
+  // last_tokens: null, or the tokens of the last tier that are attended, per sequence (its selected blocks)
+  auto run_len = [&](int t, int b) { return last_tokens && t == c->n_tiers - 1 ? last_tokens[b] : c->tier[t].len[b]; };
   int64_t S = 0;   // bytes one pass over one KV head's tokens streams
   for (int t = 0; t < c->n_tiers; ++t) {
     if (!dense[t]) continue;
-    for (int b = 0; b < c->batch; ++b) S += c->tier[t].len[b] * per_token_bytes(c->tier[t]);
+    for (int b = 0; b < c->batch; ++b) S += run_len(t, b) * per_token_bytes(c->tier[t]);
   }
   if (S == 0) return 1.0;
   const int Hkv = c->n_kv_heads, G = c->n_q_heads / Hkv;
@@ -172,30 +174,44 @@ double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_item
   static const float steps_m[] = {1.0f, 1.5f, 2.0f, 2.5f, 3.0f, 4.0f, 5.0f, 6.0f};
   double best_b = 0.0, best_loss = 1e30;
   for (int k = 0; k < 8; ++k) {
-    const double target = (double)resident * (vector_kernel ? steps_v[k] : steps_m[k]);
-    const double b = std::max(1.0, (double)S * Hkv / target);
-    double largest = 0.0, sum_b = 0.0, sum_b2 = 0.0;
+    const double want_rounds = vector_kernel ? steps_v[k] : steps_m[k];
+    double b = std::max(1.0, (double)S * Hkv / (resident * want_rounds));
+    double largest = 0.0, sum_b = 0.0, sum_b2 = 0.0, n_big = 0.0;
     bool all_max = true;   // no run can be cut finer
-    for (int t = 0; t < c->n_tiers; ++t) {
-      if (!dense[t]) continue;
-      const int pt = per_token_bytes(c->tier[t]);
-      for (int q = 0; q < c->batch; ++q) {
-        const int64_t len = c->tier[t].len[q];
-        if (len == 0) continue;
-        const int n = items_for(len, pt, b);
-        const double ib = (double)even_chunk((int)len, n) * pt;
-        sum_b += n * ib;
-        sum_b2 += n * ib * ib;
-        largest = std::max(largest, ib);
-        all_max &= n >= std::max<int64_t>(1, len / 256);
+    // the item counts come out in steps: if they overshoot the rounds aimed at, ask for slightly larger items
+    for (int attempt = 0; attempt < 4; ++attempt) {
+      if (attempt) b *= 1.03;
+      largest = sum_b = sum_b2 = 0.0;
+      all_max = true;
+      for (int pass = 0; pass < 2; ++pass) {   // pass 1 counts the items of at least half the largest size
+        n_big = 0.0;
+        for (int t = 0; t < c->n_tiers; ++t) {
+          if (!dense[t]) continue;
+          const int pt = per_token_bytes(c->tier[t]);
+          for (int q = 0; q < c->batch; ++q) {
+            const int64_t len = run_len(t, q);
+            if (len == 0) continue;
+            const int n = items_for(len, pt, b);
+            const double ib = (double)even_chunk((int)len, n) * pt;
+            if (pass == 0) {
+              sum_b += n * ib;
+              sum_b2 += n * ib * ib;
+              largest = std::max(largest, ib);
+              all_max &= n >= std::max<int64_t>(1, len / 256);
+            } else if (2.0 * ib >= largest) {
+              n_big += n;
+            }
+          }
+        }
       }
+      if (n_big * per_item <= resident * want_rounds || all_max) break;
     }
-    // Short items (a 256-token window beside a long tier) neither unbalance a launch nor fill a round: both
-    // measures weigh an item by its bytes.  rounds: the launch in units of its largest item per resident slot.
+    // Short items (a 256-token window beside a long tier) neither unbalance a launch nor fill a round: the mean
+    // weighs an item by its bytes, the rounds count only the items of at least half the largest size.
     const double imbalance = largest / (sum_b2 / sum_b);
-    const double rounds = sum_b * per_item / largest / resident;
+    const double rounds = n_big * per_item / resident;
     const double frac = rounds - std::floor(rounds);
-    const double fill = frac <= 0.08 && rounds >= 1.0 ? 1.0 : frac;
+    const double fill = frac == 0.0 ? 1.0 : frac;
     const bool filled = rounds >= 3.0 || fill >= (vector_kernel ? 0.45 : 0.75) || (rounds < 1.0 && (all_max || rounds >= 0.75));
     if (imbalance <= 1.10 && filled) return b;
     const double loss = imbalance * (1.0 + (1.0 - fill) / std::max(1.0, std::ceil(rounds)));
@@ -219,9 +235,16 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
   P->fetch.clear();
   for (int b = 0; b < c->batch; ++b) P->parts[b] = 0;
   const int last = c->n_tiers - 1;
-  for (int t = 0; t < c->n_tiers; ++t)
-    P->even[t] = c->tier[t].mem != TTKV_MEM_HOST_PINNED && !((sel_blocks || ds) && t == last);
-  const double item_bytes = choose_item_bytes(c, P->even, target_items);
+  // tiers in HBM are cut into items of equal size per run; so are the blocks a device-side selection names
+  for (int t = 0; t < c->n_tiers; ++t) P->even[t] = c->tier[t].mem != TTKV_MEM_HOST_PINNED && !(sel_blocks && t == last);
+  int64_t sel_tokens[TTKV_MAX_BATCH];
+  if (ds)
+    for (int b = 0; b < c->batch; ++b) {
+      const ttkv_tier &T = c->tier[last];
+      const int64_t live = T.len[b] ? (T.start[b] + T.len[b] + T.block_tokens - 1) / T.block_tokens - T.start[b] / T.block_tokens : 0;
+      sel_tokens[b] = std::max<int64_t>(0, std::min<int64_t>(std::min(ds->k, ds->stride), live)) * T.block_tokens;
+    }
+  const double item_bytes = choose_item_bytes(c, P->even, target_items, ds ? sel_tokens : nullptr);
   for (int t = 0; t < c->n_tiers; ++t) {
     const ttkv_tier &T = c->tier[t];
     const Layout L = make_layout(T, c->n_kv_heads);
@@ -231,10 +254,21 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     // staged slots and selected blocks of a device tier: 256-token items for parallelism
     P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : 0;   // 0: items of equal size per run
     if (ds && t == last) P->chunk[t] = host ? 2048 : 256;
+    if (ds && t == last && !host) P->chunk[t] = 0;
+    if (!host && sparse && t == last) {
+      // Blocks of a tier in HBM that the caller selected (ids on the host): one item per block once the selection
+      // alone fills the chip, finer items, down to 256 tokens, when few blocks are selected.
+      int64_t n_sel = 0;
+      for (int b = 0; b < c->batch; ++b) n_sel += sel_count[b];
+      const int legacy = default_items(c), resident = legacy == 2560 ? 1024 : legacy;
+      const int64_t wgs = std::max<int64_t>(1, n_sel * c->n_kv_heads);
+      const int ipb = (int)std::min<int64_t>(L.bt / 256, std::max<int64_t>(1, (resident + wgs - 1) / wgs));
+      P->chunk[t] = ((L.bt + ipb - 1) / ipb + 63) / 64 * 64;
+    }
     const int chunk = P->chunk[t];
     if (ds && t == last) {
       // the kernel looks the block ids up itself: the host only knows how many there are
-      const int ipb = (L.bt + chunk - 1) / chunk;   // items per block
+      const int ipb = host ? (L.bt + chunk - 1) / chunk : 0;   // items per block
       for (int b = 0; b < c->batch; ++b) {
         const int64_t first_id = T.start[b] / L.bt;
         const int64_t end_id = (T.start[b] + T.len[b] + L.bt - 1) / L.bt;  // exclusive
@@ -244,10 +278,10 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
         r.tier = t; r.b = b;
         r.rec_base = (int32_t)((int64_t)b * ds->stride);
         r.first_tok = (int32_t)(end_id - 1);
-        r.len = count;
+        r.len = host ? count : count * L.bt;     // blocks in fixed items, or their tokens as one run in equal items
         r.selected = true;
         r.part_base = P->parts[b];
-        r.n_chunks = count * ipb;
+        r.n_chunks = host ? count * ipb : items_for((int64_t)count * L.bt, per_token_bytes(T), item_bytes);
         P->parts[b] += r.n_chunks;
         P->runs.push_back(r);
       }

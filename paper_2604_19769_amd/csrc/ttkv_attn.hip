@@ -41,9 +41,10 @@ using namespace dev;
 
 // Everything one wave accumulates for one item.
 template <int KF, int VF, int G>
-__device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
-                                        int chunk, int seq, int hkv, int hq0, float (*s_acc)[4][G][128], float (*s_m)[G],
-                                        float (*s_l)[G]) {
+__device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, const Entry &en, const int32_t *sel,
+                                        int chunk_tokens, int chunk, int seq, int hkv, int hq0, float (*s_acc)[4][G][128],
+                                        float (*s_m)[G], float (*s_l)[G]) {
+  // sel: null, or the block ids behind a run made of selected blocks (ring block of token i: sel[i / bt])
   using FK = Fmt<KF>;
   using FV = Fmt<VF>;
   static_assert(FV::TPL % FK::TPL == 0, "V rows must not be wider than K rows");
@@ -134,8 +135,9 @@ __device__ __forceinline__ void process(const FusedArgs &a, const TierView &tv, 
     constexpr bool FULL = decltype(full_tag)::value;
     int tok0 = en.first_tok + i0;
     if (tok0 >= ring_tokens) tok0 -= ring_tokens;
-    const int rb = tok0 / tv.bt;
+    int rb = tok0 / tv.bt;
     const int row0 = tok0 - rb * tv.bt;
+    if (sel) rb = sel[rb] % tv.ring_blocks;
     const int64_t rec = tv.table ? (int64_t)tv.table[(int64_t)seq * tv.ring_blocks + rb] : (int64_t)en.rec_base + rb;
     const uint8_t *head = tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
     // wave-uniform section bases of the tile + per-lane 32-bit offsets: the loads below can
@@ -389,31 +391,32 @@ __global__ __launch_bounds__(256) void attn_fused_kernel(const FusedArgs a) {
   TierView tv = a.tv[tier];
   if (en.tier_seq & (1 << 24)) tv.table = nullptr;   // the run names pool records directly
   int chunk_tokens = a.chunk[tier];
-  if (chunk_tokens == 0) chunk_tokens = even_chunk(en.len, (lo + 1 < a.n_entries ? a.e[lo + 1].item_start : a.n_items) - en.item_start);
+  const bool equal_items = chunk_tokens == 0;
+  if (equal_items) chunk_tokens = even_chunk(en.len, (lo + 1 < a.n_entries ? a.e[lo + 1].item_start : a.n_items) - en.item_start);
   const int part = en.part_base + item - en.item_start;   // this item's partial
   int chunk = item - en.item_start;
-  resolve_selected(a, tv, en, seq, chunk_tokens, chunk);
+  const int32_t *sel = resolve_selected(a, tv, en, seq, equal_items, chunk_tokens, chunk);
 
   const int combo = tv.k_fmt * 8 + tv.v_fmt;
   switch (combo) {
     case TTKV_F16 * 8 + TTKV_F16:
-      process<TTKV_F16, TTKV_F16, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      process<TTKV_F16, TTKV_F16, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     case TTKV_BF16 * 8 + TTKV_BF16:
-      process<TTKV_BF16, TTKV_BF16, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      process<TTKV_BF16, TTKV_BF16, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     case TTKV_I8_SYM_G32 * 8 + TTKV_I8_SYM_G32:
-      process<TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      process<TTKV_I8_SYM_G32, TTKV_I8_SYM_G32, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     case TTKV_I4_ASYM_G64 * 8 + TTKV_I4_ASYM_G64:
-      process<TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      process<TTKV_I4_ASYM_G64, TTKV_I4_ASYM_G64, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     case TTKV_I4_ASYM_T128 * 8 + TTKV_I4_ASYM_G64:
       if constexpr (T128)
-        process<TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+        process<TTKV_I4_ASYM_T128, TTKV_I4_ASYM_G64, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
     default:
-      process<TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, G>(a, tv, en, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
+      process<TTKV_I8_SYM_G32, TTKV_I4_ASYM_G64, G>(a, tv, en, sel, chunk_tokens, chunk, seq, hkv, hq0, s_acc, s_m, s_l);
       break;
   }
   __syncthreads();

@@ -112,12 +112,24 @@ __device__ __forceinline__ float group_sum(float v) {
   if constexpr (LPT >= 16) v += dpp<0x140>(v);  // row_mirror: lane i <- lane 15-i = the other half's sum
   return v;
 }
-// A run whose blocks are named by the device-side selection: item `chunk` of the run is sub-chunk chunk % ipb of
-// the run's (chunk / ipb)-th selected block.  The entry is rewritten into a run over that one block, so that
-// everything after it sees an ordinary run.  Only the tier's newest block can be partly filled.
-__device__ __forceinline__ void resolve_selected(const FusedArgs &a, const TierView &tv, Entry &en, int seq, int chunk_tokens,
-                                                 int &chunk) {
-  if (!(en.tier_seq & (1 << 25))) return;
+// A run whose blocks are named by the device-side selection (ids ascending, so only the last can be the tier's
+// partly filled newest block).  Two forms, told apart by the tier's item size in the launch arguments:
+//   fixed items (host tiers): item `chunk` of the run is sub-chunk chunk % ipb of the run's (chunk / ipb)-th
+//     selected block; the entry is rewritten into a run over that one block;
+//   equal items (tiers in HBM): the tokens of all selected blocks form ONE run of len tokens, cut like any other
+//     run; token i of it lies in block ids[i / bt], which the tile address look-up follows (`sel`), so an item may
+//     span several blocks and small blocks cost no more than large ones.
+// Either way everything after this sees an ordinary run.  Returns the run's id list for the second form.
+__device__ __forceinline__ const int32_t *resolve_selected(const FusedArgs &a, const TierView &tv, Entry &en, int seq,
+                                                           bool equal_items, int chunk_tokens, int &chunk) {
+  if (!(en.tier_seq & (1 << 25))) return nullptr;
+  if (equal_items) {
+    const int32_t *ids = a.sel_ids + en.rec_base;
+    if (ids[en.len / tv.bt - 1] == en.first_tok) en.len -= tv.bt - a.sel_last_ntok[seq];
+    en.first_tok = 0;
+    en.rec_base = seq * tv.ring_blocks;
+    return ids;
+  }
   const int ipb = (tv.bt + chunk_tokens - 1) / chunk_tokens;
   const int blk = chunk / ipb;
   chunk -= blk * ipb;
@@ -125,6 +137,7 @@ __device__ __forceinline__ void resolve_selected(const FusedArgs &a, const TierV
   en.len = id == en.first_tok ? a.sel_last_ntok[seq] : tv.bt;
   en.first_tok = (id % tv.ring_blocks) * tv.bt;
   en.rec_base = seq * tv.ring_blocks;
+  return nullptr;
 }
 
 __device__ __forceinline__ float wave_max(float v) {

@@ -190,9 +190,10 @@ __device__ __forceinline__ void lds_half_i8(uint32_t a0, uint32_t a1, uint32_t m
 // and the group sum below depend on it; columns of heads beyond the real count stay zero), or 0 to take the real
 // count from the arguments (fp16 / bf16 / keys grouped over tokens: any count up to 16).
 template <int KF, int VF, int GT>
-__device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, int chunk_tokens,
-                                             int chunk, int seq, int hq0, int Gr, int hkv, char *s_buf,
+__device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView &tv, const Entry &en, const int32_t *sel,
+                                             int chunk_tokens, int chunk, int seq, int hq0, int Gr, int hkv, char *s_buf,
                                              float (*s_m)[16], float (*s_l)[16]) {
+  // sel: null, or the block ids behind a run made of selected blocks (ring block of token i: sel[i / bt])
   // hq0, Gr: first query head and number of heads of this workgroup's block of heads (all heads of the KV head,
   // or a block of up to 8 / 16 of them)
   const int G = GT ? GT : Gr;              // heads per group block of columns
@@ -360,9 +361,10 @@ __device__ __forceinline__ void process_mfma(const FusedArgs &a, const TierView 
   auto locate = [&](int i, int &row0) -> const uint8_t * {
     int tok0 = en.first_tok + i;
     if (tok0 >= ring_tokens) tok0 -= ring_tokens;
-    const int rb = tok0 / tv.bt;
+    int rb = tok0 / tv.bt;
     row0 = tok0 - rb * tv.bt;
     typedef const __attribute__((address_space(4))) int32_t *const_i32;
+    if (sel) rb = ((const_i32)(uintptr_t)sel)[rb] % tv.ring_blocks;   // written by the launch before this one: a scalar load
     const int64_t rec = tv.table ? (int64_t)((const_i32)(uintptr_t)tv.table)[(int64_t)seq * tv.ring_blocks + rb]
                                  : (int64_t)en.rec_base + rb;
     return tv.base + rec * tv.rec_bytes + (int64_t)hkv * tv.head_bytes;
@@ -877,13 +879,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(GQ == 16 ? 
   TierView tv = a.tv[tier];
   if (en.tier_seq & (1 << 24)) tv.table = nullptr;   // the run names pool records directly
   int chunk_tokens = a.chunk[tier];
-  if (chunk_tokens == 0) chunk_tokens = even_chunk(en.len, (lo + 1 < a.n_entries ? a.e[lo + 1].item_start : a.n_items) - en.item_start);
+  const bool equal_items = chunk_tokens == 0;
+  if (equal_items) chunk_tokens = even_chunk(en.len, (lo + 1 < a.n_entries ? a.e[lo + 1].item_start : a.n_items) - en.item_start);
   const int part = en.part_base + item - en.item_start;   // this item's partial
   int chunk = item - en.item_start;
-  resolve_selected(a, tv, en, seq, chunk_tokens, chunk);
+  const int32_t *sel = resolve_selected(a, tv, en, seq, equal_items, chunk_tokens, chunk);
 
   const int combo = tv.k_fmt * 8 + tv.v_fmt;
-#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, chunk_tokens, chunk, seq, hq0, G, hkv, s_buf, s_m, s_l)
+#define TTKV_MFMA_CASE(KF, VF, GT) process_mfma<KF, VF, GT>(a, tv, en, sel, chunk_tokens, chunk, seq, hq0, G, hkv, s_buf, s_m, s_l)
   switch (combo) {
     case TTKV_F16 * 8 + TTKV_F16: TTKV_MFMA_CASE(TTKV_F16, TTKV_F16, 0); break;
     case TTKV_BF16 * 8 + TTKV_BF16: TTKV_MFMA_CASE(TTKV_BF16, TTKV_BF16, 0); break;

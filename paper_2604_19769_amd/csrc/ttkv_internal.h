@@ -82,7 +82,8 @@ struct Run {
   int tier, b;
   int32_t rec_base, first_tok, len;
   bool no_table;
-  bool selected;   // `len` blocks named by the device-side selection (rec_base: index of the first id, first_tok: newest block id)
+  bool selected;   // blocks named by the device-side selection (rec_base: index of the first id, first_tok: newest block
+                   // id; len: their number for a host tier, their tokens for a tier in HBM)
   int part_base, n_chunks;
 };
 // Selection left on the device by the top-k kernel: ids [batch][stride], min(k, live blocks) of them per sequence.
@@ -186,8 +187,9 @@ hipError_t launch_summary(const ConvArgs &a, hipStream_t s, int *n_kernels);
 #define TTKV_MAX_ENTRIES 120
 struct Entry {
   int32_t tier_seq;     // bit 24: ignore the block table (rec_base is a pool record); bits 16-23 tier; low 16 sequence
-                        // bit 25: the run is `len` blocks named by the device-side selection: rec_base = index of
-                        // its first id in FusedArgs::sel_ids, first_tok = id of the tier's newest live block
+                        // bit 25: the run is made of blocks named by the device-side selection: rec_base = index of
+                        // its first id in FusedArgs::sel_ids, first_tok = id of the tier's newest live block, len =
+                        // the number of blocks (tier cut into fixed items) or their tokens (equal items)
   int32_t rec_base;     // record of ring block 0 (no table) or of the run's first block
   int32_t first_tok;    // ring token index of the run's first token (multiple of 64)
   int32_t len;          // tokens

@@ -9,6 +9,8 @@
 
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
 namespace ttkv {
 
 namespace {
@@ -71,25 +73,27 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(const SelectArg
   if (lane == 0) a.scores[(int64_t)b * a.max_blocks + i] = phi;
 }
 
-// One workgroup per sequence.  rank(j) = #{i : s_i > s_j or (s_i == s_j and i < j)} with NaN read as -inf, so the
-// ranks are a permutation; block j is kept iff rank(j) < k; ids are written ascending, never more than
-// min(k, sel_stride) of them.
-__global__ __launch_bounds__(256) void topk_kernel(const SelectArgs a) {
+// One workgroup per sequence, a thread per block where the launch can afford it (256 to 1024 threads, chosen from the
+// largest live block count: the ranking is n^2 comparisons -- at 768 blocks 86 us with 256 threads, a quarter of
+// that with 1024).  rank(j) = #{i : s_i > s_j or (s_i == s_j and i < j)} with NaN read as -inf, so the ranks are a
+// permutation; block j is kept iff rank(j) < k; ids are written ascending, never more than min(k, sel_stride).
+__global__ __launch_bounds__(1024) void topk_kernel(const SelectArgs a) {
   __shared__ __align__(16) float score[1024];
-  __shared__ int wave_kept[4];
+  __shared__ int wave_kept[16];
   const int b = blockIdx.x;
   const int n = a.n_blocks[b];
+  const int threads = blockDim.x, n_waves = threads >> 6;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n4 = (n + 3) & ~3;
-  for (int j = threadIdx.x; j < n4; j += 256) {
+  for (int j = threadIdx.x; j < n4; j += threads) {
     const float s = j < n ? a.scores[(int64_t)b * a.max_blocks + j] : -INFINITY;   // padding: never ahead of a live block with a lower index
     score[j] = s != s ? -INFINITY : s;
   }
   __syncthreads();
   const int limit = min(a.k, a.sel_stride);
   int32_t *ids = a.sel_out + a.n_seq + (int64_t)b * a.sel_stride;
-  int written = 0;                                     // ids written by earlier rounds of 256 blocks (same in every thread)
-  for (int base = 0; base < n; base += 256) {
+  int written = 0;                                     // ids written by earlier rounds (same in every thread)
+  for (int base = 0; base < n; base += threads) {
     const int j = base + threadIdx.x;
     bool kept = false;
     if (j < n) {
@@ -108,11 +112,15 @@ __global__ __launch_bounds__(256) void topk_kernel(const SelectArgs a) {
     const unsigned long long mask = __ballot(kept);
     if (lane == 0) wave_kept[wave] = __popcll(mask);
     __syncthreads();
-    int before = written;
-    for (int w = 0; w < wave; ++w) before += wave_kept[w];
+    int before = written, all = 0;
+    for (int w = 0; w < n_waves; ++w) {
+      const int kw = wave_kept[w];
+      before += w < wave ? kw : 0;
+      all += kw;
+    }
     const int pos = before + __popcll(mask & ((1ull << lane) - 1ull));
     if (kept && pos < limit) ids[pos] = (int32_t)(a.first_block_id[b] + j);
-    written += wave_kept[0] + wave_kept[1] + wave_kept[2] + wave_kept[3];
+    written += all;
     __syncthreads();
   }
   if (threadIdx.x == 0) a.sel_out[b] = min(written, limit);
@@ -128,7 +136,8 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(score_kernel<false>, grid, dim3(SCORE_WAVES * 64), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(topk_kernel, dim3(a.n_seq), dim3(256), 0, s, a);
+  const int threads = std::min(1024, std::max(256, (a.max_blocks + 63) / 64 * 64));
+  hipLaunchKernelGGL(topk_kernel, dim3(a.n_seq), dim3(threads), 0, s, a);
   return hipGetLastError();
 }
 

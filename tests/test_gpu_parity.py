@@ -236,11 +236,23 @@ def test_paged_tiers_with_ragged_batch(n_slots):
                lens=[300, 1500, 2900, 2047], check_state_every=35, n_slots=n_slots)
 
 
-@pytest.mark.parametrize("n_slots", [0, 2])
-def test_sparse_block_selection(n_slots):
-    """Block identification: mean-key summaries, phi, top-k; only selected host blocks are fetched."""
-    tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40))
+@pytest.mark.parametrize("n_slots,host", [(0, True), (2, True), (0, False)])
+def test_sparse_block_selection(n_slots, host):
+    """Block identification: mean-key summaries, phi, top-k; only selected host blocks are fetched.  With the last
+    tier in HBM the selected blocks' tokens are attended as one run per sequence, in items that span blocks."""
+    tiers = tiers3("bf16", summary=True, bts=(64, 128, 128), rings=(6, 8, 40), host=host)
     run_config(2, 8, 2, tiers, "bf16", 3500, 40, synth.SEED_BASE + 6, select_k=6, check_state_every=20, n_slots=n_slots)
+
+
+@pytest.mark.parametrize("Hq,Hkv,fmt,k", [(4, 2, ("i4", "i4"), 100), (8, 2, ("i8", "i4c"), 37), (2, 2, ("i8", "i8"), 700)])
+def test_selection_among_hundreds_of_small_blocks_in_hbm(Hq, Hkv, fmt, k):
+    """The last tier in HBM in 64-token blocks, 600 to 700 of them live per sequence (the ranking runs with a thread per
+    block), ragged over the batch; k of them attended as one run per sequence whose items span many blocks; k above the
+    number of live blocks attends everything, the partly filled newest block included."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=128, block_tokens=64, ring_blocks=4),
+             dict(k_fmt=fmt[0], v_fmt=fmt[1], capacity=10**9, block_tokens=64, ring_blocks=720, summary=True)]
+    run_config(2, Hq, Hkv, tiers, "f16", None, 70, synth.SEED_BASE + 95 + k, select_k=k, check_state_every=35,
+               lens=[127 + 64 * 600, 127 + 64 * 690], peaked=True)
 
 
 def test_bf16_query_on_fp16_and_quantized_tiers_and_large_batch():
@@ -468,10 +480,10 @@ def test_channel_major_values_are_refused_where_no_kernel_takes_them():
         p.close()
 
 
-@pytest.mark.parametrize("n_slots,paged", [(0, False), (2, False), (0, True)])
-def test_block_selection_over_channel_major_values(n_slots, paged):
+@pytest.mark.parametrize("n_slots,paged,host", [(0, False, True), (2, False, True), (0, True, True), (0, False, False), (0, True, False)])
+def test_block_selection_over_channel_major_values(n_slots, paged, host):
     """Block identification + top-k + attention of the selected host blocks when the host tier's values are stored
     channel-major per 32 tokens: ids left on the device (the kernel looks the blocks up and takes the newest one's
     live length, a multiple of 32, from the launch arguments), ids on the host with staged copies, paged records."""
-    tiers = tiers3("bf16", fmts=(("i8", "i8"), ("i4", "i4c")), summary=True, bts=(64, 128, 128), rings=(6, 8, 40), paged=paged)
+    tiers = tiers3("bf16", fmts=(("i8", "i8"), ("i4", "i4c")), summary=True, bts=(64, 128, 128), rings=(6, 8, 40), paged=paged, host=host)
     run_config(2, 8, 2, tiers, "bf16", 255 + 512 + 32 * 85, 40, synth.SEED_BASE + 90, select_k=6, check_state_every=20, n_slots=n_slots)

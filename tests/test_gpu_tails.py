@@ -146,14 +146,16 @@ def test_dominant_key_in_a_host_tier(Hq, Hkv, n_slots):
         p.close()
 
 
+@pytest.mark.parametrize("mem", ["host", "device"])
 @pytest.mark.parametrize("Hq,Hkv", [(2, 2), (8, 2)])
-def test_dominant_key_in_the_partly_filled_newest_selected_block(Hq, Hkv):
+def test_dominant_key_in_the_partly_filled_newest_selected_block(Hq, Hkv, mem):
     """Block identification with the ids left on the device: the attention kernels look up each selected block and
-    take the live token count of the newest one from the launch arguments.  Every block is selected (k above their
-    number); the planted keys include the last live token of that block."""
+    take the live token count of the newest one from the launch arguments (a host tier block by block, a tier in HBM
+    as one run over all selected blocks).  Every block is selected (k above their number); the planted keys include
+    the last live token of that block."""
     tiers = [dict(k_fmt="bf16", v_fmt="bf16", capacity=256, block_tokens=64, ring_blocks=6),
              dict(k_fmt="i8", v_fmt="i8", capacity=512, block_tokens=128, ring_blocks=8),
-             dict(k_fmt="i4", v_fmt="i4", capacity=10**9, block_tokens=128, ring_blocks=40, mem="host", summary=True)]
+             dict(k_fmt="i4", v_fmt="i4", capacity=10**9, block_tokens=128, ring_blocks=40, mem=mem, summary=True)]
     p = Pair(2, Hq, Hkv, tiers, "bf16")
     try:
         # steps with append and eviction (the device-side selection is part of the step call); the host tier only
