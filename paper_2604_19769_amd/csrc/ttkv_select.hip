@@ -73,57 +73,83 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void score_kernel(const SelectArg
   if (lane == 0) a.scores[(int64_t)b * a.max_blocks + i] = phi;
 }
 
-// One workgroup per sequence, a thread per block where the launch can afford it (256 to 1024 threads, chosen from the
-// largest live block count: the ranking is n^2 comparisons -- at 768 blocks 86 us with 256 threads, a quarter of
-// that with 1024).  rank(j) = #{i : s_i > s_j or (s_i == s_j and i < j)} with NaN read as -inf, so the ranks are a
-// permutation; block j is kept iff rank(j) < k; ids are written ascending, never more than min(k, sel_stride).
+// One workgroup per sequence, one thread per live block (at most 1024).  The k blocks to keep are those with
+// rank(j) = #{i : s_i > s_j or (s_i == s_j and i < j)} < k, NaN read as -inf.  Instead of counting ranks (n^2
+// comparisons: 86 us at 768 blocks) the k-th largest score is found by a radix select over the scores' order-
+// preserving 32-bit keys, one byte per pass (a 256-bin histogram in LDS, its crossing bin found by one wave), which
+// is exact; among the blocks whose score equals it the lowest ids fill the remaining places.  Ids are written
+// ascending by a ballot / popcount prefix, never more than min(k, sel_stride) of them.
 __global__ __launch_bounds__(1024) void topk_kernel(const SelectArgs a) {
-  __shared__ __align__(16) float score[1024];
-  __shared__ int wave_kept[16];
+  __shared__ __align__(16) uint32_t hist[256];
+  __shared__ uint32_t s_prefix, s_remaining;
+  __shared__ int wave_eq[16], wave_kept[16];
   const int b = blockIdx.x;
   const int n = a.n_blocks[b];
-  const int threads = blockDim.x, n_waves = threads >> 6;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n4 = (n + 3) & ~3;
-  for (int j = threadIdx.x; j < n4; j += threads) {
-    const float s = j < n ? a.scores[(int64_t)b * a.max_blocks + j] : -INFINITY;   // padding: never ahead of a live block with a lower index
-    score[j] = s != s ? -INFINITY : s;
-  }
-  __syncthreads();
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+  const bool valid = tid < n;                       // the launch has at least as many threads as live blocks
+  float s = valid ? a.scores[(int64_t)b * a.max_blocks + tid] : -INFINITY;
+  if (s != s) s = -INFINITY;
+  if (s == 0.0f) s = 0.0f;                          // -0 and +0 compare equal: one key for both
+  const uint32_t u = __float_as_uint(s);
+  const uint32_t key = (u >> 31) ? ~u : (u | 0x80000000u);   // a larger score is a larger key; equal scores, equal keys
   const int limit = min(a.k, a.sel_stride);
+  const int keep = min(a.k, n);
   int32_t *ids = a.sel_out + a.n_seq + (int64_t)b * a.sel_stride;
-  int written = 0;                                     // ids written by earlier rounds (same in every thread)
-  for (int base = 0; base < n; base += threads) {
-    const int j = base + threadIdx.x;
-    bool kept = false;
-    if (j < n) {
-      const float sj = score[j];
-      int rank = 0;
-      for (int i = 0; i < n4; i += 4) {
-        const float4 si = *(const float4 *)&score[i];
-        rank += (si.x > sj) || (si.x == sj && i < j);
-        rank += (si.y > sj) || (si.y == sj && i + 1 < j);
-        rank += (si.z > sj) || (si.z == sj && i + 2 < j);
-        rank += (si.w > sj) || (si.w == sj && i + 3 < j);
+  bool kept = valid && keep >= n;
+  if (keep > 0 && keep < n) {                       // workgroup-uniform
+    uint32_t prefix = 0, remaining = (uint32_t)keep;   // high bytes of the k-th largest key found so far; places left among the keys that share them
+    for (int pass = 3; pass >= 0; --pass) {
+      for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
+      __syncthreads();
+      if (valid && (pass == 3 || (key >> (8 * (pass + 1))) == prefix)) atomicAdd(&hist[(key >> (8 * pass)) & 255u], 1u);
+      __syncthreads();
+      if (wave == 0) {
+        // lane l holds bins 4 l .. 4 l + 3; suffix sums over the lanes find the bin in which the count from the top
+        // reaches `remaining`
+        const uint4 h4 = ((const uint4 *)hist)[lane];
+        const uint32_t mine = h4.x + h4.y + h4.z + h4.w;
+        uint32_t suf = mine;
+        for (int d = 1; d < 64; d <<= 1) {
+          const uint32_t o = __shfl_down(suf, d, 64);
+          if (lane + d < 64) suf += o;
+        }
+        const uint32_t above = suf - mine;          // keys in the bins of the lanes above this one
+        if (suf >= remaining && above < remaining) {   // exactly one lane
+          uint32_t r = remaining - above;
+          uint32_t bin;
+          if (h4.w >= r) bin = 3;
+          else if (h4.w + h4.z >= r) { bin = 2; r -= h4.w; }
+          else if (h4.w + h4.z + h4.y >= r) { bin = 1; r -= h4.w + h4.z; }
+          else { bin = 0; r -= h4.w + h4.z + h4.y; }
+          s_prefix = (prefix << 8) | (4u * lane + bin);
+          s_remaining = r;
+        }
       }
-      kept = rank < a.k;
+      __syncthreads();
+      prefix = s_prefix;
+      remaining = s_remaining;
     }
-    // ascending ids: a kept block's place is the number of kept blocks before it
-    const unsigned long long mask = __ballot(kept);
-    if (lane == 0) wave_kept[wave] = __popcll(mask);
+    // prefix is the k-th largest key; `remaining` of the blocks that have it are kept, lowest ids first
+    const bool eq = valid && key == prefix;
+    const unsigned long long eq_mask = __ballot(eq);
+    if (lane == 0) wave_eq[wave] = __popcll(eq_mask);
     __syncthreads();
-    int before = written, all = 0;
-    for (int w = 0; w < n_waves; ++w) {
-      const int kw = wave_kept[w];
-      before += w < wave ? kw : 0;
-      all += kw;
-    }
-    const int pos = before + __popcll(mask & ((1ull << lane) - 1ull));
-    if (kept && pos < limit) ids[pos] = (int32_t)(a.first_block_id[b] + j);
-    written += all;
-    __syncthreads();
+    int eq_before = __popcll(eq_mask & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
+    kept = valid && (key > prefix || (eq && (uint32_t)eq_before < remaining));
   }
-  if (threadIdx.x == 0) a.sel_out[b] = min(written, limit);
+  // ascending ids: a kept block's place is the number of kept blocks before it
+  const unsigned long long mask = __ballot(kept);
+  if (lane == 0) wave_kept[wave] = __popcll(mask);
+  __syncthreads();
+  int pos = __popcll(mask & ((1ull << lane) - 1ull)), all = 0;
+  for (int w = 0; w < n_waves; ++w) {
+    const int kw = wave_kept[w];
+    pos += w < wave ? kw : 0;
+    all += kw;
+  }
+  if (kept && pos < limit) ids[pos] = (int32_t)(a.first_block_id[b] + tid);
+  if (tid == 0) a.sel_out[b] = min(all, limit);
 }
 
 }  // namespace
@@ -136,7 +162,7 @@ hipError_t launch_select(const SelectArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(score_kernel<false>, grid, dim3(SCORE_WAVES * 64), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int threads = std::min(1024, std::max(256, (a.max_blocks + 63) / 64 * 64));
+  const int threads = std::min(1024, std::max(64, (a.max_blocks + 63) / 64 * 64));   // one thread per live block
   hipLaunchKernelGGL(topk_kernel, dim3(a.n_seq), dim3(threads), 0, s, a);
   return hipGetLastError();
 }
