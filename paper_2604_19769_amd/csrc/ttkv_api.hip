@@ -154,13 +154,24 @@ int items_for(int64_t len, int per_token, double item_bytes) {
 // target is therefore raised from the kernel's default (default_items) in steps until the items are within 10 % of
 // their mean and the last round is filled (or there are at least three rounds); failing that, the candidate with
 // the smallest estimated loss is taken.  target_items != 0 (ttkv_set_split) is taken as given.
-double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_items, const int64_t *last_tokens) {
+double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_items, const int64_t *last_tokens, SplitMemo *memo) {
   // last_tokens: null, or the tokens of the last tier that are attended, per sequence (its selected blocks)
-  auto run_len = [&](int t, int b) { return last_tokens && t == c->n_tiers - 1 ? last_tokens[b] : c->tier[t].len[b]; };
+  // The runs, gathered once: length and bytes per token (at most batch x tiers of them).
+  struct RunShape { int32_t len, per_token, finest; };
+  RunShape runs[TTKV_MAX_BATCH * TTKV_MAX_TIERS];
+  int n_runs = 0;
   int64_t S = 0;   // bytes one pass over one KV head's tokens streams
+  uint32_t sig = (uint32_t)c->batch * 31u + (uint32_t)c->n_tiers * 7u + (uint32_t)c->n_q_heads * 131u + (uint32_t)c->n_kv_heads * 17u;
   for (int t = 0; t < c->n_tiers; ++t) {
+    sig = sig * 33u + (uint32_t)(c->tier[t].k_fmt * 8 + c->tier[t].v_fmt) * 2u + (dense[t] ? 1u : 0u);
     if (!dense[t]) continue;
-    for (int b = 0; b < c->batch; ++b) S += run_len(t, b) * per_token_bytes(c->tier[t]);
+    const int pt = per_token_bytes(c->tier[t]);
+    for (int b = 0; b < c->batch; ++b) {
+      const int64_t len = last_tokens && t == c->n_tiers - 1 ? last_tokens[b] : c->tier[t].len[b];
+      if (len == 0) continue;
+      runs[n_runs++] = RunShape{(int32_t)len, pt, (int32_t)std::max<int64_t>(1, len / 256)};
+      S += len * pt;
+    }
   }
   if (S == 0) return 1.0;
   const int Hkv = c->n_kv_heads, G = c->n_q_heads / Hkv;
@@ -172,55 +183,66 @@ double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_item
   // the vector kernel's default of 2.5 rounds is as fast as one round when the items are equal (measured)
   static const float steps_v[] = {2.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 5.0f, 6.0f};
   static const float steps_m[] = {1.0f, 1.5f, 2.0f, 2.5f, 3.0f, 4.0f, 5.0f, 6.0f};
-  double best_b = 0.0, best_loss = 1e30;
-  for (int k = 0; k < 8; ++k) {
-    const double want_rounds = vector_kernel ? steps_v[k] : steps_m[k];
-    double b = std::max(1.0, (double)S * Hkv / (resident * want_rounds));
-    double largest = 0.0, sum_b = 0.0, sum_b2 = 0.0, n_big = 0.0;
-    bool all_max = true;   // no run can be cut finer
-    // the item counts come out in steps: if they overshoot the rounds aimed at, ask for slightly larger items
+  const float *steps = vector_kernel ? steps_v : steps_m;
+
+  struct Fit { double b, largest, sum_b, sum_b2, n_big; bool all_max; };
+  // Item size for `want_rounds` rounds.  The item counts come out in steps: if the large items (at least half the
+  // largest) overshoot the rounds aimed at, slightly larger items are asked for, up to three times.
+  auto fit = [&](double want_rounds) {
+    Fit f{};
+    f.b = std::max(1.0, (double)S * Hkv / (resident * want_rounds));
+    double item[TTKV_MAX_BATCH * TTKV_MAX_TIERS];
+    int count[TTKV_MAX_BATCH * TTKV_MAX_TIERS];
+    double n_big_before = -1.0;
     for (int attempt = 0; attempt < 4; ++attempt) {
-      if (attempt) b *= 1.03;
-      largest = sum_b = sum_b2 = 0.0;
-      all_max = true;
-      for (int pass = 0; pass < 2; ++pass) {   // pass 1 counts the items of at least half the largest size
-        n_big = 0.0;
-        for (int t = 0; t < c->n_tiers; ++t) {
-          if (!dense[t]) continue;
-          const int pt = per_token_bytes(c->tier[t]);
-          for (int q = 0; q < c->batch; ++q) {
-            const int64_t len = run_len(t, q);
-            if (len == 0) continue;
-            const int n = items_for(len, pt, b);
-            const double ib = (double)even_chunk((int)len, n) * pt;
-            if (pass == 0) {
-              sum_b += n * ib;
-              sum_b2 += n * ib * ib;
-              largest = std::max(largest, ib);
-              all_max &= n >= std::max<int64_t>(1, len / 256);
-            } else if (2.0 * ib >= largest) {
-              n_big += n;
-            }
-          }
-        }
+      if (attempt) f.b *= 1.03;
+      f.largest = f.sum_b = f.sum_b2 = f.n_big = 0.0;
+      f.all_max = true;
+      for (int r = 0; r < n_runs; ++r) {
+        count[r] = items_for(runs[r].len, runs[r].per_token, f.b);
+        item[r] = (double)even_chunk(runs[r].len, count[r]) * runs[r].per_token;
+        f.sum_b += count[r] * item[r];
+        f.sum_b2 += count[r] * item[r] * item[r];
+        f.largest = std::max(f.largest, item[r]);
+        f.all_max &= count[r] >= runs[r].finest;
       }
-      if (n_big * per_item <= resident * want_rounds || all_max) break;
+      bool all_min = true;   // every run in one item already: larger items change nothing
+      for (int r = 0; r < n_runs; ++r) {
+        if (2.0 * item[r] >= f.largest) f.n_big += count[r];
+        all_min &= count[r] == 1;
+      }
+      if (f.n_big * per_item <= resident * want_rounds || f.all_max || all_min || f.n_big == n_big_before) break;
+      n_big_before = f.n_big;   // the same count as before: the steps are coarser than the nudge
     }
+    return f;
+  };
+
+  // The search over the number of rounds is remembered (in the handle's plan) while the cache keeps its shape: the
+  // same tiers, formats and runs, the bytes within 1/32 of what they were; a call then only fits the item size.
+  if (memo && memo->valid && memo->sig == sig && memo->n_runs == n_runs && memo->sel == (last_tokens != nullptr) &&
+      std::llabs(S - memo->bytes) <= memo->bytes / 32)
+    return fit(steps[memo->step]).b;
+
+  double best_b = 0.0, best_loss = 1e30;
+  int best_step = 0;
+  for (int k = 0; k < 8; ++k) {
+    const Fit f = fit(steps[k]);
     // Short items (a 256-token window beside a long tier) neither unbalance a launch nor fill a round: the mean
     // weighs an item by its bytes, the rounds count only the items of at least half the largest size.
-    const double imbalance = largest / (sum_b2 / sum_b);
-    const double rounds = n_big * per_item / resident;
+    const double imbalance = f.largest / (f.sum_b2 / f.sum_b);
+    const double rounds = f.n_big * per_item / resident;
     const double frac = rounds - std::floor(rounds);
     const double fill = frac == 0.0 ? 1.0 : frac;
-    const bool filled = rounds >= 3.0 || fill >= (vector_kernel ? 0.45 : 0.75) || (rounds < 1.0 && (all_max || rounds >= 0.75));
-    if (imbalance <= 1.10 && filled) return b;
-    const double loss = imbalance * (1.0 + (1.0 - fill) / std::max(1.0, std::ceil(rounds)));
+    const bool filled = rounds >= 3.0 || fill >= (vector_kernel ? 0.45 : 0.75) || (rounds < 1.0 && (f.all_max || rounds >= 0.75));
+    const double loss = imbalance <= 1.10 && filled ? 0.0 : imbalance * (1.0 + (1.0 - fill) / std::max(1.0, std::ceil(rounds)));
     if (loss < best_loss) {
       best_loss = loss;
-      best_b = b;
+      best_b = f.b;
+      best_step = k;
     }
-    if (all_max) break;   // finer targets change nothing
+    if (loss == 0.0 || f.all_max) break;   // good enough, or finer targets change nothing
   }
+  if (memo) *memo = SplitMemo{true, sig, n_runs, last_tokens != nullptr, best_step, S};
   return best_b;
 }
 
@@ -244,7 +266,7 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
       const int64_t live = T.len[b] ? (T.start[b] + T.len[b] + T.block_tokens - 1) / T.block_tokens - T.start[b] / T.block_tokens : 0;
       sel_tokens[b] = std::max<int64_t>(0, std::min<int64_t>(std::min(ds->k, ds->stride), live)) * T.block_tokens;
     }
-  const double item_bytes = choose_item_bytes(c, P->even, target_items, ds ? sel_tokens : nullptr);
+  const double item_bytes = choose_item_bytes(c, P->even, target_items, ds ? sel_tokens : nullptr, &P->memo);
   for (int t = 0; t < c->n_tiers; ++t) {
     const ttkv_tier &T = c->tier[t];
     const Layout L = make_layout(T, c->n_kv_heads);
@@ -543,6 +565,7 @@ ttkv_status ttkv_create(ttkv_handle *out) {
     return TTKV_ERR_INVALID_ARG;
   }
   h->have_events = false;
+  h->plan.memo.valid = false;
   h->target_items = 0;
   h->check_tables = true;
   h->time_on = false;

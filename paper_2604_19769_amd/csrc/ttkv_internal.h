@@ -103,7 +103,17 @@ struct Fetch {
 // Lives in the handle and is rebuilt by every call: the vectors keep their storage, so a call allocates host
 // memory only when its plan is larger than any before it (ttkv_create reserves TTKV_PLAN_RESERVE entries).
 #define TTKV_PLAN_RESERVE 4096
+// What the search for the split-K item size settled on, kept while the cache keeps its shape.
+struct SplitMemo {
+  bool valid;
+  uint32_t sig;      // tiers, formats, head counts, batch
+  int n_runs;
+  bool sel;          // the last tier was a device-side selection
+  int step;          // index into the table of rounds
+  int64_t bytes;     // bytes of one pass over one KV head when it was chosen
+};
 struct Plan {
+  SplitMemo memo;
   std::vector<Run> runs;
   std::vector<Fetch> fetch;
   std::vector<const Run *> order;   // launch order of `runs`
