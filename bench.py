@@ -296,9 +296,9 @@ def build_offload128k(steps_total):
 
 # ------------------------------------------------------------------ workload: ragged paged serving batch
 
-def build_serving_ragged(steps_total, batch=16):
+def build_serving_ragged(steps_total, batch=16, last_mem="host"):
     """The ragged serving benchmark configuration: batch 16, 32 q / 8 kv heads, contexts uniform in [16K, 64K], 256-token pages with
-    shuffled page tables; 4K fp16 + 12K int8 in HBM, the rest int4 in pinned host memory."""
+    shuffled page tables; 4K fp16 + 12K int8 in HBM, the rest int4 in pinned host memory (last_mem "device": in HBM too)."""
     import numpy as np
     import torch
     from paper_2604_19769_amd import synth
@@ -310,7 +310,7 @@ def build_serving_ragged(steps_total, batch=16):
     ctx = synth.rng(SEED + 4).integers(16384, 65537, batch)
     tiers = [TierConfig("f16", "f16", 4096, page, 4096 // page + 1, paged_seed=SEED + 40),
              TierConfig("i8", "i8", 12288, page, 12288 // page + 2, paged_seed=SEED + 41),
-             TierConfig("i4", "i4", 10**9, page, (65536 - 16384) // page + 4, mem="host", paged_seed=SEED + 42)]
+             TierConfig("i4", "i4", 10**9, page, (65536 - 16384) // page + 4, mem=last_mem, paged_seed=SEED + 42)]
     cache = TieredCache(batch, Hq, Hkv, tiers)
     kv = []
     for b in range(batch):
@@ -328,6 +328,21 @@ def build_serving_ragged(steps_total, batch=16):
     vn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.float16)
     torch.cuda.synchronize()
     return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, ctx=ctx)
+
+
+def serving_ragged_all_in_hbm(steps, warmup):
+    """The same sequences, pages and formats with the int4 tier in HBM as well (1.3 GB of 288): what the placement costs."""
+    cache, kv, (q, kn, vn), shape = build_serving_ragged(steps + warmup, last_mem="device")
+    try:
+        del kv
+        settle(cache, q, 64)
+        timed_steps(cache, q, kn, vn, 0, warmup)
+        total, _ = algorithmic_bytes(cache)
+        t = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        return {"ms_per_step": round(t * 1e3, 4), "tokens_per_s": round(shape["B"] / t, 1), "bytes_per_step": int(total),
+                "effective_kv_GBs": round(total / t / 1e9, 1), "frac_of_hbm_peak": round(total / t / 1e9 / HBM_PEAK_GBS, 4)}
+    finally:
+        cache.close()
 
 
 def run_serving_ragged(steps, warmup, cpu_baseline=True):
@@ -352,8 +367,10 @@ def run_serving_ragged(steps, warmup, cpu_baseline=True):
             cpu = oracle_sample(tiers, [4096 + 512, 12288 + 1024, 65536], 32, 8, [0, 5], [(b, kv[b][0], kv[b][1])], steps_in, 0, keep[0],
                                 f"sequence {b} (the shortest, {int(shape['ctx'][b])} tokens) of 16, KV heads 0 and 5 of 8 (8 query "
                                 f"heads), the first decode step incl. append+evict")
+        hbm = serving_ragged_all_in_hbm(steps, warmup)
         return {"workload": "batch 16, 32 q / 8 kv heads, contexts U[16K, 64K] (mean %d), 256-token pages, 4K fp16 + 12K int8 in HBM, "
                             "rest int4 in pinned host memory" % int(shape["ctx"].mean()),
+                "same_cache_all_in_hbm": hbm,
                 "steps": steps, "ms_per_step": round(t * 1e3, 3), "tokens_per_s": round(shape["B"] / t, 1),
                 "host_tier_record_bytes_per_step": int(h2d), "host_tier_live_bytes_per_step": int(live),
                 "device_tier_bytes_per_step": int(by_tier[0] + by_tier[1]),
