@@ -310,7 +310,8 @@ def build_serving_ragged(steps_total, batch=16, last_mem="host"):
     ctx = synth.rng(SEED + 4).integers(16384, 65537, batch)
     tiers = [TierConfig("f16", "f16", 4096, page, 4096 // page + 1, paged_seed=SEED + 40),
              TierConfig("i8", "i8", 12288, page, 12288 // page + 2, paged_seed=SEED + 41),
-             TierConfig("i4", "i4", 10**9, page, (65536 - 16384) // page + 4, mem=last_mem, paged_seed=SEED + 42)]
+             TierConfig("i4", "i4c" if last_mem == "device" else "i4", 10**9, page, (65536 - 16384) // page + 4, mem=last_mem,
+                        paged_seed=SEED + 42)]   # in HBM: the same int4 codes stored channel-major per 32 tokens
     cache = TieredCache(batch, Hq, Hkv, tiers)
     kv = []
     for b in range(batch):
@@ -318,6 +319,8 @@ def build_serving_ragged(steps_total, batch=16, last_mem="host"):
         K = device_normal(gen, (Hkv, n, 128), torch.float16)
         V = device_normal(gen, (Hkv, n, 128), torch.float16)
         n2 = n - 4095 - 12288                      # oldest tokens -> host tier (>= 0 since ctx >= 16384)
+        if last_mem == "device":
+            n2 = n2 // 32 * 32                     # channel-major values arrive in whole groups of 32 tokens
         if n2 > 0:
             cache.append(2, K[:, :n2].contiguous(), V[:, :n2].contiguous(), seq=b, through_tiers=True)
         cache.append(1, K[:, n2:n2 + 12288].contiguous(), V[:, n2:n2 + 12288].contiguous(), seq=b, through_tiers=True)
