@@ -135,10 +135,10 @@ int even_items(int len, int want) {
     n = n2;
   }
 }
-// Items for a run of `len` tokens of `per_token` bytes when an item should stream about item_bytes: between 256
-// and 8192 tokens each.
+// Items for a run of `len` tokens of `per_token` bytes when an item should stream about item_bytes: at most 8192
+// tokens each, and no more items than 256-token ones would give.
 int items_for(int64_t len, int per_token, double item_bytes) {
-  const int64_t lo = (len + 8191) / 8192, hi = std::max<int64_t>(1, len / 256);
+  const int64_t lo = (len + 8191) / 8192, hi = (len + 255) / 256;
   const int64_t want = (int64_t)((double)len * per_token / item_bytes + 0.5);
   return even_items((int)len, (int)std::max(lo, std::min(hi, want)));
 }
@@ -169,7 +169,7 @@ double choose_item_bytes(const ttkv_cache *c, const bool *dense, int target_item
     for (int b = 0; b < c->batch; ++b) {
       const int64_t len = last_tokens && t == c->n_tiers - 1 ? last_tokens[b] : c->tier[t].len[b];
       if (len == 0) continue;
-      runs[n_runs++] = RunShape{(int32_t)len, pt, (int32_t)std::max<int64_t>(1, len / 256)};
+      runs[n_runs++] = RunShape{(int32_t)len, pt, (int32_t)((len + 255) / 256)};
       S += len * pt;
     }
   }

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2604_19769_amd import binding as B
 from paper_2604_19769_amd import synth
 from ttkv_testlib import Pair, assert_close, dev
 
@@ -36,9 +37,18 @@ def tier_positions(lo, hi, chunk, bt):
     return sorted(lo + r for r in rel if 0 <= r < n)
 
 
+def finest_items(n_tokens):
+    """Tokens per work item of a run of n_tokens in HBM under the finest split (ttkv_set_split with a huge target):
+    ceil(n / 256) items of equal size, a multiple of 64 tokens."""
+    n = -(-n_tokens // 256)
+    return (-(-n_tokens // n) + 63) // 64 * 64
+
+
 def run_planted(p, B_, Hq, Hkv, dtype, lens, seed, chunks):
     """Load B_ sequences of lens[b] tokens whose keys at the listed positions point along one direction each, then
-    one attention call (no append, no eviction) per direction."""
+    one attention call (no append, no eviction) per direction.  The split is forced to its finest, so that the item
+    boundaries are known here: chunks[t] for a host tier (fixed items), finest_items for a run in HBM."""
+    B.ttkv_set_split(p.gpu.h, 1 << 20)
     g = synth.rng(seed)
     ks, vs = [], []
     for b in range(B_):
@@ -51,7 +61,8 @@ def run_planted(p, B_, Hq, Hkv, dtype, lens, seed, chunks):
         for t, spec in enumerate(p.tiers):
             take = rest if t == len(p.tiers) - 1 else min(rest, spec["capacity"] - 1 if t == 0 else spec["capacity"])
             if take:
-                P += tier_positions(hi - take, hi, chunks[t], spec["block_tokens"])
+                chunk = chunks[t] if spec.get("mem") == "host" else finest_items(take)
+                P += tier_positions(hi - take, hi, chunk, spec["block_tokens"])
             hi, rest = hi - take, rest - take
         pos.append(sorted(set(P)))
     n_dir = max(len(x) for x in pos)
