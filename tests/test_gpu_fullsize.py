@@ -10,7 +10,7 @@ import bench
 import oracle as O
 from oracle import OracleCache, TierSpec
 from paper_2604_19769_amd import synth
-from ttkv_testlib import assert_close
+from ttkv_testlib import assert_close, decode_i4c
 
 pytestmark = pytest.mark.gpu
 
@@ -20,6 +20,22 @@ def sample_oracle(cache_cfg, Hq, Hkv, heads, K, V, max_tokens):
     G = Hq // Hkv
     ora = OracleCache(1, G * len(heads), len(heads), 128, cache_cfg, max_tokens)
     ora.load(0, K[heads].float().cpu().numpy(), V[heads].float().cpu().numpy())
+    return ora
+
+
+def sample_oracle_sizes(cache_cfg, Hq, Hkv, heads, K, V, max_tokens, sizes_oldest_first):
+    """sample_oracle with the tiers' token counts given (oldest tier first) instead of filled by capacity."""
+    G = Hq // Hkv
+    ora = OracleCache(1, G * len(heads), len(heads), 128, cache_cfg, max_tokens)
+    k, v = K[heads].float().cpu().numpy(), V[heads].float().cpu().numpy()
+    lo = 0
+    for t, n in zip(reversed(range(len(cache_cfg))), sizes_oldest_first):
+        if n:
+            xk, xv = ora.through_formats(k[:, lo:lo + n], v[:, lo:lo + n], t)
+            ora.append(t, 0, xk, xv, lo)
+        lo += n
+    assert lo == k.shape[1]
+    ora.total[0] = lo
     return ora
 
 
@@ -44,7 +60,7 @@ def compare_codes(cache, ora, b, heads, fmts):
         assert int(cache.len[t][b]) == s.count and int(cache.start[t][b]) == s.first, (t, b)
         sl = slice(s.first, s.first + s.count)
         for name, fmt, hat, q in (("k", kf, s.khat, s.kq), ("v", vf, s.vhat, s.vq)):
-            got = d[name][heads]
+            got = (decode_i4c(d[name]) if fmt == "i4c" else d[name])[heads]   # channel-major values: the same codes, unpacked
             if fmt in ("f16", "bf16"):
                 assert np.array_equal(got.view(np.uint16), synth.to_bits(hat[:, sl], fmt)), (t, name)
             elif fmt == "i8":
@@ -166,20 +182,27 @@ def test_offload128k_full_size_sampled_heads():
         cache.close()
 
 
-def test_serving_ragged_full_size_sampled():
-    """The ragged serving benchmark configuration: batch 16, ragged contexts in [16K, 64K], paged 256-token blocks on every tier."""
+@pytest.mark.parametrize("last_mem", ["host", "device"])
+def test_serving_ragged_full_size_sampled(last_mem):
+    """The ragged serving benchmark configuration: batch 16, ragged contexts in [16K, 64K], paged 256-token blocks on every tier;
+    the int4 tier in pinned host memory, and (the bench's all-in-HBM variant) in HBM with its values channel-major."""
     steps = 2
-    cache, kv, (q, kn, vn), shape = bench.build_serving_ragged(steps)
+    cache, kv, (q, kn, vn), shape = bench.build_serving_ragged(steps, last_mem=last_mem)
+    last_fmt = ("i4", "i4c" if last_mem == "device" else "i4")
     try:
         heads, G = [0, 5], 4
         rows = q_rows(heads, G)
         ctx = shape["ctx"]
         picks = [int(np.argmin(ctx)), int(np.argmax(ctx))]           # shortest and longest sequence
-        tiers = [TierSpec("f16", "f16", 4096, 256), TierSpec("i8", "i8", 12288, 256), TierSpec("i4", "i4", 10**9, 256, mem="host")]
+        tiers = [TierSpec("f16", "f16", 4096, 256), TierSpec("i8", "i8", 12288, 256), TierSpec("i4", "i4", 10**9, 256, mem=last_mem)]
         oras = {}
         for b in picks:
-            oras[b] = sample_oracle(tiers, 32, 8, heads, kv[b][0], kv[b][1], [4096 + 512, 12288 + 1024, 65536])
-            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), ("i4", "i4")])
+            if last_mem == "device":     # the loader put whole groups of 32 tokens into the last tier: so does the oracle
+                sizes = [int(cache.len[t][b]) for t in (2, 1, 0)]
+                oras[b] = sample_oracle_sizes(tiers, 32, 8, heads, kv[b][0], kv[b][1], [4096 + 512, 12288 + 1024, 65536], sizes)
+            else:
+                oras[b] = sample_oracle(tiers, 32, 8, heads, kv[b][0], kv[b][1], [4096 + 512, 12288 + 1024, 65536])
+            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), last_fmt])
         for s in range(steps):
             out, lse = cache.step(q[s], kn[s], vn[s])
             torch.cuda.synchronize()
@@ -189,7 +212,7 @@ def test_serving_ragged_full_size_sampled():
                 assert_close(out[b, rows].cpu().numpy(), ro[0], f"out seq {b} step {s}")
                 assert_close(lse[b, rows].cpu().numpy(), rl[0], f"lse seq {b} step {s}")
         for b in picks:
-            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), ("i4", "i4")])
+            compare_codes(cache, oras[b], b, heads, [("f16", "f16"), ("i8", "i8"), last_fmt])
             total = sum(int(cache.len[t][b]) for t in range(3))
             assert total == int(ctx[b]) - 1 + steps
             for pos in (0, total // 3, total - 1):
