@@ -915,40 +915,53 @@ def run_grid(only=None):
 
 # ------------------------------------------------------------------ workload: block-sparse attention over a tier in HBM
 
-def run_sparse_hbm(steps=32, warmup=8):
-    """The sparse-recall layout with the old tier in HBM instead of pinned host memory (what 288 GB allow): batch 4,
-    32 q / 8 kv heads, 128K tokens = 4096 bf16 + 28672 int8 + 98304 int4 in blocks of 1024, 256 or 128 tokens; per step
-    block identification + top-k on the device, attention over the dense tiers and the selected blocks, append, evict.
-    Selecting 2/3 of the blocks (BASELINE's 64 of 96) and the paper's own B_blk = 128."""
+SPARSE_HBM_ROWS = ((1024, 64, ("i4", "i4")), (1024, 64, ("i4", "i4c")), (256, 256, ("i4", "i4")), (128, 512, ("i4", "i4")),
+                   (128, 64, ("i4", "i4")))     # block tokens, k, formats of the int4 tier
+
+
+def build_sparse_hbm(steps_total, bt, fmt, batch=4):
+    """The sparse-recall layout with the old tier in HBM: batch 4, 32 q / 8 kv heads, 128K tokens = 4096 bf16 + 28672 int8
+    + 98304 int4 in blocks of bt tokens with mean-key summaries."""
     import torch
     from paper_2604_19769_amd.cache import TierConfig, TieredCache
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(SEED + 11)
-    batch, Hq, Hkv, N, n_last = 4, 32, 8, 131072, 98304
+    Hq, Hkv, N, n_last = 32, 8, 131072, 98304
+    tiers = [TierConfig("bf16", "bf16", 4096, 128, 33), TierConfig("i8", "i8", 28672, 1024, 30),
+             TierConfig(fmt[0], fmt[1], 10**9, bt, n_last // bt + 1024 // bt + 3, summary=True)]
+    cache = TieredCache(batch, Hq, Hkv, tiers)
+    kv = []
+    for b in range(batch):
+        K = device_normal(gen, (Hkv, N - 1, 128), torch.bfloat16)
+        V = device_normal(gen, (Hkv, N - 1, 128), torch.bfloat16)
+        a, b2 = n_last, n_last + 28672
+        cache.append(2, K[:, :a].contiguous(), V[:, :a].contiguous(), seq=b, through_tiers=True)
+        cache.append(1, K[:, a:b2].contiguous(), V[:, a:b2].contiguous(), seq=b, through_tiers=True)
+        cache.append(0, K[:, b2:].contiguous(), V[:, b2:].contiguous(), seq=b)
+        kv.append((K, V))
+    q = device_normal(gen, (steps_total, batch, Hq, 128), torch.bfloat16)
+    kn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.bfloat16)
+    vn = device_normal(gen, (steps_total, batch, Hkv, 1, 128), torch.bfloat16)
+    torch.cuda.synchronize()
+    return cache, kv, (q, kn, vn), dict(B=batch, Hq=Hq, Hkv=Hkv, N=N, n_last=n_last)
+
+
+def run_sparse_hbm(steps=32, warmup=8):
+    """Block-sparse attention with the old tier in HBM instead of pinned host memory (what 288 GB allow); per step block
+    identification + top-k on the device, attention over the dense tiers and the selected blocks, append, evict.
+    Selecting 2/3 of the blocks (BASELINE's 64 of 96) in blocks of 1024, 256 and the paper's own B_blk = 128 tokens."""
+    import torch
     per = {"i4": 72, "i8": 136, "i4c": 72}
     rows = []
-    for bt, k, fmt in ((1024, 64, ("i4", "i4")), (1024, 64, ("i4", "i4c")), (256, 256, ("i4", "i4")), (128, 512, ("i4", "i4")),
-                       (128, 64, ("i4", "i4"))):
-        tiers = [TierConfig("bf16", "bf16", 4096, 128, 33), TierConfig("i8", "i8", 28672, 1024, 30),
-                 TierConfig(fmt[0], fmt[1], 10**9, bt, n_last // bt + 1024 // bt + 3, summary=True)]
-        cache = TieredCache(batch, Hq, Hkv, tiers)
-        for b in range(batch):
-            K = device_normal(gen, (Hkv, N - 1, 128), torch.bfloat16)
-            V = device_normal(gen, (Hkv, N - 1, 128), torch.bfloat16)
-            a, b2 = n_last, n_last + 28672
-            cache.append(2, K[:, :a].contiguous(), V[:, :a].contiguous(), seq=b, through_tiers=True)
-            cache.append(1, K[:, a:b2].contiguous(), V[:, a:b2].contiguous(), seq=b, through_tiers=True)
-            cache.append(0, K[:, b2:].contiguous(), V[:, b2:].contiguous(), seq=b)
-            del K, V
-        total = steps + warmup
-        q = device_normal(gen, (total, batch, Hq, 128), torch.bfloat16)
-        kn = device_normal(gen, (total, batch, Hkv, 1, 128), torch.bfloat16)
-        vn = device_normal(gen, (total, batch, Hkv, 1, 128), torch.bfloat16)
+    for bt, k, fmt in SPARSE_HBM_ROWS:
+        cache, kv, (q, kn, vn), shape = build_sparse_hbm(steps + warmup, bt, fmt)
+        del kv
+        batch, Hkv, n_last = shape["B"], shape["Hkv"], shape["n_last"]
         for s in range(warmup):
             cache.step(q[s], kn[s], vn[s], select_k=k)
         t0 = sync_time()
-        for s in range(warmup, total):
+        for s in range(warmup, steps + warmup):
             cache.step(q[s], kn[s], vn[s], select_k=k)
         dt = (sync_time() - t0) / steps
         attended = batch * Hkv * (4096 * 512 + 28672 * 272 + min(k, n_last // bt) * bt * (per[fmt[0]] + per[fmt[1]]))

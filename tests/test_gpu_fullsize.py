@@ -255,3 +255,29 @@ def test_sparse_recall_full_size_one_sequence():
             assert_close(lse[b].cpu().numpy(), rl[0], f"lse step {s}")
     finally:
         cache.close()
+
+
+@pytest.mark.parametrize("bt,k,fmt", [(128, 512, ("i4", "i4")), (1024, 64, ("i4", "i4c"))])
+def test_sparse_attention_over_a_tier_in_hbm_full_size_one_sequence(bt, k, fmt):
+    """bench.py's sparse_hbm rows at full size (batch 4, 128K tokens, every tier in HBM): identification, top-k (a thread
+    per block, 768 of them at 128-token blocks) and attention over the selected blocks as one run whose items span
+    blocks; the oracle recomputes one whole sequence: ids identical, outputs within tolerance."""
+    steps = 2
+    cache, kv, (q, kn, vn), shape = bench.build_sparse_hbm(steps, bt, fmt)
+    try:
+        b = 2
+        tiers = [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 1024), TierSpec("i4", "i4", 10**9, bt, summary=True)]
+        ora = OracleCache(1, 32, 8, 128, tiers, [4096 + 256, 28672 + 2048, 98304 + 4096])
+        ora.load(0, kv[b][0].float().cpu().numpy(), kv[b][1].float().cpu().numpy())
+        for s in range(steps):
+            out, lse = cache.step(q[s], kn[s], vn[s], select_k=k)
+            torch.cuda.synchronize()
+            ro, rl, rsel = ora.step(q[s, b][None].float().cpu().numpy(), kn[s, b, :, 0][None].float().cpu().numpy(),
+                                    vn[s, b, :, 0][None].float().cpu().numpy(), select_k=k)
+            got = cache.sel_blocks.numpy()[b, :int(cache.sel_count.numpy()[b])]
+            assert len(got) == k and np.array_equal(got, rsel[0]), (got, rsel[0])
+            assert_close(out[b].cpu().numpy(), ro[0], f"out step {s}")
+            assert_close(lse[b].cpu().numpy(), rl[0], f"lse step {s}")
+        assert cache.stats()["h2d_bytes"] == 0
+    finally:
+        cache.close()
