@@ -950,7 +950,7 @@ def build_sparse_hbm(steps_total, bt, fmt, batch=4):
 def run_sparse_hbm(steps=32, warmup=8):
     """Block-sparse attention with the old tier in HBM instead of pinned host memory (what 288 GB allow); per step block
     identification + top-k on the device, attention over the dense tiers and the selected blocks, append, evict.
-    Selecting 2/3 of the blocks (BASELINE's 64 of 96) in blocks of 1024, 256 and the paper's own B_blk = 128 tokens."""
+    Selecting 2/3 of the blocks (the sparse-recall benchmark's 64 of 96) in blocks of 1024, 256 and the paper's own B_blk = 128 tokens."""
     import torch
     per = {"i4": 72, "i8": 136, "i4c": 72}
     rows = []
