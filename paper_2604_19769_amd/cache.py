@@ -83,6 +83,7 @@ class TieredCache:
         self.demote_ws = None
         self._demote_need = None          # per tier: bytes of staging ttkv_tier_demote wants (constant for a cache)
         self._parts_age = None            # dense steps since the parts per row were last counted (None: never)
+        self._until_evict = 0             # steps until some sequence's tier 0 can have filled (0: ask the library)
         self.sel_blocks = self.sel_count = self.sel_scratch = None
         self.out = torch.empty(batch, n_q_heads, 128, dtype=torch.float32, device=self.device)
         self.lse = torch.empty(batch, n_q_heads, dtype=torch.float32, device=self.device)
@@ -116,6 +117,7 @@ class TieredCache:
         assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape and k.dtype == v.dtype
         n = k.shape[-2]
         self._parts_age = None            # lengths jump: count the parts again at the next step
+        self._until_evict = 0
         if self.cfg[tier].mem == "host" and self.host_append_direct:
             # no staging: the conversion kernels store into the pinned records
             B.ttkv_quantize_append_host(self.h, self.c, tier, seq, k, v, fmt, n, int(through_tiers), None, 0, self._compute())
@@ -228,11 +230,21 @@ class TieredCache:
                                 self._compute())
         return self.out, self.lse
 
+    def _evict_if_due(self, overlap):
+        """Alg. 1's eviction check after a step that appended one token per sequence.  A tier below the first only grows
+        when the one above evicts, so nothing can be due before some sequence's tier 0 has filled: until then the
+        library is not asked (every call validates the whole descriptor)."""
+        self._until_evict -= 1
+        if self._until_evict > 0:
+            return
+        self.demote(overlap)
+        self._until_evict = max(1, int((self.cfg[0].capacity - self.len[0]).min()))
+
     def step(self, q, k_new, v_new, select_k=None, overlap=True):
         """One decode step (Alg. 1): append -> [identify blocks] -> attend -> evict.  k_new, v_new [B][Hkv][1][128]."""
         if select_k is not None and self.device_topk and self.one_call_step and self.n_slots == 0:
             out, lse = self.step_topk(q, k_new, v_new, select_k)
-            self.demote(overlap)
+            self._evict_if_due(overlap)
             return out, lse
         if not self.one_call_step:
             self.append(0, k_new, v_new)
@@ -241,7 +253,7 @@ class TieredCache:
         else:
             sel = self.select(q, select_k) if select_k is not None else None
             out, lse = self.decode(q, sel, overlap, new=(k_new, v_new))
-        self.demote(overlap)
+        self._evict_if_due(overlap)
         return out, lse
 
     # ------------------------------------------------------------------ inspection (layout decoding only)
