@@ -59,6 +59,7 @@ extern "C" {
 
 #define TTKV_MAX_TIERS 4
 #define TTKV_MAX_BATCH 64
+#define TTKV_MAX_KV_HEADS 1023   /* n_kv_heads beyond this: TTKV_ERR_UNSUPPORTED */
 #define TTKV_HEAD_DIM 128
 #define TTKV_MAX_SLOTS 16
 #define TTKV_NOALLOC_SCRATCH_BYTES (16u << 20) /* split partials of ttkv_decode_attn_noalloc, per GPU */

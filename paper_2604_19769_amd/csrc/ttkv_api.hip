@@ -17,6 +17,7 @@ ttkv_status validate_cache(const ttkv_cache *c, bool check_tables) {
   if (c->head_dim != TTKV_HEAD_DIM) return TTKV_ERR_UNSUPPORTED;
   if (c->batch < 1 || c->batch > TTKV_MAX_BATCH) return TTKV_ERR_INVALID_ARG;
   if (c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return TTKV_ERR_INVALID_ARG;
+  if (c->n_kv_heads > TTKV_MAX_KV_HEADS) return TTKV_ERR_UNSUPPORTED;   // (sequence, KV head) pairs index a launch grid's third dimension
   if (c->n_tiers < 1 || c->n_tiers > TTKV_MAX_TIERS) return TTKV_ERR_INVALID_ARG;
   if (!(c->softmax_scale > 0.0f)) return TTKV_ERR_INVALID_ARG;
   for (int t = 0; t < c->n_tiers; ++t) {

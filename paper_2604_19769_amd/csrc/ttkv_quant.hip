@@ -27,6 +27,19 @@ __device__ __forceinline__ int wrap(int tok, const TierView &v) {
   return tok >= ring ? tok - ring : tok;
 }
 
+// rint(x / s) as the IEEE division followed by round-to-nearest-even gives it (the recipe of Sec. 4.2's quantizers,
+// one IEEE operation per step), wherever the caller's clamp to [-127, 127] or [0, 15] lets the difference show, for
+// a group's many x against one s: r = 1 / s is divided once; x * r is within 2^-22 |x / s| of the true quotient,
+// i.e. within 5e-5 for |x / s| < 200, so the two rounded integers agree unless the quotient lies within that
+// distance of a half-integer -- ties included -- and there the exact division decides (about one element in a
+// thousand takes it).  Beyond 200 either rounding is clamped to the same bound.
+__device__ __forceinline__ float quot_rint(float x, float s, float r) {
+  const float t = x * r;
+  float q = rintf(t);
+  if (fabsf(t - q) > 0.4995f) q = rintf(x / s);
+  return q;
+}
+
 // ---- in-register quantize / decompress over a group spread across `LANES`
 // consecutive lanes holding N values each.
 
@@ -41,10 +54,11 @@ __device__ __forceinline__ uint16_t q1_group(const float (&x)[N], int (&c)[N]) {
   float s32 = amax / 127.0f;
   uint16_t sh = f2h(s32);
   float s = h2f(sh);
+  const float r = s != 0.0f ? 1.0f / s : 0.0f;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     float q = 0.0f;
-    if (s != 0.0f) q = fminf(fmaxf(rintf(x[i] / s), -127.0f), 127.0f);
+    if (s != 0.0f) q = fminf(fmaxf(quot_rint(x[i], s, r), -127.0f), 127.0f);
     c[i] = (int)q;
   }
   return sh;
@@ -68,10 +82,11 @@ __device__ __forceinline__ void q2_group(const float (&x)[N], int (&c)[N], uint1
   float s32 = (hi - lo) / 15.0f;
   uint16_t sh = f2h(s32), zh = f2h(lo);
   float s = h2f(sh), z = h2f(zh);
+  const float r = s != 0.0f ? 1.0f / s : 0.0f;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     float q = 0.0f;
-    if (s != 0.0f) q = fminf(fmaxf(rintf((x[i] - z) / s), 0.0f), 15.0f);
+    if (s != 0.0f) q = fminf(fmaxf(quot_rint(x[i] - z, s, r), 0.0f), 15.0f);
     c[i] = (int)q;
   }
   *sh_out = sh;
@@ -189,17 +204,15 @@ __device__ __forceinline__ void store8_tier(uint8_t *head, int fmt, int code_off
 }
 
 // One 16-lane group converts one row (one token of one KV head); blockIdx.y
-// picks K (0) or V (1).
+// picks K (0) or V (1), blockIdx.z the (entry, KV head).
 __global__ __launch_bounds__(256) void convert_rows_kernel(const ConvArgs a) {
+  // grid: (16 tokens per workgroup, K / V, entry x KV head) -- no per-thread division of a 64-bit row number
   const int which = blockIdx.y + a.which0;
   const int l16 = threadIdx.x & 15;
-  const int64_t total = (int64_t)a.n_seq * a.Hkv * a.n_tokens;
-  int64_t row_id = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-  const bool live = row_id < total;
-  if (!live) row_id = total - 1;
-  const int t = (int)(row_id % a.n_tokens);
-  const int h = (int)((row_id / a.n_tokens) % a.Hkv);
-  const int j = (int)(row_id / ((int64_t)a.n_tokens * a.Hkv));
+  int t = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const bool live = t < a.n_tokens;
+  if (!live) t = a.n_tokens - 1;
+  const int j = blockIdx.z / a.Hkv, h = blockIdx.z - j * a.Hkv;
   const int seq = a.seq_id[j];
 
   float x[8];
@@ -300,6 +313,7 @@ __global__ __launch_bounds__(128) void convert_keys_t128_kernel(const ConvArgs a
   const float s32 = (hi - lo) / 15.0f;
   const uint16_t sh = f2h(s32), zh = f2h(lo);
   const float s = h2f(sh), z = h2f(zh);
+  const float r = s != 0.0f ? 1.0f / s : 0.0f;
   int row0;
   uint8_t *head = head_ptr(a.dst, seq, a.dst_rec_base[j], wrap(a.dst_first_tok[j] + g * 128, a.dst), h, &row0);
   // the group's 128 meta rows of 4 bytes hold {scale, zero} of the 128 channels
@@ -307,7 +321,7 @@ __global__ __launch_bounds__(128) void convert_keys_t128_kernel(const ConvArgs a
   for (int t = 0; t < 128; ++t) {
     const float x = arriving_key(a, j, seq, h, g * 128 + t, i);
     float q = 0.0f;
-    if (s != 0.0f) q = fminf(fmaxf(rintf((x - z) / s), 0.0f), 15.0f);
+    if (s != 0.0f) q = fminf(fmaxf(quot_rint(x - z, s, r), 0.0f), 15.0f);
     const int c = (int)q;
     const int other = __shfl_xor(c, 1);
     if (!(i & 1)) head[(row0 + t) * 64 + (i >> 1)] = (uint8_t)(c | (other << 4));
@@ -370,19 +384,19 @@ hipError_t launch_convert(const ConvArgs &a, hipStream_t s, int *n_kernels) {
     // values row by row, keys by groups of 128 tokens per channel (the caller has checked alignment)
     ConvArgs v = a;
     v.which0 = 1;
-    hipLaunchKernelGGL(convert_rows_kernel, dim3((unsigned)((total + 15) / 16), 1), dim3(256), 0, s, v);
+    hipLaunchKernelGGL(convert_rows_kernel, dim3((a.n_tokens + 15) / 16, 1, a.n_seq * a.Hkv), dim3(256), 0, s, v);
     hipLaunchKernelGGL(convert_keys_t128_kernel, dim3(a.n_tokens / 128, a.Hkv, a.n_seq), dim3(128), 0, s, a);
     *n_kernels += 2;
     return hipGetLastError();
   }
   if (a.dst.v_fmt == TTKV_I4_ASYM_G64_T32) {
     // keys row by row, values by groups of 32 tokens (the caller has checked alignment)
-    hipLaunchKernelGGL(convert_rows_kernel, dim3((unsigned)((total + 15) / 16), 1), dim3(256), 0, s, a);   // which0 = 0: K only
+    hipLaunchKernelGGL(convert_rows_kernel, dim3((a.n_tokens + 15) / 16, 1, a.n_seq * a.Hkv), dim3(256), 0, s, a);   // which0 = 0: K only
     hipLaunchKernelGGL(convert_values_t32_kernel, dim3(a.n_tokens / 32, a.Hkv, a.n_seq), dim3(256), 0, s, a);
     *n_kernels += 2;
     return hipGetLastError();
   }
-  dim3 grid((unsigned)((total + 15) / 16), 2);
+  dim3 grid((a.n_tokens + 15) / 16, 2, a.n_seq * a.Hkv);
   hipLaunchKernelGGL(convert_rows_kernel, grid, dim3(256), 0, s, a);
   ++*n_kernels;
   return hipGetLastError();
