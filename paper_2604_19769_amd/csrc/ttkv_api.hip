@@ -273,11 +273,10 @@ void build_plan(const ttkv_cache *c, const int32_t *sel_blocks, const int32_t *s
     const Layout L = make_layout(T, c->n_kv_heads);
     const bool sparse = sel_blocks && t == last;
     const bool host = T.mem == TTKV_MEM_HOST_PINNED;
-    // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured);
-    // staged slots and selected blocks of a device tier: 256-token items for parallelism
-    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : 0;   // 0: items of equal size per run
-    if (ds && t == last) P->chunk[t] = host ? 2048 : 256;
-    if (ds && t == last && !host) P->chunk[t] = 0;
+    // host rows read in place: few large sequential items keep the PCIe read stream efficient (measured); staged
+    // slots: 256-token items for parallelism; tiers in HBM, dense or selected on the device: equal items per run (0)
+    P->chunk[t] = (host && !staged) ? 2048 : (host || sparse) ? 256 : 0;
+    if (ds && t == last) P->chunk[t] = host ? 2048 : 0;
     if (!host && sparse && t == last) {
       // Blocks of a tier in HBM that the caller selected (ids on the host): one item per block once the selection
       // alone fills the chip, finer items, down to 256 tokens, when few blocks are selected.
