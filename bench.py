@@ -294,6 +294,46 @@ def build_offload128k(steps_total):
                                                     d2h_bytes=cache.stats()["d2h_bytes"])
 
 
+def offload128k_all_in_hbm(steps, warmup):
+    """The same 128K context and formats with the int4 tier in HBM as well (113 MB of 288 GB), its values stored
+    channel-major: microseconds per token and the time to tier the prompt when nothing crosses PCIe."""
+    import torch
+    from paper_2604_19769_amd.cache import TierConfig, TieredCache
+    B, Hq, Hkv, N = 1, 32, 8, 131072
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(SEED + 3)
+    tiers = [TierConfig("bf16", "bf16", 4096, 128, 33), TierConfig("i8", "i8", 28672, 128, 28672 // 128 + 2),
+             TierConfig("i4", "i4c", 10**9, 1024, 98304 // 1024 + 2)]
+    K = device_normal(gen, (B, Hkv, N - 1, 128), torch.bfloat16)
+    V = device_normal(gen, (B, Hkv, N - 1, 128), torch.bfloat16)
+    a, b = 98304, 98304 + 28672
+    parts = [(2, K[:, :, :a].contiguous(), V[:, :, :a].contiguous(), True), (1, K[:, :, a:b].contiguous(), V[:, :, a:b].contiguous(), True),
+             (0, K[:, :, b:].contiguous(), V[:, :, b:].contiguous(), False)]
+    tier_s = []
+    for rep in range(3):                     # the last build is the one that is kept
+        cache = TieredCache(B, Hq, Hkv, tiers)
+        t0 = sync_time()
+        for t, kk, vv, through in parts:
+            cache.append(t, kk, vv, through_tiers=through)
+        tier_s.append(sync_time() - t0)
+        if rep < 2:
+            cache.close()
+    try:
+        total_steps = steps + warmup
+        q = device_normal(gen, (total_steps, B, Hq, 128), torch.bfloat16)
+        kn = device_normal(gen, (total_steps, B, Hkv, 1, 128), torch.bfloat16)
+        vn = device_normal(gen, (total_steps, B, Hkv, 1, 128), torch.bfloat16)
+        settle(cache, q, 96)
+        timed_steps(cache, q, kn, vn, 0, warmup)
+        total, _ = algorithmic_bytes(cache)
+        t = timed_steps(cache, q, kn, vn, warmup, steps) / steps
+        return {"us_per_token": round(t * 1e6, 1), "bytes_per_step": int(total), "effective_kv_GBs": round(total / t / 1e9, 1),
+                "frac_of_hbm_peak": round(total / t / 1e9 / HBM_PEAK_GBS, 4), "prefill_tiering_ms": round(min(tier_s) * 1e3, 3)}
+    finally:
+        cache.close()
+
+
 # ------------------------------------------------------------------ workload: ragged paged serving batch
 
 def build_serving_ragged(steps_total, batch=16, last_mem="host"):
@@ -656,6 +696,7 @@ def run_offload128k(steps, warmup, cpu_baseline=True, staged_only=False):
             tiers = [TierSpec("bf16", "bf16", 4096, 128), TierSpec("i8", "i8", 28672, 128), TierSpec("i4", "i4", 10**9, 1024, mem="host")]
             cpu = oracle_sample(tiers, [4096 + 256, 28672 + 512, 98304 + 2048], 32, 8, [1, 6], [(0, kv[0][0], kv[1][0])], steps_in, 0,
                                 keep[0], "KV heads 1 and 6 of 8 (8 query heads), all 131072 tokens, the first decode step incl. append+evict")
+        hbm = offload128k_all_in_hbm(64, 8)
         roof = pcie_roofline(live, t_all, "attn_mfma_kernel<4>: device tiers + host records read in place, one launch")
         roof["frac_of_measured_link_peak"] = round(live / t_all / 1e9 / peak, 4)
         roof["measured_link_peak_GBs"] = round(peak, 2)
@@ -686,6 +727,7 @@ def run_offload128k(steps, warmup, cpu_baseline=True, staged_only=False):
             "prefill_tiering_tokens_per_s": round((shape["N"] - 1) / shape["tiering_s"], 0),
             "prefill_d2h_GBs": round(shape["d2h_bytes"] / shape["tiering_s"] / 1e9, 2),
             "prefill_tiering_staged_ms": round(shape["tiering_staged_s"] * 1e3, 2),
+            "same_cache_all_in_hbm": hbm,
         }
     finally:
         cache.close()
