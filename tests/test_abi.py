@@ -77,6 +77,10 @@ def test_invalid_arguments_are_status_codes():
     c.head_dim = 64
     assert L.ttkv_decode_attn(h, C.byref(c), dummy, B.F16, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_UNSUPPORTED
     c.head_dim = 128
+    # more KV heads than a launch grid's third dimension indexes together with the batch
+    c.n_q_heads, c.n_kv_heads = 1024, 1024
+    assert L.ttkv_decode_attn(h, C.byref(c), dummy, B.F16, dummy, None, None, None, 0, dummy, 1 << 20, 2, None, None) == B.ERR_UNSUPPORTED
+    c.n_q_heads, c.n_kv_heads = 8, 2
     # unsupported format pair (V wider than K)
     c.tier[1].k_fmt, c.tier[1].v_fmt = B.I4_ASYM_G64, B.I8_SYM_G32
     assert L.ttkv_count_parts(h, C.byref(c), None, None, 0, 0) == -1
