@@ -255,6 +255,20 @@ def test_selection_among_hundreds_of_small_blocks_in_hbm(Hq, Hkv, fmt, k):
                lens=[127 + 64 * 600, 127 + 64 * 690], peaked=True)
 
 
+@pytest.mark.parametrize("slow", [("i8", "i8"), ("i4", "i4c")])
+def test_many_sequences_with_the_item_size_chosen_per_call(slow):
+    """16 ragged sequences of a few thousand tokens, two tiers in HBM: more bytes than one round of workgroups takes in
+    256-token items and more runs than fit one item each into a round, so the split plan chooses an item size between
+    the two (equal items per run, a whole number of rounds) and re-fits it as the lengths grow and blocks are evicted;
+    outputs, lse and the stored state against the oracle over 140 steps."""
+    tiers = [dict(k_fmt="f16", v_fmt="f16", capacity=1024, block_tokens=128, ring_blocks=9),
+             dict(k_fmt=slow[0], v_fmt=slow[1], capacity=10**9, block_tokens=128, ring_blocks=80)]
+    lens = [1023 + 128 * n for n in (17, 40, 23, 31, 46, 19, 28, 35, 44, 21, 38, 26, 33, 48, 24, 42)]
+    st = run_config(16, 32, 8, tiers, "f16", None, 140, synth.SEED_BASE + 97, lens=lens, check_state_every=70, peaked=True,
+                    want_stats=True)
+    assert st["mfma_launches"] == 140 and st["demotions"] >= 16
+
+
 def test_bf16_query_on_fp16_and_quantized_tiers_and_large_batch():
     """bf16 queries over int8/int4 tiers with more (tier, sequence) runs than one launch table holds."""
     tiers = tiers3("bf16", host=False, bts=(64, 64, 64), caps=(128, 192), rings=(3, 5, 8))
